@@ -1,0 +1,180 @@
+/*
+ * CPU oracle for decode attention over a dynamic key/value range.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain statement of what
+ * the GPU library must compute.  It is used by the tests, by the smoke check
+ * and by the benchmark's CPU-baseline leg, and by nothing else.  It shares no
+ * code, layout, table or helper with the HIP path: keys and values live in
+ * flat [B][T][Hkv][D] arrays (no temporal blocks, no block table), every
+ * floating-point operation is fp64, and the loops follow the defining
+ * equation term by term.
+ *
+ * What it follows.  The paper's attention equation (Section 2, Eq. 1):
+ *     a_t = softmax(q_t . k_phi(t)^T * s) . v_phi(t)
+ * with the attention pattern phi(t) (same section):
+ *     causal:  phi(t) = 0 : t+1              (step t sees keys 0..t, itself included)
+ *     window:  phi(t) = max(t-w', 0) : t+1   (a backward window)
+ * Here `window` counts the visible keys, so lo = max(0, t-window+1); the
+ * paper's slice with window size w' is window = w'+1.  window = 0 selects the
+ * causal pattern.  Static tiling (Section 4.3) is an exact reformulation of
+ * the same result, so it does not appear in the attention routine; its integer
+ * bookkeeping (tile count ceil((t+1)/Z), tile n = [nZ, min((n+1)Z, t+1)),
+ * the padding of the last tile) is restated below with counting loops.
+ *
+ * Grouped-query attention is not described in the paper; query head h reads
+ * key/value head h div (Hq/Hkv) (contiguous groups).
+ *
+ * Every function here is pinned by tests that do not call it to produce their
+ * expected value (closed forms, a brute-force evaluator written differently,
+ * the padded+masked formulation, the paper's tiled three-reduction form, the
+ * paper's printed inverse-window example).  Nothing is "parity unpinned".
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* Is key j visible to the query of step t?  (Section 2: causal and window
+ * patterns; window = number of visible keys, 0 = causal.) */
+static int visible(int j, int t, int window) {
+  if (j < 0 || j > t) return 0;
+  if (window == 0) return 1;
+  return (t - j) < window;
+}
+
+/*
+ * Integer quantities of a step, by counting (Section 2 patterns; Section 4.3
+ * tiles of static size Z).  Outputs:
+ *   lo, hi            first and last visible key (hi == t)
+ *   first_tile        tile holding key lo        (tile of key j is j div Z)
+ *   last_tile         tile holding key t
+ *   n_tiles           number of tiles that exist at step t = ceil((t+1)/Z)
+ *   first_tile_skip   keys of first_tile that lie before lo (masked at the front)
+ *   last_tile_valid   keys of last_tile that exist at step t (the rest is padding)
+ * Returns 0, or -1 for t < 0, window < 0 or Z < 1.
+ */
+int tempo_oracle_visible_range(int t, int window, int Z, int* lo, int* hi,
+                               int* first_tile, int* last_tile, int* n_tiles,
+                               int* first_tile_skip, int* last_tile_valid) {
+  if (t < 0 || window < 0 || Z < 1) return -1;
+  int first = -1, last = -1;
+  for (int j = 0; j <= t; ++j) {
+    if (visible(j, t, window)) {
+      if (first < 0) first = j;
+      last = j;
+    }
+  }
+  /* Walk the keys in order, opening a new tile every Z keys. */
+  int tile = 0, slot = 0, tile_of_first = 0, tile_of_last = 0;
+  int skipped_in_first = 0, existing_in_last = 0;
+  for (int j = 0; j <= t; ++j) {
+    if (j == first) tile_of_first = tile;
+    if (j == last) tile_of_last = tile;
+    if (++slot == Z) { slot = 0; ++tile; }
+  }
+  tile = 0; slot = 0;
+  for (int j = 0; j <= t; ++j) {
+    if (tile == tile_of_first && j < first) ++skipped_in_first;
+    if (tile == tile_of_last) ++existing_in_last;
+    if (++slot == Z) { slot = 0; ++tile; }
+  }
+  int tiles = 0;
+  for (int j = 0; j <= t; j += Z) ++tiles;
+  *lo = first; *hi = last;
+  *first_tile = tile_of_first; *last_tile = tile_of_last; *n_tiles = tiles;
+  *first_tile_skip = skipped_in_first; *last_tile_valid = existing_in_last;
+  return 0;
+}
+
+/* Number of visible keys of step t that fall in tile n (Section 4.3: tile n
+ * spans keys [nZ, min((n+1)Z, t+1)); the window pattern further cuts its front). */
+int tempo_oracle_tile_visible_count(int t, int window, int Z, int n) {
+  if (t < 0 || window < 0 || Z < 1 || n < 0) return -1;
+  int count = 0;
+  for (int j = 0; j <= t; ++j) {
+    int tile = 0;
+    for (int k = Z; k <= j; k += Z) ++tile;
+    if (tile == n && visible(j, t, window)) ++count;
+  }
+  return count;
+}
+
+/* Where step t's key/value is written (block store, Section 6: one write per
+ * timestep into a pre-allocated block): tile t div Z, slot t mod Z, found by
+ * walking. */
+int tempo_oracle_append_slot(int t, int Z, int* tile, int* slot) {
+  if (t < 0 || Z < 1) return -1;
+  int n = 0, s = 0;
+  for (int j = 0; j < t; ++j) {
+    if (++s == Z) { s = 0; ++n; }
+  }
+  *tile = n; *slot = s;
+  return 0;
+}
+
+/*
+ * Eq. 1 for every sequence b and query head h, at that sequence's own step
+ * t[b].  All arrays are fp64, row-major:
+ *   q   [B][Hq][D]        query of step t[b]
+ *   K,V [B][T][Hkv][D]    keys/values of steps 0..T-1 (only 0..t[b] are read)
+ *   out [B][Hq][D]
+ * window: number of visible keys (0 = causal).  Returns 0, or -1 on a bad
+ * argument (Hq not a multiple of Hkv, t[b] outside [0,T), ...).
+ */
+int tempo_oracle_attend(const double* q, const double* K, const double* V,
+                        int B, int T, int Hq, int Hkv, int D,
+                        const int* t, int window, double scale, double* out) {
+  if (!q || !K || !V || !t || !out) return -1;
+  if (B < 1 || T < 1 || Hq < 1 || Hkv < 1 || D < 1 || window < 0) return -1;
+  if (Hq % Hkv != 0) return -1;
+  for (int b = 0; b < B; ++b)
+    if (t[b] < 0 || t[b] >= T) return -1;
+  const int group = Hq / Hkv;
+
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+  for (int b = 0; b < B; ++b) {
+    for (int h = 0; h < Hq; ++h) {
+      const int g = h / group;                 /* key/value head of query head h */
+      const int hi = t[b];
+      const int lo = (window == 0) ? 0 : (hi - window + 1 > 0 ? hi - window + 1 : 0);
+      const double* qv = q + ((size_t)b * Hq + h) * D;
+      double* ov = out + ((size_t)b * Hq + h) * D;
+
+      /* logits z_j = s * <q, k_j>, and their maximum */
+      double zmax = -INFINITY;
+      for (int j = lo; j <= hi; ++j) {
+        const double* kv = K + (((size_t)b * T + j) * Hkv + g) * D;
+        double z = 0.0;
+        for (int d = 0; d < D; ++d) z += qv[d] * kv[d];
+        z *= scale;
+        if (z > zmax) zmax = z;
+      }
+      /* softmax weights p_j = exp(z_j - zmax) / sum, applied to v_j */
+      double denom = 0.0;
+      for (int d = 0; d < D; ++d) ov[d] = 0.0;
+      for (int j = lo; j <= hi; ++j) {
+        const double* kv = K + (((size_t)b * T + j) * Hkv + g) * D;
+        const double* vv = V + (((size_t)b * T + j) * Hkv + g) * D;
+        double z = 0.0;
+        for (int d = 0; d < D; ++d) z += qv[d] * kv[d];
+        z *= scale;
+        const double p = exp(z - zmax);
+        denom += p;
+        for (int d = 0; d < D; ++d) ov[d] += p * vv[d];
+      }
+      for (int d = 0; d < D; ++d) ov[d] /= denom;
+    }
+  }
+  return 0;
+}
+
+/* Threads the attention routine will use (for reporting beside a timing). */
+int tempo_oracle_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
