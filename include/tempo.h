@@ -1,0 +1,220 @@
+/*
+ * tempo.h -- C ABI of the decode-attention library for MI355X (gfx950).
+ *
+ * One hot path, from the Tempo paper's dynamic-tensor method: at decode step t
+ * the query q_t attends over a key/value tensor whose temporal extent depends
+ * on t (Section 2, Eq. 1):
+ *
+ *     a_t = softmax(q_t . k_phi(t)^T * s) . v_phi(t)
+ *     causal:  phi(t) = 0 : t+1                 keys 0..t, key t included
+ *     window:  phi(t) = max(t-w', 0) : t+1      a backward window
+ *
+ * Keys and values are kept as temporal tiles of a static size Z (Section 4.3,
+ * "static tiling": ceil((t+1)/Z) tiles, tile n = keys [nZ, min((n+1)Z, t+1)),
+ * the unfilled tail of the last tile masked), held in pre-allocated blocks that
+ * are written in place one timestep at a time (Section 6, "block store" and the
+ * "in-place writes" kernel wrapper).  A block table maps a sequence's logical
+ * tile n to a physical block of a shared pool.
+ *
+ * Conventions
+ *  - `window` is the NUMBER OF VISIBLE KEYS: lo = max(0, t-window+1), hi = t.
+ *    The paper's slice with window size w' is window = w'+1.
+ *  - Grouped-query attention: query head h reads key/value head
+ *    h div (num_q_heads / num_kv_heads).
+ *  - Order: step t's key/value must be appended before step t attends.
+ *  - Pointers marked "device" are HIP device pointers; `stream` is a
+ *    hipStream_t passed as void* (NULL = the default stream).  Everything else
+ *    is host memory.  The caller owns every buffer.  The library allocates
+ *    nothing, never synchronises, keeps no state between calls, and every
+ *    launch is asynchronous on `stream`; calls may be captured in a HIP graph.
+ *  - `out` must not alias q, the pools or the workspace.
+ *  - Results are deterministic: same inputs and same arguments, same bits.
+ *  - Every entry point validates its arguments on the host and returns a
+ *    negative tempo_status before launching anything if they are bad.  Block
+ *    ids read from the table on the device are clamped into [0, num_blocks),
+ *    so a corrupt table gives wrong numbers, not a memory fault.
+ *  - The result never depends on pool contents outside the visible range:
+ *    masking is by index (the paper's -inf mask under max, 0 mask under sums).
+ *
+ * Supported shapes: head_dim in {64, 128}; block_size a power of two, >= 32
+ * for bf16 and >= 4 for f32; num_q_heads a multiple of num_kv_heads with a
+ * group of at most 16 query heads per key/value head.
+ */
+#ifndef TEMPO_H
+#define TEMPO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { TEMPO_BF16 = 0, TEMPO_F32 = 1 } tempo_dtype;
+
+typedef enum {
+  TEMPO_OK = 0,
+  TEMPO_ERR_NULL = -1,      /* a required pointer is NULL */
+  TEMPO_ERR_SHAPE = -2,     /* unsupported head_dim / block_size / head counts / batch */
+  TEMPO_ERR_RANGE = -3,     /* t < 0, window < 1, or step t does not fit max_blocks_per_seq */
+  TEMPO_ERR_WORKSPACE = -4, /* workspace NULL, misaligned or too small */
+  TEMPO_ERR_DTYPE = -5,     /* dtype is not a tempo_dtype */
+  TEMPO_ERR_LAUNCH = -6     /* the HIP runtime refused a launch */
+} tempo_status;
+
+/*
+ * The block store.  k_pool and v_pool each hold
+ * num_blocks * num_kv_heads * block_size * head_dim elements of `dtype`.
+ * Within the pool, the elements of one (block, kv head) pair are contiguous
+ * (block_size*head_dim of them); their order inside that tile depends on dtype
+ * and is defined by tempo_kv_element_offset():
+ *
+ *   TEMPO_F32   row-major [slot][d].
+ *   TEMPO_BF16  "operand-major": the tile is cut into groups of 32 consecutive
+ *               slots, and inside a group the 16-byte units are ordered so that
+ *               a 64-lane wavefront loading consecutive units receives exactly
+ *               the register image of a 16x16x32 bf16 MFMA operand (K: 16 slots
+ *               x 32 dims per unit group; V: 32 slots x 16 dims).  A decode step
+ *               therefore streams K and V with contiguous 1 KiB loads and no
+ *               transposition; the price is paid once per token at append time.
+ *
+ * The pools are opaque to the caller: write them with tempo_kv_append, read
+ * them back with tempo_kv_gather.  Slots that were never appended may hold
+ * anything (NaN included).
+ */
+typedef struct tempo_kv {
+  void* k_pool;               /* device */
+  void* v_pool;               /* device */
+  const int32_t* block_table; /* device; [batch][max_blocks_per_seq]; tile n -> physical block */
+  int32_t num_blocks;
+  int32_t max_blocks_per_seq;
+  int32_t block_size;         /* Z, the static tile size of Section 4.3 */
+  int32_t num_kv_heads;       /* Hkv */
+  int32_t head_dim;           /* D */
+  int32_t dtype;              /* tempo_dtype of pools, q, k_new, v_new and out */
+} tempo_kv;
+
+/* How a step's visible range is cut into independent partial-attention work
+ * items ("splits"), each a run of tokens_per_split consecutive key positions
+ * aligned to a multiple of tokens_per_split; one workgroup of `waves` 64-lane
+ * wavefronts handles the query group of one (sequence, kv head, split). */
+typedef struct tempo_plan {
+  int32_t tokens_per_split;   /* power of two, >= 32 */
+  int32_t num_splits;         /* splits launched per (sequence, kv head) for the longest range */
+  int32_t waves;              /* 1, 2, 4 or 8 */
+} tempo_plan;
+
+/* ---- pure host functions (no GPU needed) -------------------------------- */
+
+/*
+ * Integer quantities of step t (Section 2 patterns, Section 4.3 tiles).
+ * window = 0 selects the causal pattern.  Writes: lo, hi (first/last visible
+ * key, hi = t); first_tile = lo div Z and last_tile = t div Z; first_tile_skip
+ * = keys of first_tile before lo; last_tile_valid = (t mod Z)+1 keys of the
+ * last tile that exist (the rest is the padding Section 4.3 masks).  Any output
+ * pointer may be NULL.  Returns TEMPO_ERR_RANGE for t < 0, window < 0, Z < 1.
+ */
+int tempo_visible_range(int32_t t, int32_t window, int32_t Z, int32_t* lo, int32_t* hi,
+                        int32_t* first_tile, int32_t* last_tile, int32_t* first_tile_skip,
+                        int32_t* last_tile_valid);
+
+/* Where step t is written (block store, Section 6): tile = t div Z, slot = t mod Z. */
+int tempo_append_slot(int32_t t, int32_t Z, int32_t* tile, int32_t* slot);
+
+/*
+ * Element offset, from the start of k_pool (which = 0) or v_pool (which = 1),
+ * of dimension d of slot `slot` of kv head `head` of physical block `block`.
+ * Only the layout fields of kv are read.  Returns -1 for arguments out of range.
+ */
+int64_t tempo_kv_element_offset(const tempo_kv* kv, int32_t which, int32_t block, int32_t head,
+                                int32_t slot, int32_t d);
+
+/* Bytes of one pool (k_pool or v_pool); 0 if the layout fields are invalid. */
+size_t tempo_kv_pool_bytes(const tempo_kv* kv);
+
+/*
+ * The split plan the attention entry points use for a batch whose longest
+ * step is t_max (window = 0: causal).  Deterministic function of its arguments.
+ */
+int tempo_attn_plan(const tempo_kv* kv, int32_t batch, int32_t num_q_heads, int32_t t_max,
+                    int32_t window, tempo_plan* plan);
+
+/*
+ * Workspace bytes that tempo_attn_decode_causal / _window need for any step
+ * t <= max_t of `batch` sequences (partials: running max, running sum and
+ * fp32 accumulator per (sequence, query head, split)).  0 on invalid arguments.
+ */
+size_t tempo_attn_workspace_bytes(const tempo_kv* kv, int32_t batch, int32_t num_q_heads,
+                                  int32_t max_t);
+
+const char* tempo_strerror(int status);
+
+/* ---- device entry points ------------------------------------------------ */
+
+/*
+ * Block-store write of one timestep (Section 6): k_new, v_new (device,
+ * [batch][Hkv][D] of dtype) go to physical block block_table[b][t div Z], slot
+ * t mod Z.  If t_per_seq (device, [batch]) is not NULL each sequence b is
+ * written at its own step t_per_seq[b], and t must be an upper bound of those
+ * steps (it is only used for validation).
+ */
+int tempo_kv_append(const tempo_kv* kv, const void* k_new, const void* v_new, int32_t batch,
+                    int32_t t, const int32_t* t_per_seq, void* stream);
+
+/*
+ * Read keys/values of steps j0 .. j0+count-1 of every sequence back out of the
+ * block store into flat arrays k_out, v_out (device, [batch][count][Hkv][D] of
+ * dtype; either may be NULL).  The "slice read" of the block store; used by
+ * tests and for inspection, not by the decode path.
+ */
+int tempo_kv_gather(const tempo_kv* kv, void* k_out, void* v_out, int32_t batch, int32_t j0,
+                    int32_t count, void* stream);
+
+/*
+ * Eq. 1 with the causal pattern: out[b][h][:] (device, [batch][Hq][D] of dtype)
+ * = attention of q[b][h][:] (device, same shape) over keys/values 0..t of
+ * sequence b.  If t_per_seq (device, [batch]) is not NULL, sequence b is at step
+ * t_per_seq[b] and t must be an upper bound of those steps (it fixes the launch
+ * geometry).  scale is the constant s of Eq. 1.  workspace: device, 256-byte
+ * aligned, at least tempo_attn_workspace_bytes(kv, batch, num_q_heads, t) bytes.
+ * Launches: partial attention per split, then the split combine.
+ */
+int tempo_attn_decode_causal(const tempo_kv* kv, const void* q, void* out, int32_t batch,
+                             int32_t num_q_heads, int32_t t, const int32_t* t_per_seq,
+                             float scale, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Same with the window pattern: keys max(0, t-window+1) .. t; window >= 1. */
+int tempo_attn_decode_window(const tempo_kv* kv, const void* q, void* out, int32_t batch,
+                             int32_t num_q_heads, int32_t t, const int32_t* t_per_seq,
+                             int32_t window, float scale, void* workspace,
+                             size_t workspace_bytes, void* stream);
+
+/*
+ * The two launches of the attention entry points, separately, with an explicit
+ * plan (for profiling one kernel at a time and for sweeping plans).  window = 0
+ * is causal.  tempo_attn_decode_partial writes one (max, sum, accumulator)
+ * partial per (sequence, query head, non-empty split) into workspace
+ * (Section 4.3: per-tile reductions under -inf / 0 masks);
+ * tempo_attn_decode_combine sums the partials into out (Section 4.3: "sums
+ * together each masked attention tile").  plan->num_splits must cover the range
+ * of step t, at least (t div tps) - (lo div tps) + 1 splits, and with t_per_seq
+ * the range of any step up to t (what tempo_attn_plan returns).
+ */
+int tempo_attn_decode_partial(const tempo_kv* kv, const void* q, int32_t batch,
+                              int32_t num_q_heads, int32_t t, const int32_t* t_per_seq,
+                              int32_t window, float scale, const tempo_plan* plan,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
+int tempo_attn_decode_combine(const tempo_kv* kv, void* out, int32_t batch, int32_t num_q_heads,
+                              int32_t t, const int32_t* t_per_seq, int32_t window,
+                              const tempo_plan* plan, const void* workspace,
+                              size_t workspace_bytes, void* stream);
+
+/* Workspace bytes for an explicit plan. */
+size_t tempo_attn_plan_workspace_bytes(const tempo_kv* kv, int32_t batch, int32_t num_q_heads,
+                                       const tempo_plan* plan);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TEMPO_H */

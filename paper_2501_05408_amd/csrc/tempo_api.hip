@@ -1,0 +1,367 @@
+// The C ABI declared in tempo.h: argument validation, split planning, launches.
+// Host code only; every step of the path runs in the kernels this file launches.
+#include <math.h>
+#include <stdio.h>
+
+#include "tempo_internal.h"
+
+namespace {
+
+using namespace tempo;
+
+int ilog2_exact(int32_t v) {  // log2 of a power of two, else -1
+  if (v <= 0 || (v & (v - 1)) != 0) return -1;
+  int k = 0;
+  while ((1 << k) < v) ++k;
+  return k;
+}
+
+// Layout fields only (no pointers): dtype, head_dim, block_size, heads, counts.
+int check_layout(const tempo_kv* kv) {
+  if (!kv) return TEMPO_ERR_NULL;
+  if (kv->dtype != TEMPO_BF16 && kv->dtype != TEMPO_F32) return TEMPO_ERR_DTYPE;
+  if (kv->head_dim != 64 && kv->head_dim != 128) return TEMPO_ERR_SHAPE;
+  const int zl = ilog2_exact(kv->block_size);
+  if (zl < 0) return TEMPO_ERR_SHAPE;
+  if (kv->dtype == TEMPO_BF16 && kv->block_size < 32) return TEMPO_ERR_SHAPE;
+  if (kv->dtype == TEMPO_F32 && kv->block_size < 4) return TEMPO_ERR_SHAPE;
+  if (kv->num_kv_heads < 1 || kv->num_kv_heads > 65535) return TEMPO_ERR_SHAPE;
+  if (kv->num_blocks < 1 || kv->max_blocks_per_seq < 1) return TEMPO_ERR_SHAPE;
+  return TEMPO_OK;
+}
+
+int check_store(const tempo_kv* kv) {
+  const int rc = check_layout(kv);
+  if (rc != TEMPO_OK) return rc;
+  if (!kv->k_pool || !kv->v_pool || !kv->block_table) return TEMPO_ERR_NULL;
+  return TEMPO_OK;
+}
+
+int check_heads(const tempo_kv* kv, int32_t batch, int32_t Hq) {
+  if (batch < 1 || batch > 65535) return TEMPO_ERR_SHAPE;
+  if (Hq < 1 || Hq % kv->num_kv_heads != 0) return TEMPO_ERR_SHAPE;
+  if (Hq / kv->num_kv_heads > 16 || Hq > 65535) return TEMPO_ERR_SHAPE;
+  return TEMPO_OK;
+}
+
+int check_step(const tempo_kv* kv, int32_t t) {
+  if (t < 0) return TEMPO_ERR_RANGE;
+  if (t / kv->block_size >= kv->max_blocks_per_seq) return TEMPO_ERR_RANGE;
+  return TEMPO_OK;
+}
+
+// Upper bound of the number of splits any step t' <= t can need with this tps.
+int32_t splits_bound(int32_t t, int32_t window, int tps_log2) {
+  const int32_t causal = (t >> tps_log2) + 1;
+  if (window <= 0) return causal;
+  // a run of `window` keys starting anywhere touches at most ceil((window-1)/tps)+1 chunks
+  const int32_t tps = 1 << tps_log2;
+  const int32_t win = (window <= 1) ? 1 : (int32_t)(((int64_t)window - 2 + tps) >> tps_log2) + 1;
+  return causal < win ? causal : win;
+}
+
+// Work items wanted before a split is made shorter: 4 workgroups per compute unit.
+constexpr int kTargetItems = 1024;
+constexpr int kMaxSplits = 1024;
+
+void make_plan(const tempo_kv* kv, int32_t batch, int32_t Hq, int32_t t_max, int32_t window,
+               tempo_plan* plan) {
+  // bf16 shares one key/value read across the query group; fp32 launches per query head.
+  const int64_t pairs = (int64_t)batch * (kv->dtype == TEMPO_BF16 ? kv->num_kv_heads : Hq);
+  int tps_log2 = 8;
+  while (tps_log2 > 5 && pairs * splits_bound(t_max, window, tps_log2) < kTargetItems) --tps_log2;
+  while (splits_bound(t_max, window, tps_log2) > kMaxSplits) ++tps_log2;
+  plan->tokens_per_split = 1 << tps_log2;
+  plan->num_splits = splits_bound(t_max, window, tps_log2);
+  const int groups = plan->tokens_per_split / 32;
+  plan->waves = groups >= 4 ? 4 : groups;
+}
+
+// A uniform step needs its own split count; ragged steps (any t' <= t) need the bound.
+int check_plan(const tempo_plan* plan, int32_t t, int32_t window, bool ragged) {
+  if (!plan) return TEMPO_ERR_NULL;
+  const int k = ilog2_exact(plan->tokens_per_split);
+  if (k < 5) return TEMPO_ERR_SHAPE;
+  if (plan->waves != 1 && plan->waves != 2 && plan->waves != 4 && plan->waves != 8) return TEMPO_ERR_SHAPE;
+  if (plan->num_splits < 1 || plan->num_splits > 65535) return TEMPO_ERR_SHAPE;
+  const int32_t need = ragged ? splits_bound(t, window, k) : seq_range(t, window, k).nchunks;
+  if (plan->num_splits < need) return TEMPO_ERR_RANGE;
+  return TEMPO_OK;
+}
+
+// Map a launch status to the ABI's; say on stderr what the runtime said.
+int launch_status(hipError_t e, const char* what) {
+  if (e == hipSuccess) return TEMPO_OK;
+  fprintf(stderr, "libtempo: launch of %s failed: %s\n", what, hipGetErrorString(e));
+  return TEMPO_ERR_LAUNCH;
+}
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+size_t ml_bytes(int32_t batch, int32_t Hq, int32_t S) {
+  return align_up((size_t)batch * Hq * S * 2 * sizeof(float), 256);
+}
+
+size_t plan_bytes(const tempo_kv* kv, int32_t batch, int32_t Hq, int32_t S) {
+  return ml_bytes(batch, Hq, S) + align_up((size_t)batch * Hq * S * kv->head_dim * sizeof(float), 256);
+}
+
+AttnParams attn_params(const tempo_kv* kv, const void* q, void* out, int32_t Hq, int32_t t,
+                       const int32_t* t_per_seq, int32_t window, float scale,
+                       const tempo_plan* plan, void* workspace, int32_t batch) {
+  AttnParams p;
+  p.k_pool = kv->k_pool;
+  p.v_pool = kv->v_pool;
+  p.block_table = kv->block_table;
+  p.q = q;
+  p.t_per_seq = t_per_seq;
+  p.ws_ml = static_cast<float*>(workspace);
+  p.ws_acc = reinterpret_cast<float*>(static_cast<char*>(workspace) + ml_bytes(batch, Hq, plan->num_splits));
+  p.out = out;
+  p.t = t;
+  p.window = window;
+  p.z_log2 = ilog2_exact(kv->block_size);
+  p.max_blocks_per_seq = kv->max_blocks_per_seq;
+  p.num_blocks = kv->num_blocks;
+  p.Hkv = kv->num_kv_heads;
+  p.Hq = Hq;
+  p.G = Hq / kv->num_kv_heads;
+  p.tps_log2 = ilog2_exact(plan->tokens_per_split);
+  p.num_splits = plan->num_splits;
+  p.direct = 0;
+  p.scale_log2e = scale * 1.44269504088896340736f;
+  return p;
+}
+
+StoreParams store_params(const tempo_kv* kv, int32_t batch, int32_t t, const int32_t* t_per_seq) {
+  StoreParams p;
+  p.k_pool = kv->k_pool;
+  p.v_pool = kv->v_pool;
+  p.block_table = kv->block_table;
+  p.t_per_seq = t_per_seq;
+  p.t = t;
+  p.z_log2 = ilog2_exact(kv->block_size);
+  p.max_blocks_per_seq = kv->max_blocks_per_seq;
+  p.num_blocks = kv->num_blocks;
+  p.Hkv = kv->num_kv_heads;
+  p.batch = batch;
+  return p;
+}
+
+// Splits to launch along grid.x: exact for a uniform step, the bound for ragged steps.
+int32_t grid_splits(const tempo_plan* plan, int32_t t, const int32_t* t_per_seq, int32_t window) {
+  if (t_per_seq) return plan->num_splits;
+  const int32_t exact = seq_range(t, window, ilog2_exact(plan->tokens_per_split)).nchunks;
+  return exact < plan->num_splits ? exact : plan->num_splits;
+}
+
+int check_attn(const tempo_kv* kv, int32_t batch, int32_t Hq, int32_t t, int32_t window, bool ragged,
+               const tempo_plan* plan, const void* workspace, size_t workspace_bytes) {
+  int rc = check_store(kv);
+  if (rc != TEMPO_OK) return rc;
+  if ((rc = check_heads(kv, batch, Hq)) != TEMPO_OK) return rc;
+  if (window < 0) return TEMPO_ERR_RANGE;
+  if ((rc = check_step(kv, t)) != TEMPO_OK) return rc;
+  if ((rc = check_plan(plan, t, window, ragged)) != TEMPO_OK) return rc;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return TEMPO_ERR_WORKSPACE;
+  if (workspace_bytes < plan_bytes(kv, batch, Hq, plan->num_splits)) return TEMPO_ERR_WORKSPACE;
+  return TEMPO_OK;
+}
+
+int do_partial(const tempo_kv* kv, const void* q, void* out_if_direct, int32_t batch, int32_t Hq,
+               int32_t t, const int32_t* t_per_seq, int32_t window, float scale,
+               const tempo_plan* plan, void* workspace, hipStream_t stream) {
+  AttnParams p = attn_params(kv, q, out_if_direct, Hq, t, t_per_seq, window, scale, plan, workspace, batch);
+  p.direct = (out_if_direct != nullptr && plan->num_splits == 1) ? 1 : 0;
+  const int32_t gs = grid_splits(plan, t, t_per_seq, window);
+  const hipError_t e = kv->dtype == TEMPO_BF16
+                           ? launch_partial_bf16(p, batch, kv->head_dim, gs, plan->waves, stream)
+                           : launch_partial_f32(p, batch, kv->head_dim, gs, plan->waves, stream);
+  return launch_status(e, "attn_decode_partial");
+}
+
+int do_combine(const tempo_kv* kv, void* out, int32_t batch, int32_t Hq, int32_t t,
+               const int32_t* t_per_seq, int32_t window, const tempo_plan* plan, void* workspace,
+               hipStream_t stream) {
+  AttnParams p = attn_params(kv, nullptr, out, Hq, t, t_per_seq, window, 1.0f, plan, workspace, batch);
+  const hipError_t e = launch_combine(p, batch, kv->head_dim, kv->dtype, stream);
+  return launch_status(e, "attn_decode_combine");
+}
+
+int decode(const tempo_kv* kv, const void* q, void* out, int32_t batch, int32_t Hq, int32_t t,
+           const int32_t* t_per_seq, int32_t window, float scale, void* workspace,
+           size_t workspace_bytes, void* stream) {
+  int rc = check_layout(kv);
+  if (rc != TEMPO_OK) return rc;
+  if (!q || !out) return TEMPO_ERR_NULL;
+  if ((rc = check_heads(kv, batch, Hq)) != TEMPO_OK) return rc;
+  if (t < 0 || window < 0) return TEMPO_ERR_RANGE;
+  tempo_plan plan;
+  make_plan(kv, batch, Hq, t, window, &plan);
+  if ((rc = check_attn(kv, batch, Hq, t, window, t_per_seq != nullptr, &plan, workspace, workspace_bytes)) != TEMPO_OK) return rc;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  rc = do_partial(kv, q, out, batch, Hq, t, t_per_seq, window, scale, &plan, workspace, s);
+  if (rc != TEMPO_OK || plan.num_splits == 1) return rc;  // a single split wrote `out` itself
+  return do_combine(kv, out, batch, Hq, t, t_per_seq, window, &plan, workspace, s);
+}
+
+}  // namespace
+
+extern "C" {
+
+int tempo_visible_range(int32_t t, int32_t window, int32_t Z, int32_t* lo, int32_t* hi,
+                        int32_t* first_tile, int32_t* last_tile, int32_t* first_tile_skip,
+                        int32_t* last_tile_valid) {
+  if (t < 0 || window < 0 || Z < 1) return TEMPO_ERR_RANGE;
+  const int32_t l = (window > 0 && t - window + 1 > 0) ? t - window + 1 : 0;
+  if (lo) *lo = l;
+  if (hi) *hi = t;
+  if (first_tile) *first_tile = l / Z;
+  if (last_tile) *last_tile = t / Z;
+  if (first_tile_skip) *first_tile_skip = l % Z;
+  if (last_tile_valid) *last_tile_valid = t % Z + 1;
+  return TEMPO_OK;
+}
+
+int tempo_append_slot(int32_t t, int32_t Z, int32_t* tile, int32_t* slot) {
+  if (t < 0 || Z < 1) return TEMPO_ERR_RANGE;
+  if (tile) *tile = t / Z;
+  if (slot) *slot = t % Z;
+  return TEMPO_OK;
+}
+
+int64_t tempo_kv_element_offset(const tempo_kv* kv, int32_t which, int32_t block, int32_t head,
+                                int32_t slot, int32_t d) {
+  if (check_layout(kv) != TEMPO_OK) return -1;
+  if (which < 0 || which > 1 || block < 0 || block >= kv->num_blocks || head < 0 ||
+      head >= kv->num_kv_heads || slot < 0 || slot >= kv->block_size || d < 0 || d >= kv->head_dim)
+    return -1;
+  const int D = kv->head_dim;
+  const int64_t base = ((int64_t)block * kv->num_kv_heads + head) * kv->block_size * D;
+  if (kv->dtype == TEMPO_F32) return base + tile_off_f32(D, slot, d);
+  return base + (which == 0 ? tile_off_k_bf16(D, slot, d) : tile_off_v_bf16(D, slot, d));
+}
+
+size_t tempo_kv_pool_bytes(const tempo_kv* kv) {
+  if (check_layout(kv) != TEMPO_OK) return 0;
+  const size_t e = kv->dtype == TEMPO_BF16 ? 2 : 4;
+  return (size_t)kv->num_blocks * kv->num_kv_heads * kv->block_size * kv->head_dim * e;
+}
+
+int tempo_attn_plan(const tempo_kv* kv, int32_t batch, int32_t num_q_heads, int32_t t_max,
+                    int32_t window, tempo_plan* plan) {
+  int rc = check_layout(kv);
+  if (rc != TEMPO_OK) return rc;
+  if (!plan) return TEMPO_ERR_NULL;
+  if ((rc = check_heads(kv, batch, num_q_heads)) != TEMPO_OK) return rc;
+  if (t_max < 0 || window < 0) return TEMPO_ERR_RANGE;
+  make_plan(kv, batch, num_q_heads, t_max, window, plan);
+  return TEMPO_OK;
+}
+
+size_t tempo_attn_plan_workspace_bytes(const tempo_kv* kv, int32_t batch, int32_t num_q_heads,
+                                       const tempo_plan* plan) {
+  if (check_layout(kv) != TEMPO_OK || !plan) return 0;
+  if (check_heads(kv, batch, num_q_heads) != TEMPO_OK || plan->num_splits < 1) return 0;
+  return plan_bytes(kv, batch, num_q_heads, plan->num_splits);
+}
+
+size_t tempo_attn_workspace_bytes(const tempo_kv* kv, int32_t batch, int32_t num_q_heads,
+                                  int32_t max_t) {
+  if (check_layout(kv) != TEMPO_OK || max_t < 0) return 0;
+  if (check_heads(kv, batch, num_q_heads) != TEMPO_OK) return 0;
+  // The planner's split count is not monotone in t (short ranges use shorter
+  // splits), so bound it over every step t' <= max_t and every window:
+  //  - with the default split length (2^8) or a longer one, the count is at most
+  //    min(splits(max_t, 2^8), kMaxSplits);
+  //  - a shorter length 2^k is only chosen while pairs * splits(t', 2^(k+1)) is
+  //    below the target, and halving the length at most doubles the count, so the
+  //    count is below 2 * ceil(target / pairs), and never above splits(max_t, 2^5).
+  const int64_t pairs = (int64_t)batch * (kv->dtype == TEMPO_BF16 ? kv->num_kv_heads : num_q_heads);
+  int64_t long_case = splits_bound(max_t, 0, 8);
+  if (long_case > kMaxSplits) long_case = kMaxSplits;
+  int64_t short_case = 2 * ((kTargetItems + pairs - 1) / pairs);
+  if (short_case > splits_bound(max_t, 0, 5)) short_case = splits_bound(max_t, 0, 5);
+  const int32_t worst = (int32_t)(long_case > short_case ? long_case : short_case);
+  return plan_bytes(kv, batch, num_q_heads, worst);
+}
+
+const char* tempo_strerror(int status) {
+  switch (status) {
+    case TEMPO_OK: return "ok";
+    case TEMPO_ERR_NULL: return "a required pointer is NULL";
+    case TEMPO_ERR_SHAPE: return "unsupported shape (head_dim, block_size, head counts or batch)";
+    case TEMPO_ERR_RANGE: return "step or window out of range for this block store";
+    case TEMPO_ERR_WORKSPACE: return "workspace is NULL, misaligned or too small";
+    case TEMPO_ERR_DTYPE: return "unknown dtype";
+    case TEMPO_ERR_LAUNCH: return "HIP launch failed";
+    default: return "unknown status";
+  }
+}
+
+int tempo_kv_append(const tempo_kv* kv, const void* k_new, const void* v_new, int32_t batch,
+                    int32_t t, const int32_t* t_per_seq, void* stream) {
+  int rc = check_store(kv);
+  if (rc != TEMPO_OK) return rc;
+  if (!k_new || !v_new) return TEMPO_ERR_NULL;
+  if (batch < 1 || batch > 65535) return TEMPO_ERR_SHAPE;
+  if ((rc = check_step(kv, t)) != TEMPO_OK) return rc;
+  const StoreParams p = store_params(kv, batch, t, t_per_seq);
+  const hipError_t e = launch_append(p, k_new, v_new, kv->head_dim, kv->dtype, static_cast<hipStream_t>(stream));
+  return launch_status(e, "kv_append");
+}
+
+int tempo_kv_gather(const tempo_kv* kv, void* k_out, void* v_out, int32_t batch, int32_t j0,
+                    int32_t count, void* stream) {
+  int rc = check_store(kv);
+  if (rc != TEMPO_OK) return rc;
+  if (batch < 1 || batch > 65535) return TEMPO_ERR_SHAPE;
+  if (j0 < 0 || count < 0) return TEMPO_ERR_RANGE;
+  if (count == 0) return TEMPO_OK;
+  if ((int64_t)j0 + count - 1 > INT32_MAX) return TEMPO_ERR_RANGE;
+  if ((rc = check_step(kv, j0 + count - 1)) != TEMPO_OK) return rc;
+  const StoreParams p = store_params(kv, batch, 0, nullptr);
+  const hipError_t e = launch_gather(p, k_out, v_out, kv->head_dim, kv->dtype, j0, count,
+                                     static_cast<hipStream_t>(stream));
+  return launch_status(e, "kv_gather");
+}
+
+int tempo_attn_decode_causal(const tempo_kv* kv, const void* q, void* out, int32_t batch,
+                             int32_t num_q_heads, int32_t t, const int32_t* t_per_seq,
+                             float scale, void* workspace, size_t workspace_bytes, void* stream) {
+  return decode(kv, q, out, batch, num_q_heads, t, t_per_seq, 0, scale, workspace, workspace_bytes, stream);
+}
+
+int tempo_attn_decode_window(const tempo_kv* kv, const void* q, void* out, int32_t batch,
+                             int32_t num_q_heads, int32_t t, const int32_t* t_per_seq,
+                             int32_t window, float scale, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+  if (window < 1) return TEMPO_ERR_RANGE;
+  return decode(kv, q, out, batch, num_q_heads, t, t_per_seq, window, scale, workspace, workspace_bytes, stream);
+}
+
+int tempo_attn_decode_partial(const tempo_kv* kv, const void* q, int32_t batch,
+                              int32_t num_q_heads, int32_t t, const int32_t* t_per_seq,
+                              int32_t window, float scale, const tempo_plan* plan,
+                              void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_layout(kv);
+  if (rc != TEMPO_OK) return rc;
+  if (!q) return TEMPO_ERR_NULL;
+  if ((rc = check_attn(kv, batch, num_q_heads, t, window, t_per_seq != nullptr, plan, workspace, workspace_bytes)) != TEMPO_OK) return rc;
+  return do_partial(kv, q, nullptr, batch, num_q_heads, t, t_per_seq, window, scale, plan, workspace,
+                    static_cast<hipStream_t>(stream));
+}
+
+int tempo_attn_decode_combine(const tempo_kv* kv, void* out, int32_t batch, int32_t num_q_heads,
+                              int32_t t, const int32_t* t_per_seq, int32_t window,
+                              const tempo_plan* plan, const void* workspace,
+                              size_t workspace_bytes, void* stream) {
+  int rc = check_layout(kv);
+  if (rc != TEMPO_OK) return rc;
+  if (!out) return TEMPO_ERR_NULL;
+  if ((rc = check_attn(kv, batch, num_q_heads, t, window, t_per_seq != nullptr, plan, workspace, workspace_bytes)) != TEMPO_OK) return rc;
+  return do_combine(kv, out, batch, num_q_heads, t, t_per_seq, window, plan,
+                    const_cast<void*>(workspace), static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,124 @@
+// Internal declarations shared by the translation units of libtempo.
+// Nothing here crosses the C ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tempo.h"
+
+namespace tempo {
+
+// ---- block-store layout ----------------------------------------------------
+// Offsets are in elements, inside the tile of one (block, kv head) pair, which
+// holds block_size * head_dim elements.
+
+// f32: row-major [slot][d].
+__host__ __device__ inline int64_t tile_off_f32(int D, int slot, int d) {
+  return (int64_t)slot * D + d;
+}
+
+// bf16 keys.  Groups of 32 slots; a group is 2 row-tiles (slots 0..15, 16..31)
+// x D/32 contraction steps, each a 1 KiB unit of 64 lanes x 8 elements: lane
+// (row + 16*c) holds dims 32*s + 8*c .. +7 of slot `row` of the tile.  That is
+// the A-operand image of a 16x16x32 MFMA (rows = slots, contraction = dims).
+__host__ __device__ inline int64_t tile_off_k_bf16(int D, int slot, int d) {
+  const int grp = slot >> 5, u = slot & 31, tile = u >> 4, row = u & 15;
+  const int s = d >> 5, c = (d & 31) >> 3, e = d & 7;
+  return (int64_t)grp * 32 * D + (int64_t)(((tile * (D >> 5) + s) * 64) + c * 16 + row) * 8 + e;
+}
+
+// bf16 values.  Same groups of 32 slots; a group is D/16 column-tiles, each a
+// 1 KiB unit: lane (n + 16*c) holds dim 16*dt + n of the 8 slots
+// {4c..4c+3, 16+4c..16+4c+3}.  That is the B-operand image of a 16x16x32 MFMA
+// (contraction = slots, columns = dims) whose contraction order matches the
+// accumulator image of the two key row-tiles above.
+__host__ __device__ inline int64_t tile_off_v_bf16(int D, int slot, int d) {
+  const int grp = slot >> 5, u = slot & 31, half = u >> 4, uu = u & 15;
+  const int c = uu >> 2, e = (uu & 3) + 4 * half;
+  const int dt = d >> 4, n = d & 15;
+  return (int64_t)grp * 32 * D + (int64_t)((dt * 64) + c * 16 + n) * 8 + e;
+}
+
+__host__ __device__ inline int clamp_block(int phys, int num_blocks) {
+  return phys < 0 ? 0 : (phys >= num_blocks ? num_blocks - 1 : phys);
+}
+
+// ---- kernel parameter blocks -------------------------------------------------
+struct StoreParams {
+  void* k_pool;
+  void* v_pool;
+  const int32_t* block_table;
+  const int32_t* t_per_seq;  // may be null
+  int32_t t;                 // uniform step / upper bound
+  int32_t z_log2;
+  int32_t max_blocks_per_seq;
+  int32_t num_blocks;
+  int32_t Hkv;
+  int32_t batch;
+};
+
+struct AttnParams {
+  const void* k_pool;
+  const void* v_pool;
+  const int32_t* block_table;
+  const void* q;
+  const int32_t* t_per_seq;  // may be null
+  float* ws_ml;              // [B][Hq][S][2]  (running max in log2 units, running sum)
+  float* ws_acc;             // [B][Hq][S][D]
+  void* out;                 // [B][Hq][D]
+  int32_t t;                 // uniform step / upper bound
+  int32_t window;            // 0 = causal
+  int32_t z_log2;
+  int32_t max_blocks_per_seq;
+  int32_t num_blocks;
+  int32_t Hkv;
+  int32_t Hq;
+  int32_t G;                 // Hq / Hkv
+  int32_t tps_log2;          // log2(tokens per split)
+  int32_t num_splits;        // S: stride of the split axis in the workspace
+  int32_t direct;            // 1: single split, write `out` and skip the combine
+  float scale_log2e;         // s * log2(e)
+};
+
+// Visible range and split bookkeeping of one sequence, identical on host and device.
+struct SeqRange {
+  int lo, hi, chunk0, nchunks;
+};
+__host__ __device__ inline SeqRange seq_range(int t_b, int window, int tps_log2) {
+  SeqRange r;
+  r.hi = t_b;
+  r.lo = (window > 0 && t_b - window + 1 > 0) ? t_b - window + 1 : 0;
+  r.chunk0 = r.lo >> tps_log2;
+  r.nchunks = (t_b >> tps_log2) - r.chunk0 + 1;
+  return r;
+}
+
+// Launch and return the launch's own status.  hipGetLastError() is not used: it
+// reports the last error of any HIP call on the thread, including benign ones
+// left behind by the caller's framework (an event query that was "not ready").
+template <typename... Params>
+inline hipError_t launch_converted(void (*kernel)(Params...), dim3 grid, dim3 block, size_t lds,
+                                   hipStream_t stream, Params... vals) {
+  void* argv[] = {(void*)&vals...};
+  return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, argv, lds, stream);
+}
+template <typename... Params, typename... Args>
+inline hipError_t launch(void (*kernel)(Params...), dim3 grid, dim3 block, size_t lds,
+                         hipStream_t stream, Args... args) {
+  static_assert(sizeof...(Params) == sizeof...(Args), "kernel argument count");
+  return launch_converted<Params...>(kernel, grid, block, lds, stream, static_cast<Params>(args)...);
+}
+
+// ---- launchers (defined next to their kernels) -------------------------------
+hipError_t launch_append(const StoreParams& p, const void* k_new, const void* v_new, int D,
+                         int dtype, hipStream_t stream);
+hipError_t launch_gather(const StoreParams& p, void* k_out, void* v_out, int D, int dtype, int j0,
+                         int count, hipStream_t stream);
+hipError_t launch_partial_bf16(const AttnParams& p, int batch, int D, int grid_splits, int waves,
+                               hipStream_t stream);
+hipError_t launch_partial_f32(const AttnParams& p, int batch, int D, int grid_splits, int waves,
+                              hipStream_t stream);
+hipError_t launch_combine(const AttnParams& p, int batch, int D, int dtype, hipStream_t stream);
+
+}  // namespace tempo

@@ -1,0 +1,106 @@
+"""Device-memory plumbing around the C ABI: allocate a block pool, a block table
+and a workspace with torch, keep the tempo_kv descriptor next to the tensors it
+points into, and forward to the entry points.  No arithmetic of the method lives
+here; every step runs in libtempo's kernels.
+"""
+from __future__ import annotations
+
+import math
+
+import torch
+
+from . import tempo as T
+
+_TORCH_DTYPE = {T.TEMPO_BF16: torch.bfloat16, T.TEMPO_F32: torch.float32}
+
+
+class BlockStore:
+    """A paged key/value pool (the paper's block store, Section 6) for `batch`
+    sequences, plus the workspace the attention entry points need.
+
+    block_table: int32 tensor [batch][max_blocks_per_seq] (tile n -> physical
+    block); by default sequence b owns blocks b*max_blocks_per_seq + n.
+    fill: "nan" poisons the pool so that any read outside the visible range shows.
+    """
+
+    def __init__(self, batch, num_q_heads, num_kv_heads, head_dim, block_size, max_t, dtype,
+                 device="cuda:0", num_blocks=None, block_table=None, fill="zero", pools=None):
+        self.batch, self.Hq, self.Hkv, self.D, self.Z = batch, num_q_heads, num_kv_heads, head_dim, block_size
+        self.dtype = dtype
+        self.device = torch.device(device)
+        self.max_blocks_per_seq = max_t // block_size + 1
+        self.max_t = self.max_blocks_per_seq * block_size - 1
+        self.num_blocks = num_blocks if num_blocks is not None else batch * self.max_blocks_per_seq
+        tdt = _TORCH_DTYPE[dtype]
+        shape = (self.num_blocks, num_kv_heads, block_size * head_dim)
+        if pools is not None:
+            self.k_pool, self.v_pool = pools
+            assert tuple(self.k_pool.shape) == shape and tuple(self.v_pool.shape) == shape
+        elif fill == "nan":
+            self.k_pool = torch.full(shape, float("nan"), dtype=tdt, device=self.device)
+            self.v_pool = torch.full(shape, float("nan"), dtype=tdt, device=self.device)
+        else:
+            self.k_pool = torch.zeros(shape, dtype=tdt, device=self.device)
+            self.v_pool = torch.zeros(shape, dtype=tdt, device=self.device)
+        if block_table is None:
+            block_table = torch.arange(batch * self.max_blocks_per_seq, dtype=torch.int32).reshape(
+                batch, self.max_blocks_per_seq)
+        self.block_table = block_table.to(device=self.device, dtype=torch.int32).contiguous()
+        assert tuple(self.block_table.shape) == (batch, self.max_blocks_per_seq)
+        self.kv = T.make_kv(self.k_pool, self.v_pool, self.block_table, self.num_blocks,
+                            self.max_blocks_per_seq, block_size, num_kv_heads, head_dim, dtype)
+        self.workspace_bytes = T.tempo_attn_workspace_bytes(self.kv, batch, num_q_heads, self.max_t)
+        self.workspace = torch.empty(self.workspace_bytes, dtype=torch.uint8, device=self.device)
+        self.scale = 1.0 / math.sqrt(head_dim)
+
+    # -- forwarding ----------------------------------------------------------------
+    def append(self, k_new, v_new, t, t_per_seq=None):
+        T.tempo_kv_append(self.kv, k_new, v_new, self.batch, t, t_per_seq)
+
+    def gather(self, j0, count):
+        tdt = _TORCH_DTYPE[self.dtype]
+        k = torch.empty((self.batch, count, self.Hkv, self.D), dtype=tdt, device=self.device)
+        v = torch.empty_like(k)
+        T.tempo_kv_gather(self.kv, k, v, self.batch, j0, count)
+        return k, v
+
+    def new_out(self):
+        return torch.empty((self.batch, self.Hq, self.D), dtype=_TORCH_DTYPE[self.dtype], device=self.device)
+
+    def attend_causal(self, q, out, t, t_per_seq=None, scale=None):
+        T.tempo_attn_decode_causal(self.kv, q, out, self.batch, self.Hq, t, t_per_seq,
+                                   self.scale if scale is None else scale, self.workspace,
+                                   self.workspace_bytes)
+        return out
+
+    def attend_window(self, q, out, t, window, t_per_seq=None, scale=None):
+        T.tempo_attn_decode_window(self.kv, q, out, self.batch, self.Hq, t, t_per_seq, window,
+                                   self.scale if scale is None else scale, self.workspace,
+                                   self.workspace_bytes)
+        return out
+
+    def attend_with_plan(self, q, out, t, plan, window=0, t_per_seq=None, scale=None):
+        """Partial + combine with an explicit plan (its own workspace)."""
+        nbytes = T.tempo_attn_plan_workspace_bytes(self.kv, self.batch, self.Hq, plan)
+        if getattr(self, "_plan_ws", None) is None or self._plan_ws.numel() < nbytes:
+            self._plan_ws = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        s = self.scale if scale is None else scale
+        T.tempo_attn_decode_partial(self.kv, q, self.batch, self.Hq, t, t_per_seq, window, s, plan,
+                                    self._plan_ws, nbytes)
+        T.tempo_attn_decode_combine(self.kv, out, self.batch, self.Hq, t, t_per_seq, window, plan,
+                                    self._plan_ws, nbytes)
+        return out
+
+    def prefill(self, K, V, upto, lengths=None):
+        """Write steps 0..upto of flat K, V ([batch][T][Hkv][D] device tensors)
+        into the pool, one tempo_kv_append per step.  With `lengths` (int32 device
+        tensor of per-sequence lengths) sequence b stops at its own last step."""
+        if lengths is None:
+            for j in range(upto + 1):
+                self.append(K[:, j].contiguous(), V[:, j].contiguous(), j)
+            return
+        last = (lengths.to(torch.int64) - 1).clamp_(min=0)
+        ar = torch.arange(self.batch, device=self.device)
+        for j in range(upto + 1):
+            tj = torch.clamp(last, max=j)
+            self.append(K[ar, tj].contiguous(), V[ar, tj].contiguous(), j, tj.to(torch.int32))

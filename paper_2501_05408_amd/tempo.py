@@ -1,0 +1,246 @@
+"""Thin Python binding of libtempo's C ABI (include/tempo.h).
+
+Argument marshalling only: every function here has the name and the meaning of
+the C entry point it forwards to, and no step of the path is computed in Python.
+Device buffers are passed as torch tensors (their data_ptr() is taken) or as raw
+integer addresses; torch is used by callers for device memory and streams only.
+
+The shared library is loaded from paper_2501_05408_amd/lib/libtempo.so.  If it
+has not been built yet it is compiled (hipcc, gfx950) on first use; if it cannot
+be loaded the import of a GPU entry point fails loudly -- there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+from . import build as _build
+
+TEMPO_BF16 = 0
+TEMPO_F32 = 1
+
+TEMPO_OK = 0
+TEMPO_ERR_NULL = -1
+TEMPO_ERR_SHAPE = -2
+TEMPO_ERR_RANGE = -3
+TEMPO_ERR_WORKSPACE = -4
+TEMPO_ERR_DTYPE = -5
+TEMPO_ERR_LAUNCH = -6
+
+
+class tempo_kv(ctypes.Structure):
+    _fields_ = [
+        ("k_pool", ctypes.c_void_p),
+        ("v_pool", ctypes.c_void_p),
+        ("block_table", ctypes.c_void_p),
+        ("num_blocks", ctypes.c_int32),
+        ("max_blocks_per_seq", ctypes.c_int32),
+        ("block_size", ctypes.c_int32),
+        ("num_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32),
+        ("dtype", ctypes.c_int32),
+    ]
+
+
+class tempo_plan(ctypes.Structure):
+    _fields_ = [
+        ("tokens_per_split", ctypes.c_int32),
+        ("num_splits", ctypes.c_int32),
+        ("waves", ctypes.c_int32),
+    ]
+
+    def __repr__(self):
+        return (f"tempo_plan(tokens_per_split={self.tokens_per_split}, "
+                f"num_splits={self.num_splits}, waves={self.waves})")
+
+
+class TempoError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {tempo_strerror(status)} (status {status})")
+
+
+_lib = None
+
+_i32 = ctypes.c_int32
+_vp = ctypes.c_void_p
+_kvp = ctypes.POINTER(tempo_kv)
+_planp = ctypes.POINTER(tempo_plan)
+_i32p = ctypes.POINTER(ctypes.c_int32)
+
+# name -> (restype, argtypes); kept in the order of include/tempo.h
+SIGNATURES = {
+    "tempo_visible_range": (ctypes.c_int, [_i32, _i32, _i32] + [_i32p] * 6),
+    "tempo_append_slot": (ctypes.c_int, [_i32, _i32, _i32p, _i32p]),
+    "tempo_kv_element_offset": (ctypes.c_int64, [_kvp, _i32, _i32, _i32, _i32, _i32]),
+    "tempo_kv_pool_bytes": (ctypes.c_size_t, [_kvp]),
+    "tempo_attn_plan": (ctypes.c_int, [_kvp, _i32, _i32, _i32, _i32, _planp]),
+    "tempo_attn_workspace_bytes": (ctypes.c_size_t, [_kvp, _i32, _i32, _i32]),
+    "tempo_strerror": (ctypes.c_char_p, [ctypes.c_int]),
+    "tempo_kv_append": (ctypes.c_int, [_kvp, _vp, _vp, _i32, _i32, _vp, _vp]),
+    "tempo_kv_gather": (ctypes.c_int, [_kvp, _vp, _vp, _i32, _i32, _i32, _vp]),
+    "tempo_attn_decode_causal": (ctypes.c_int, [_kvp, _vp, _vp, _i32, _i32, _i32, _vp, ctypes.c_float,
+                                                _vp, ctypes.c_size_t, _vp]),
+    "tempo_attn_decode_window": (ctypes.c_int, [_kvp, _vp, _vp, _i32, _i32, _i32, _vp, _i32,
+                                                ctypes.c_float, _vp, ctypes.c_size_t, _vp]),
+    "tempo_attn_decode_partial": (ctypes.c_int, [_kvp, _vp, _i32, _i32, _i32, _vp, _i32, ctypes.c_float,
+                                                 _planp, _vp, ctypes.c_size_t, _vp]),
+    "tempo_attn_decode_combine": (ctypes.c_int, [_kvp, _vp, _i32, _i32, _i32, _vp, _i32, _planp, _vp,
+                                                 ctypes.c_size_t, _vp]),
+    "tempo_attn_plan_workspace_bytes": (ctypes.c_size_t, [_kvp, _i32, _i32, _planp]),
+}
+
+
+def library_path() -> str:
+    return _build.LIB
+
+
+def _hip_runtimes_mapped():
+    """Paths of the HIP runtime libraries mapped into this process."""
+    found = set()
+    try:
+        with open("/proc/self/maps") as f:
+            for line in f:
+                if "libamdhip64" in line:
+                    found.add(line.split()[-1])
+    except OSError:
+        pass
+    return sorted(found)
+
+
+def load():
+    """Open libtempo.so (building it first only if it does not exist).
+
+    The library must run on the same HIP runtime as the tensors it is handed.
+    PyTorch ships its own copy of that runtime, so torch is imported first: the
+    dynamic loader then resolves libtempo's dependency to the copy already in the
+    process.  Two runtimes in one process is an error, not a fallback."""
+    global _lib
+    if _lib is None:
+        try:
+            import torch  # noqa: F401  (loads torch's HIP runtime before ours is resolved)
+        except ImportError:
+            pass
+        path = _build.LIB
+        if not os.path.exists(path):
+            _build.build(force=True)
+        lib = ctypes.CDLL(path)
+        runtimes = _hip_runtimes_mapped()
+        if len(runtimes) > 1:
+            raise RuntimeError("two HIP runtimes are loaded in this process: " + ", ".join(runtimes))
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(lib, name)  # AttributeError if the library lacks a declared symbol
+            fn.restype = res
+            fn.argtypes = args
+        _lib = lib
+    return _lib
+
+
+def _ptr(x):
+    if x is None:
+        return None
+    if hasattr(x, "data_ptr"):
+        return x.data_ptr()
+    return int(x)
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return _ptr(getattr(stream, "cuda_stream", stream))
+
+
+def _check(rc: int, where: str):
+    if rc != TEMPO_OK:
+        raise TempoError(rc, where)
+
+
+def make_kv(k_pool, v_pool, block_table, num_blocks, max_blocks_per_seq, block_size, num_kv_heads,
+            head_dim, dtype) -> tempo_kv:
+    """Fill a tempo_kv descriptor; the caller keeps the tensors alive."""
+    return tempo_kv(_ptr(k_pool), _ptr(v_pool), _ptr(block_table), num_blocks, max_blocks_per_seq,
+                    block_size, num_kv_heads, head_dim, dtype)
+
+
+# ---- pure host functions -------------------------------------------------------
+def tempo_visible_range(t: int, window: int, Z: int) -> dict:
+    vals = [ctypes.c_int32(0) for _ in range(6)]
+    _check(load().tempo_visible_range(t, window, Z, *[ctypes.byref(v) for v in vals]),
+           "tempo_visible_range")
+    names = ["lo", "hi", "first_tile", "last_tile", "first_tile_skip", "last_tile_valid"]
+    return {n: v.value for n, v in zip(names, vals)}
+
+
+def tempo_append_slot(t: int, Z: int):
+    tile, slot = ctypes.c_int32(0), ctypes.c_int32(0)
+    _check(load().tempo_append_slot(t, Z, ctypes.byref(tile), ctypes.byref(slot)), "tempo_append_slot")
+    return tile.value, slot.value
+
+
+def tempo_kv_element_offset(kv: tempo_kv, which: int, block: int, head: int, slot: int, d: int) -> int:
+    return load().tempo_kv_element_offset(ctypes.byref(kv), which, block, head, slot, d)
+
+
+def tempo_kv_pool_bytes(kv: tempo_kv) -> int:
+    return load().tempo_kv_pool_bytes(ctypes.byref(kv))
+
+
+def tempo_attn_plan(kv: tempo_kv, batch: int, num_q_heads: int, t_max: int, window: int = 0) -> tempo_plan:
+    plan = tempo_plan()
+    _check(load().tempo_attn_plan(ctypes.byref(kv), batch, num_q_heads, t_max, window, ctypes.byref(plan)),
+           "tempo_attn_plan")
+    return plan
+
+
+def tempo_attn_workspace_bytes(kv: tempo_kv, batch: int, num_q_heads: int, max_t: int) -> int:
+    return load().tempo_attn_workspace_bytes(ctypes.byref(kv), batch, num_q_heads, max_t)
+
+
+def tempo_attn_plan_workspace_bytes(kv: tempo_kv, batch: int, num_q_heads: int, plan: tempo_plan) -> int:
+    return load().tempo_attn_plan_workspace_bytes(ctypes.byref(kv), batch, num_q_heads, ctypes.byref(plan))
+
+
+def tempo_strerror(status: int) -> str:
+    return load().tempo_strerror(status).decode()
+
+
+# ---- device entry points ---------------------------------------------------------
+def tempo_kv_append(kv, k_new, v_new, batch, t, t_per_seq=None, stream=None):
+    _check(load().tempo_kv_append(ctypes.byref(kv), _ptr(k_new), _ptr(v_new), batch, t, _ptr(t_per_seq),
+                                  _stream(stream)), "tempo_kv_append")
+
+
+def tempo_kv_gather(kv, k_out, v_out, batch, j0, count, stream=None):
+    _check(load().tempo_kv_gather(ctypes.byref(kv), _ptr(k_out), _ptr(v_out), batch, j0, count,
+                                  _stream(stream)), "tempo_kv_gather")
+
+
+def tempo_attn_decode_causal(kv, q, out, batch, num_q_heads, t, t_per_seq, scale, workspace,
+                             workspace_bytes, stream=None):
+    _check(load().tempo_attn_decode_causal(ctypes.byref(kv), _ptr(q), _ptr(out), batch, num_q_heads, t,
+                                           _ptr(t_per_seq), scale, _ptr(workspace), workspace_bytes,
+                                           _stream(stream)), "tempo_attn_decode_causal")
+
+
+def tempo_attn_decode_window(kv, q, out, batch, num_q_heads, t, t_per_seq, window, scale, workspace,
+                             workspace_bytes, stream=None):
+    _check(load().tempo_attn_decode_window(ctypes.byref(kv), _ptr(q), _ptr(out), batch, num_q_heads, t,
+                                           _ptr(t_per_seq), window, scale, _ptr(workspace),
+                                           workspace_bytes, _stream(stream)), "tempo_attn_decode_window")
+
+
+def tempo_attn_decode_partial(kv, q, batch, num_q_heads, t, t_per_seq, window, scale, plan, workspace,
+                              workspace_bytes, stream=None):
+    _check(load().tempo_attn_decode_partial(ctypes.byref(kv), _ptr(q), batch, num_q_heads, t,
+                                            _ptr(t_per_seq), window, scale, ctypes.byref(plan),
+                                            _ptr(workspace), workspace_bytes, _stream(stream)),
+           "tempo_attn_decode_partial")
+
+
+def tempo_attn_decode_combine(kv, out, batch, num_q_heads, t, t_per_seq, window, plan, workspace,
+                              workspace_bytes, stream=None):
+    _check(load().tempo_attn_decode_combine(ctypes.byref(kv), _ptr(out), batch, num_q_heads, t,
+                                            _ptr(t_per_seq), window, ctypes.byref(plan), _ptr(workspace),
+                                            workspace_bytes, _stream(stream)),
+           "tempo_attn_decode_combine")

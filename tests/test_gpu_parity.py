@@ -1,0 +1,350 @@
+"""GPU parity: libtempo (through its C ABI) against the fp64 CPU oracle, element
+by element, on the same seeded inputs.
+
+Tolerances (written out here on purpose):
+  bf16 workloads  |gpu - oracle| <= 2e-2 elementwise  and  max|gpu - oracle| <= 1e-2 * max|oracle|
+  fp32 workloads  the same two measures with 1e-5
+Integer results (visible range, tile, slot) and everything the block store holds
+are compared bit for bit.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import tempo_oracle as oracle
+from paper_2501_05408_amd import synth
+from paper_2501_05408_amd import tempo as T
+from paper_2501_05408_amd.store import BlockStore
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+TOL = {T.TEMPO_BF16: (2e-2, 1e-2), T.TEMPO_F32: (1e-5, 1e-5)}
+TDT = {T.TEMPO_BF16: torch.bfloat16, T.TEMPO_F32: torch.float32}
+NAME = {T.TEMPO_BF16: "bf16", T.TEMPO_F32: "f32"}
+
+
+def np64(x):
+    return x.detach().float().cpu().numpy().astype(np.float64)
+
+
+def assert_close(got, ref, dtype, what):
+    atol, rtol = TOL[dtype]
+    g = np64(got) if isinstance(got, torch.Tensor) else got
+    assert np.isfinite(g).all(), f"{what}: non-finite output"
+    err = np.abs(g - ref).max()
+    assert err <= atol, f"{what}: max-abs {err:.3e} > {atol}"
+    assert err <= rtol * np.abs(ref).max(), f"{what}: max-abs {err:.3e} > {rtol} * {np.abs(ref).max():.3e}"
+
+
+def host_inputs(seed, B, T_len, Hq, Hkv, D, dtype):
+    """q for every step and K, V: fp32 arrays holding values rounded to dtype."""
+    q = synth.normal_as(seed, 1, (T_len, B, Hq, D), NAME[dtype])
+    K = synth.normal_as(seed, 2, (B, T_len, Hkv, D), NAME[dtype])
+    V = synth.normal_as(seed, 3, (B, T_len, Hkv, D), NAME[dtype])
+    return q, K, V
+
+
+def dev(x, dtype):
+    return torch.from_numpy(np.ascontiguousarray(x)).to(DEV).to(TDT[dtype])
+
+
+def random_table(seed, batch, max_blocks, extra=3):
+    n = batch * max_blocks + extra
+    perm = synth.permutation(seed, 77, n)[: batch * max_blocks]
+    return torch.from_numpy(perm.reshape(batch, max_blocks).copy()), n
+
+
+# ----------------------------------------------------------------------------
+# Block store: what append writes is what the header's layout says, bit for bit.
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", [T.TEMPO_BF16, T.TEMPO_F32])
+@pytest.mark.parametrize("D,Z", [(128, 64), (64, 32)])
+def test_append_then_gather_is_identity(dtype, D, Z):
+    B, Hq, Hkv, steps = 3, 4, 2, 150
+    _, K, V = host_inputs(31, B, steps, Hq, Hkv, D, dtype)
+    table, nb = random_table(31, B, steps // Z + 1)
+    st = BlockStore(B, Hq, Hkv, D, Z, steps - 1, dtype, num_blocks=nb, block_table=table, fill="nan")
+    Kd, Vd = dev(K, dtype), dev(V, dtype)
+    for t in range(steps):
+        st.append(Kd[:, t].contiguous(), Vd[:, t].contiguous(), t)
+    kg, vg = st.gather(0, steps)
+    assert torch.equal(kg, Kd) and torch.equal(vg, Vd)
+    kg, vg = st.gather(37, 70)
+    assert torch.equal(kg, Kd[:, 37:107]) and torch.equal(vg, Vd[:, 37:107])
+    # the pool itself, element by element, at the offsets the ABI documents
+    kp = st.k_pool.flatten().cpu()
+    vp = st.v_pool.flatten().cpu()
+    Kc, Vc = Kd.cpu(), Vd.cpu()
+    rng = np.random.default_rng(5)
+    for _ in range(400):
+        b, t, h, d = rng.integers(B), rng.integers(steps), rng.integers(Hkv), rng.integers(D)
+        tile, slot = T.tempo_append_slot(int(t), Z)
+        assert (tile, slot) == oracle.append_slot(int(t), Z)
+        blk = int(table[b, tile])
+        assert kp[T.tempo_kv_element_offset(st.kv, 0, blk, int(h), slot, int(d))] == Kc[b, t, h, d]
+        assert vp[T.tempo_kv_element_offset(st.kv, 1, blk, int(h), slot, int(d))] == Vc[b, t, h, d]
+    # per-sequence steps: each sequence writes at its own position only
+    st2 = BlockStore(B, Hq, Hkv, D, Z, steps - 1, dtype, num_blocks=nb, block_table=table)
+    tps = torch.tensor([5, 149, 64], dtype=torch.int32, device=DEV)
+    ar = torch.arange(B, device=DEV)
+    st2.append(Kd[ar, tps.long()].contiguous(), Vd[ar, tps.long()].contiguous(), 149, tps)
+    kg2, _ = st2.gather(0, steps)
+    for b in range(B):
+        assert torch.equal(kg2[b, int(tps[b])], Kd[b, int(tps[b])])
+        assert int((kg2[b] != 0).any(dim=-1).any(dim=-1).sum()) == 1
+
+
+# ----------------------------------------------------------------------------
+# Tiny causal decode, fp32, every step (append then attend).
+# ----------------------------------------------------------------------------
+def test_tiny_causal_fp32_every_step():
+    B, Hq, Hkv, D, Z, steps = 1, 8, 2, 64, 64, 512
+    dtype = T.TEMPO_F32
+    q, K, V = host_inputs(1, B, steps, Hq, Hkv, D, dtype)
+    st = BlockStore(B, Hq, Hkv, D, Z, steps - 1, dtype, fill="nan")
+    qd, Kd, Vd = dev(q, dtype), dev(K, dtype), dev(V, dtype)
+    outs = torch.empty((steps, B, Hq, D), dtype=torch.float32, device=DEV)
+    for t in range(steps):
+        st.append(Kd[:, t].contiguous(), Vd[:, t].contiguous(), t)
+        st.attend_causal(qd[t], outs[t], t)
+    torch.cuda.synchronize()
+    got = np64(outs)
+    K64, V64 = K.astype(np.float64), V.astype(np.float64)
+    for t in range(steps):
+        ref = oracle.attend(q[t].astype(np.float64), K64, V64, t, 0, 1.0 / np.sqrt(D))
+        assert_close(got[t], ref, dtype, f"fp32 causal t={t}")
+    # t = 0 is exactly V[0] (softmax over one key)
+    assert np.array_equal(got[0][0, :4], np.broadcast_to(V64[0, 0, 0], (4, D)))
+
+
+# ----------------------------------------------------------------------------
+# bf16, small batch, every step: causal and several windows, tiles of 64 with a
+# ragged tail, window fronts cutting through the middle of a 32-slot group.
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("window", [0, 1, 2, 50, 51, 64, 65, 97])
+def test_bf16_every_step_causal_and_window(window):
+    B, Hq, Hkv, D, Z, steps = 2, 6, 2, 128, 64, 230
+    dtype = T.TEMPO_BF16
+    q, K, V = host_inputs(2, B, steps, Hq, Hkv, D, dtype)
+    table, nb = random_table(2, B, steps // Z + 1)
+    st = BlockStore(B, Hq, Hkv, D, Z, steps - 1, dtype, num_blocks=nb, block_table=table, fill="nan")
+    qd, Kd, Vd = dev(q, dtype), dev(K, dtype), dev(V, dtype)
+    outs = torch.empty((steps, B, Hq, D), dtype=torch.bfloat16, device=DEV)
+    for t in range(steps):
+        st.append(Kd[:, t].contiguous(), Vd[:, t].contiguous(), t)
+        if window:
+            st.attend_window(qd[t], outs[t], t, window)
+        else:
+            st.attend_causal(qd[t], outs[t], t)
+    torch.cuda.synchronize()
+    got = np64(outs)
+    K64, V64 = K.astype(np.float64), V.astype(np.float64)
+    for t in range(steps):
+        ref = oracle.attend(q[t].astype(np.float64), K64, V64, t, window, 1.0 / np.sqrt(D))
+        assert_close(got[t], ref, dtype, f"bf16 window={window} t={t}")
+
+
+@pytest.mark.parametrize("dtype", [T.TEMPO_BF16, T.TEMPO_F32])
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("G", [1, 2, 3, 4, 5, 8, 16])
+def test_group_sizes_and_head_dims(dtype, D, G):
+    B, Hkv, Z, steps = 2, 2, 32, 140
+    Hq = Hkv * G
+    q, K, V = host_inputs(3 + G, B, steps, Hq, Hkv, D, dtype)
+    st = BlockStore(B, Hq, Hkv, D, Z, steps - 1, dtype, fill="nan")
+    qd, Kd, Vd = dev(q, dtype), dev(K, dtype), dev(V, dtype)
+    st.prefill(Kd, Vd, steps - 1)
+    K64, V64 = K.astype(np.float64), V.astype(np.float64)
+    for t, w in ((0, 0), (31, 0), (32, 0), (77, 0), (139, 0), (139, 40), (100, 33)):
+        out = st.new_out()
+        if w:
+            st.attend_window(qd[t], out, t, w, scale=0.2)
+        else:
+            st.attend_causal(qd[t], out, t, scale=0.2)
+        ref = oracle.attend(q[t].astype(np.float64), K64, V64, t, w, 0.2)
+        assert_close(out, ref, dtype, f"G={G} D={D} t={t} w={w}")
+
+
+# ----------------------------------------------------------------------------
+# The result does not depend on pool contents outside the visible range.
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", [T.TEMPO_BF16, T.TEMPO_F32])
+def test_poisoned_pool_gives_identical_bits(dtype):
+    B, Hq, Hkv, D, Z, steps = 2, 6, 2, 128, 64, 200
+    q, K, V = host_inputs(4, B, steps, Hq, Hkv, D, dtype)
+    qd, Kd, Vd = dev(q, dtype), dev(K, dtype), dev(V, dtype)
+    results = []
+    for fill in ("zero", "nan"):
+        st = BlockStore(B, Hq, Hkv, D, Z, steps - 1, dtype, fill=fill)
+        outs = []
+        for t in range(steps):
+            st.append(Kd[:, t].contiguous(), Vd[:, t].contiguous(), t)
+            if t in (0, 1, 30, 31, 32, 33, 63, 64, 65, 100, 127, 128, 199):
+                for w in (0, 1, 7, 33, 70):
+                    out = st.new_out()
+                    if w:
+                        st.attend_window(qd[t], out, t, w)
+                    else:
+                        st.attend_causal(qd[t], out, t)
+                    outs.append(out)
+        results.append(torch.stack(outs))
+    assert torch.isfinite(results[1].float()).all()
+    assert torch.equal(results[0], results[1])
+
+
+# ----------------------------------------------------------------------------
+# Ragged batch (per-sequence steps), random block table in a shared pool.
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", [T.TEMPO_BF16, T.TEMPO_F32])
+@pytest.mark.parametrize("window", [0, 45])
+def test_ragged_steps_random_block_table(dtype, window):
+    B, Hq, Hkv, D, Z, T_len = 7, 6, 2, 128, 32, 300
+    q, K, V = host_inputs(5, B, T_len, Hq, Hkv, D, dtype)
+    lengths = np.array([1, 300, 33, 32, 150, 257, 2], dtype=np.int32)
+    table, nb = random_table(5, B, (T_len - 1) // Z + 1)
+    st = BlockStore(B, Hq, Hkv, D, Z, T_len - 1, dtype, num_blocks=nb, block_table=table, fill="nan")
+    Kd, Vd = dev(K, dtype), dev(V, dtype)
+    len_d = torch.from_numpy(lengths).to(DEV)
+    st.prefill(Kd, Vd, T_len - 1, lengths=len_d)
+    tps = (len_d - 1).to(torch.int32)
+    qd = dev(q[0], dtype)
+    out = st.new_out()
+    if window:
+        st.attend_window(qd, out, T_len - 1, window, t_per_seq=tps)
+    else:
+        st.attend_causal(qd, out, T_len - 1, t_per_seq=tps)
+    ref = oracle.attend(q[0].astype(np.float64), K.astype(np.float64), V.astype(np.float64),
+                        lengths - 1, window, 1.0 / np.sqrt(D))
+    assert_close(out, ref, dtype, f"ragged window={window}")
+    # a ragged call with all steps equal is the uniform call, bit for bit
+    st2 = BlockStore(B, Hq, Hkv, D, Z, T_len - 1, dtype, num_blocks=nb, block_table=table)
+    st2.prefill(Kd, Vd, 200)
+    a, b = st2.new_out(), st2.new_out()
+    same = torch.full((B,), 200, dtype=torch.int32, device=DEV)
+    st2.attend_causal(qd, a, 200)
+    st2.attend_causal(qd, b, 200, t_per_seq=same)
+    assert torch.equal(a, b)
+
+
+# ----------------------------------------------------------------------------
+# Any valid split plan gives the same result within tolerance; same plan, same bits.
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", [T.TEMPO_BF16, T.TEMPO_F32])
+def test_explicit_plans_and_determinism(dtype):
+    B, Hq, Hkv, D, Z, steps = 2, 6, 2, 128, 128, 700
+    q, K, V = host_inputs(6, B, steps, Hq, Hkv, D, dtype)
+    st = BlockStore(B, Hq, Hkv, D, Z, steps - 1, dtype, fill="nan")
+    qd, Kd, Vd = dev(q, dtype), dev(K, dtype), dev(V, dtype)
+    st.prefill(Kd, Vd, steps - 1)
+    K64, V64 = K.astype(np.float64), V.astype(np.float64)
+    for t, w in ((699, 0), (699, 300), (415, 0), (31, 0)):
+        ref = oracle.attend(q[t].astype(np.float64), K64, V64, t, w, 1.0 / np.sqrt(D))
+        lo = 0 if w == 0 else max(0, t - w + 1)
+        for tps in (32, 64, 128, 256, 512, 1024):
+            for waves in (1, 2, 4, 8):
+                plan = T.tempo_plan(tps, t // tps - lo // tps + 1, waves)
+                out = st.new_out()
+                st.attend_with_plan(qd[t], out, t, plan, window=w)
+                assert_close(out, ref, dtype, f"plan tps={tps} waves={waves} t={t} w={w}")
+                again = st.new_out()
+                st.attend_with_plan(qd[t], again, t, plan, window=w)
+                assert torch.equal(out, again)
+
+
+# ----------------------------------------------------------------------------
+# Full-size workloads, in the launch configuration the benchmark times.
+# Keys/values are drawn on the GPU (seeded), appended through the ABI, and the
+# oracle reads the same values back from the flat tensors.
+# ----------------------------------------------------------------------------
+def flat_kv(seed, B, T_len, Hkv, D):
+    K = synth.device_normal((B, T_len, Hkv, D), seed * 10 + 1, torch.bfloat16, DEV)
+    V = synth.device_normal((B, T_len, Hkv, D), seed * 10 + 2, torch.bfloat16, DEV)
+    return K, V
+
+
+def test_llama_shape_causal_bf16_full_size():
+    B, Hq, Hkv, D, Z, T_len = 16, 24, 8, 128, 256, 4096
+    dtype = T.TEMPO_BF16
+    K, V = flat_kv(21, B, T_len, Hkv, D)
+    table, nb = random_table(21, B, T_len // Z, extra=0)
+    st = BlockStore(B, Hq, Hkv, D, Z, T_len - 1, dtype, num_blocks=nb, block_table=table, fill="nan")
+    st.prefill(K, V, T_len - 1)
+    K64, V64 = np64(K), np64(V)
+    steps = [0, 1, 31, 32, 255, 256, 257, 1000, 2047, 2048, 3000, 4094, 4095]
+    for t in steps:
+        q = synth.device_normal((B, Hq, D), 2100 + t, torch.bfloat16, DEV)
+        out = st.attend_causal(q, st.new_out(), t)
+        ref = oracle.attend(np64(q), K64[:, :t + 1], V64[:, :t + 1], t, 0, 1.0 / np.sqrt(D))
+        assert_close(out, ref, dtype, f"llama causal t={t}")
+
+
+def test_llama_shape_window_bf16_full_size():
+    B, Hq, Hkv, D, Z, T_len, w = 16, 24, 8, 128, 256, 16384, 512
+    dtype = T.TEMPO_BF16
+    K, V = flat_kv(22, B, T_len, Hkv, D)
+    st = BlockStore(B, Hq, Hkv, D, Z, T_len - 1, dtype, fill="nan")
+    st.prefill(K, V, T_len - 1)
+    steps = [0, 100, 510, 511, 512, 513, 767, 768, 1023, 1024, 1279, 5000, 8191, 8192, 16383]
+    for t in steps:
+        r = T.tempo_visible_range(t, w, Z)
+        assert r == {k: v for k, v in oracle.visible_range(t, w, Z).items() if k in r}
+        lo = r["lo"]
+        q = synth.device_normal((B, Hq, D), 2200 + t, torch.bfloat16, DEV)
+        out = st.attend_window(q, st.new_out(), t, w)
+        ref = oracle.attend(np64(q), np64(K[:, lo:t + 1]), np64(V[:, lo:t + 1]), t - lo, w, 1.0 / np.sqrt(D))
+        assert_close(out, ref, dtype, f"llama window t={t}")
+
+
+def test_long_single_sequence_bf16_full_size():
+    B, Hq, Hkv, D, Z, T_len = 1, 24, 8, 128, 256, 65536
+    dtype = T.TEMPO_BF16
+    K, V = flat_kv(23, B, T_len, Hkv, D)
+    st = BlockStore(B, Hq, Hkv, D, Z, T_len - 1, dtype, fill="nan")
+    st.prefill(K, V, T_len - 1)
+    K64, V64 = np64(K), np64(V)
+    for t, strict_tps in ((8191, 32), (32767, 128), (65535, 256)):
+        q = synth.device_normal((B, Hq, D), 2300 + t, torch.bfloat16, DEV)
+        ref = oracle.attend(np64(q), K64[:, :t + 1], V64[:, :t + 1], t, 0, 1.0 / np.sqrt(D))
+        plan = T.tempo_attn_plan(st.kv, B, Hq, t, 0)
+        assert plan.num_splits * Hkv >= 256          # at least 256 partial-attention work items
+        out = st.attend_causal(q, st.new_out(), t)
+        assert_close(out, ref, dtype, f"long t={t} default plan")
+        strict = T.tempo_plan(strict_tps, (t + 1) // strict_tps, 1 if strict_tps == 32 else 4)
+        assert strict.num_splits >= 256               # at least 256 partitions along the sequence
+        out = st.attend_with_plan(q, st.new_out(), t, strict)
+        assert_close(out, ref, dtype, f"long t={t} 256-way plan")
+
+
+def test_ragged_multi_layer_shared_pool_bf16():
+    # The ragged multi-layer workload at its real per-layer shape (batch 64, lengths
+    # uniform in [1, 8192], one shared pool, a random block table per layer); 4 of
+    # the 28 layers, since layers are independent calls of identical geometry.
+    layers, B, Hq, Hkv, D, Z, T_max = 4, 64, 24, 8, 128, 256, 8192
+    dtype = T.TEMPO_BF16
+    lengths = synth.integers(24, 1, B, 1, T_max)
+    lengths[0], lengths[1] = 1, T_max                    # both extremes are present
+    blocks_per_seq = T_max // Z
+    perm = synth.permutation(24, 2, layers * B * blocks_per_seq)
+    tables = torch.from_numpy(perm.reshape(layers, B, blocks_per_seq).copy())
+    nb = layers * B * blocks_per_seq
+    shape = (nb, Hkv, Z * D)
+    k_pool = torch.full(shape, float("nan"), dtype=torch.bfloat16, device=DEV)
+    v_pool = torch.full(shape, float("nan"), dtype=torch.bfloat16, device=DEV)
+    len_d = torch.from_numpy(lengths).to(DEV)
+    tps = (len_d - 1).to(torch.int32)
+    sample = [0, 1] + [int(i) for i in np.argsort(lengths)[[5, 20, 40, 60]]]
+    for layer in range(layers):
+        K, V = flat_kv(240 + layer, B, T_max, Hkv, D)
+        st = BlockStore(B, Hq, Hkv, D, Z, T_max - 1, dtype, num_blocks=nb, block_table=tables[layer],
+                        pools=(k_pool, v_pool))
+        st.prefill(K, V, T_max - 1, lengths=len_d)
+        q = synth.device_normal((B, Hq, D), 2400 + layer, torch.bfloat16, DEV)
+        out = st.attend_causal(q, st.new_out(), T_max - 1, t_per_seq=tps)
+        for b in sample:
+            L = int(lengths[b])
+            ref = oracle.attend(np64(q[b:b + 1]), np64(K[b:b + 1, :L]), np64(V[b:b + 1, :L]), L - 1, 0,
+                                1.0 / np.sqrt(D))
+            assert_close(out[b:b + 1], ref, dtype, f"layer {layer} seq {b} len {L}")
+        assert torch.isfinite(out.float()).all()
+        del K, V

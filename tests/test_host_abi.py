@@ -1,0 +1,163 @@
+"""Host-side tests of libtempo: the library loads and exports every symbol the
+header declares, the integer functions agree bit for bit with the oracle's
+counting loops, the block-store layout is the one the header describes, the
+split planner's promises hold, and bad arguments are refused before any launch.
+No test here computes anything on a GPU."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import tempo_oracle as oracle
+from paper_2501_05408_amd import tempo as T
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "tempo.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tempo_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = T.load()
+    names = header_functions()
+    assert len(names) >= 14
+    for name in names:
+        assert hasattr(lib, name), f"libtempo.so lacks {name}"
+    assert sorted(T.SIGNATURES) == names, "binding and header disagree on the entry points"
+    for name in names:
+        assert callable(getattr(T, name)), f"binding lacks {name}"
+
+
+def test_visible_range_and_slot_match_oracle_bit_exact():
+    for Z in (1, 2, 3, 4, 8, 64, 256):
+        for t in list(range(0, 70)) + [255, 256, 257, 511, 4095, 16383]:
+            for w in (0, 1, 2, 3, 4, 9, 64, 512, 100000):
+                got = T.tempo_visible_range(t, w, Z)
+                ref = oracle.visible_range(t, w, Z)
+                for k in got:
+                    assert got[k] == ref[k], (t, w, Z, k)
+            assert T.tempo_append_slot(t, Z) == oracle.append_slot(t, Z)
+    with pytest.raises(T.TempoError):
+        T.tempo_visible_range(-1, 0, 4)
+    with pytest.raises(T.TempoError):
+        T.tempo_append_slot(3, 0)
+
+
+def kv_desc(dtype, D=128, Z=64, Hkv=2, num_blocks=3, max_blocks=4, pools=(1 << 20, 1 << 21, 1 << 22)):
+    return T.tempo_kv(pools[0], pools[1], pools[2], num_blocks, max_blocks, Z, Hkv, D, dtype)
+
+
+@pytest.mark.parametrize("D", [64, 128])
+def test_layout_is_a_bijection_and_matches_the_documented_order(D):
+    Z, Hkv, NB = 64, 2, 3
+    kv = kv_desc(T.TEMPO_BF16, D=D, Z=Z, Hkv=Hkv, num_blocks=NB)
+    n = NB * Hkv * Z * D
+    assert T.tempo_kv_pool_bytes(kv) == n * 2
+    for which in (0, 1):
+        seen = np.zeros(n, dtype=bool)
+        for blk in range(NB):
+            for head in range(Hkv):
+                for slot in range(Z):
+                    for d in range(D):
+                        off = T.tempo_kv_element_offset(kv, which, blk, head, slot, d)
+                        base = (blk * Hkv + head) * Z * D
+                        grp, u = divmod(slot, 32)
+                        if which == 0:
+                            # K: lane (row + 16c) of unit (tile, s) holds dims 32s+8c..+7 of slot row
+                            tile, row = divmod(u, 16)
+                            s, rem = divmod(d, 32)
+                            c, e = divmod(rem, 8)
+                            unit, lane = tile * (D // 32) + s, c * 16 + row
+                        else:
+                            # V: lane (n + 16c) of unit dt holds dim 16dt+n of slots {4c..4c+3, 16+4c..}
+                            half, uu = divmod(u, 16)
+                            c, e = uu // 4, uu % 4 + 4 * half
+                            unit, nn = divmod(d, 16)
+                            lane = c * 16 + nn
+                        assert off == base + grp * 32 * D + (unit * 64 + lane) * 8 + e
+                        seen[off] = True
+        assert seen.all()
+    kvf = kv_desc(T.TEMPO_F32, D=D, Z=Z, Hkv=Hkv, num_blocks=NB)
+    assert T.tempo_kv_pool_bytes(kvf) == n * 4
+    assert T.tempo_kv_element_offset(kvf, 0, 2, 1, 5, 7) == ((2 * Hkv + 1) * Z + 5) * D + 7
+    assert T.tempo_kv_element_offset(kvf, 1, 2, 1, 5, 7) == ((2 * Hkv + 1) * Z + 5) * D + 7
+    assert T.tempo_kv_element_offset(kv, 0, NB, 0, 0, 0) == -1
+    assert T.tempo_kv_element_offset(kv, 0, 0, 0, Z, 0) == -1
+    assert T.tempo_kv_element_offset(kv, 2, 0, 0, 0, 0) == -1
+
+
+def test_plan_covers_every_step_and_workspace_bound_holds():
+    for dtype, hq_hkv in ((T.TEMPO_BF16, (24, 8)), (T.TEMPO_F32, (8, 2)), (T.TEMPO_BF16, (4, 4))):
+        Hq, Hkv = hq_hkv
+        for batch in (1, 3, 16, 64):
+            for max_t in (0, 31, 32, 511, 4095, 70000):
+                kv = kv_desc(dtype, Hkv=Hkv, Z=64, max_blocks=max_t // 64 + 1)
+                bound = T.tempo_attn_workspace_bytes(kv, batch, Hq, max_t)
+                assert bound > 0 and bound % 256 == 0
+                ts = sorted(set(list(range(0, min(max_t, 700) + 1, 7)) + [max_t, max_t // 2, max_t // 3]))
+                for t in ts:
+                    for w in (0, 1, 5, 512, 513):
+                        plan = T.tempo_attn_plan(kv, batch, Hq, t, w)
+                        tps = plan.tokens_per_split
+                        assert tps >= 32 and tps & (tps - 1) == 0
+                        assert plan.waves in (1, 2, 4, 8) and plan.waves * 32 <= max(tps, 32)
+                        lo = 0 if w == 0 else max(0, t - w + 1)
+                        assert plan.num_splits >= t // tps - lo // tps + 1
+                        # any earlier step of a ragged batch is covered too
+                        for t2 in (t, t // 2, max(0, t - 17)):
+                            lo2 = 0 if w == 0 else max(0, t2 - w + 1)
+                            assert plan.num_splits >= t2 // tps - lo2 // tps + 1
+                        assert plan.num_splits <= 1024
+                        assert T.tempo_attn_plan_workspace_bytes(kv, batch, Hq, plan) <= bound
+
+
+def test_bad_arguments_are_refused_before_any_launch():
+    lib = T.load()
+    good = kv_desc(T.TEMPO_BF16)
+    fake = 1 << 20   # a non-NULL address that is never dereferenced: validation fails first
+
+    def append(kv, k=fake, v=fake, batch=2, t=5):
+        return lib.tempo_kv_append(ctypes.byref(kv), k, v, batch, t, None, None)
+
+    assert append(kv_desc(T.TEMPO_BF16, pools=(None, 1, 1))) == T.TEMPO_ERR_NULL
+    assert append(good, k=None) == T.TEMPO_ERR_NULL
+    assert append(kv_desc(7)) == T.TEMPO_ERR_DTYPE
+    assert append(kv_desc(T.TEMPO_BF16, D=96)) == T.TEMPO_ERR_SHAPE
+    assert append(kv_desc(T.TEMPO_BF16, Z=48)) == T.TEMPO_ERR_SHAPE
+    assert append(kv_desc(T.TEMPO_BF16, Z=16)) == T.TEMPO_ERR_SHAPE
+    assert append(good, batch=0) == T.TEMPO_ERR_SHAPE
+    assert append(good, t=-1) == T.TEMPO_ERR_RANGE
+    assert append(good, t=4 * 64) == T.TEMPO_ERR_RANGE          # needs a fifth block of four
+
+    def causal(kv, Hq=6, t=5, ws=fake << 4, ws_bytes=1 << 30, q=fake, out=fake):
+        return lib.tempo_attn_decode_causal(ctypes.byref(kv), q, out, 2, Hq, t, None, 0.1, ws, ws_bytes, None)
+
+    assert causal(good, Hq=5) == T.TEMPO_ERR_SHAPE              # not a multiple of Hkv
+    assert causal(good, Hq=2 * 17) == T.TEMPO_ERR_SHAPE         # group larger than 16
+    assert causal(good, q=None) == T.TEMPO_ERR_NULL
+    assert causal(good, t=1000) == T.TEMPO_ERR_RANGE
+    assert causal(good, ws=None) == T.TEMPO_ERR_WORKSPACE
+    assert causal(good, ws=(fake << 4) + 8) == T.TEMPO_ERR_WORKSPACE     # misaligned
+    assert causal(good, ws_bytes=16) == T.TEMPO_ERR_WORKSPACE
+
+    def window(kv, w):
+        return lib.tempo_attn_decode_window(ctypes.byref(kv), fake, fake, 2, 6, 5, None, w, 0.1, fake << 4,
+                                            1 << 30, None)
+
+    assert window(good, 0) == T.TEMPO_ERR_RANGE
+    assert window(good, -3) == T.TEMPO_ERR_RANGE
+
+    bad_plan = T.tempo_plan(48, 1, 1)
+    assert lib.tempo_attn_decode_partial(ctypes.byref(good), fake, 2, 6, 5, None, 0, 0.1,
+                                         ctypes.byref(bad_plan), fake << 4, 1 << 30, None) == T.TEMPO_ERR_SHAPE
+    short_plan = T.tempo_plan(32, 1, 1)                          # step 100 needs 4 splits of 32
+    assert lib.tempo_attn_decode_partial(ctypes.byref(good), fake, 2, 6, 100, None, 0, 0.1,
+                                         ctypes.byref(short_plan), fake << 4, 1 << 30, None) == T.TEMPO_ERR_RANGE
+    assert lib.tempo_kv_gather(ctypes.byref(good), fake, fake, 2, 0, 4 * 64 + 1, None) == T.TEMPO_ERR_RANGE
+    assert T.tempo_attn_workspace_bytes(kv_desc(T.TEMPO_BF16, D=96), 2, 6, 100) == 0
+    assert "workspace" in T.tempo_strerror(T.TEMPO_ERR_WORKSPACE)
