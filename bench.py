@@ -1,0 +1,240 @@
+#!/usr/bin/env python3
+"""Benchmark of the decode-attention hot path on one MI355X.
+
+Workload (the configuration the metric is quoted on): Llama-3.2-3B attention
+layer shape, bf16 -- batch 16, 24 query heads, 8 key/value heads, head_dim 128,
+key/value blocks of 256 -- causal decode at step t = 4095.  One "step" is one
+pass of the whole path for one layer: tempo_kv_append of step t's key/value, the
+partial-attention launch over keys 0..t, and the split combine.  Successive steps
+rotate over several layers' pools (a decode step of a real model visits every
+layer's keys/values once), so the key/value bytes of a step are not left in the
+last-level cache by the previous one.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+Prints ONE JSON line.  value = key/value GB/s = algorithmic key/value bytes read
+per step (batch * (t+1) * 2 * Hkv * D * 2 bytes) / mean step time, inputs resident
+in HBM.  "roofline" prices the dominant kernel (partial attention) against the
+8 TB/s HBM peak from its own HIP-event durations inside the same run;
+"cpu_baseline" is the fp64 oracle timed on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+# HBM bytes per launch of the partial-attention kernel at the benchmark workload,
+# from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/), scaled by what
+# the same counters read for a copy kernel of known size.  None until measured.
+MEASURED_TRAFFIC_BYTES = None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--layers", type=int, default=8, help="pools rotated over (cache defeat)")
+    ap.add_argument("--no-extras", action="store_true", help="skip the per-t curve and whole-run legs")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+              "use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2501_05408_amd import synth
+    from paper_2501_05408_amd import tempo as T
+    from paper_2501_05408_amd.store import BlockStore
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    T.load()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    B, Hq, Hkv, D, Z, t = 16, 24, 8, 128, 256, 4095
+    R = args.layers
+    T_len = t + 1
+    scale = 1.0 / math.sqrt(D)
+    kv_bytes_per_token = 2 * Hkv * D * 2                      # K and V, bf16
+    step_bytes = B * T_len * kv_bytes_per_token               # 256 MiB at t = 4095
+
+    # --- build R layers: flat K/V drawn on the GPU, written through the ABI -------
+    stores, keep_flat = [], None
+    for layer in range(R):
+        K = synth.device_normal((B, T_len, Hkv, D), 1000 + 2 * layer, torch.bfloat16, dev)
+        V = synth.device_normal((B, T_len, Hkv, D), 1001 + 2 * layer, torch.bfloat16, dev)
+        perm = synth.permutation(7, layer, B * (T_len // Z))
+        table = torch.from_numpy(perm.reshape(B, T_len // Z).copy())
+        st = BlockStore(B, Hq, Hkv, D, Z, t, T.TEMPO_BF16, device=dev, block_table=table)
+        st.prefill(K, V, t - 1)
+        st.k_last, st.v_last = K[:, t].contiguous(), V[:, t].contiguous()
+        stores.append(st)
+        if layer == 0:
+            keep_flat = (K, V)
+    q = synth.device_normal((B, Hq, D), 99, torch.bfloat16, dev)
+    outs = [st.new_out() for st in stores]
+    torch.cuda.synchronize()
+
+    def step(i):
+        st = stores[i % R]
+        st.append(st.k_last, st.v_last, t)
+        st.attend_causal(q, outs[i % R], t)
+
+    # --- the timed region: W warm-up steps, then exactly K steps -------------------
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+    value = step_bytes / (elapsed / args.steps) / 1e9
+
+    # --- the dominant kernel alone, HIP events on the launch stream, same steps ----
+    plan = T.tempo_attn_plan(stores[0].kv, B, Hq, t, 0)
+    ws_bytes = stores[0].workspace_bytes
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(args.steps)]
+    for i in range(args.steps):
+        st = stores[i % R]
+        st.append(st.k_last, st.v_last, t)
+        ev[i][0].record()
+        T.tempo_attn_decode_partial(st.kv, q, B, Hq, t, None, 0, scale, plan, st.workspace, ws_bytes)
+        ev[i][1].record()
+        T.tempo_attn_decode_combine(st.kv, outs[i % R], B, Hq, t, None, 0, plan, st.workspace, ws_bytes)
+    torch.cuda.synchronize()
+    kernel_ms = [a.elapsed_time(b) for a, b in ev]
+    kernel_avg_ms = sum(kernel_ms) / len(kernel_ms)
+    achieved = step_bytes / (kernel_avg_ms * 1e-3) / 1e9
+
+    result = {
+        "metric": "decode-attention KV GB/s (% of HBM peak) + steps/s, Llama-3.2-3B shape",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": "llama-3.2-3b attention-layer shape, causal decode at t=4095 "
+                        "(append + partial attention + split combine per step)",
+            "batch": B, "num_q_heads": Hq, "num_kv_heads": Hkv, "head_dim": D, "kv_block": Z,
+            "t": t, "layers_rotated": R, "kv_bytes_per_step": step_bytes,
+            "plan": {"tokens_per_split": plan.tokens_per_split, "num_splits": plan.num_splits,
+                     "waves": plan.waves},
+        },
+        "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
+        "steps_per_s": round(args.steps / elapsed, 1),
+        "roofline": {
+            "kernel": "attn_partial_bf16<128>",
+            "bound": "hbm",
+            "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "traffic": MEASURED_TRAFFIC_BYTES,
+            "kernel_avg_us": round(kernel_avg_ms * 1e3, 2),
+            "kernel_min_us": round(min(kernel_ms) * 1e3, 2),
+            "algorithmic_bytes_per_launch": step_bytes,
+        },
+    }
+
+    # --- parity spot check of the timed configuration (sampled outputs) ------------
+    from oracle import tempo_oracle as oracle
+
+    K0, V0 = keep_flat
+    sample_b = [0, 7, 15]
+    got = outs[0].float().cpu().numpy().astype(np.float64)
+    K64 = K0[sample_b].float().cpu().numpy().astype(np.float64)
+    V64 = V0[sample_b].float().cpu().numpy().astype(np.float64)
+    q64 = q[sample_b].float().cpu().numpy().astype(np.float64)
+    ref = oracle.attend(q64, K64, V64, t, 0, scale)
+    err = float(np.abs(got[sample_b] - ref).max())
+    result["parity"] = {"max_abs_err": err, "ok": bool(err <= 2e-2 and err <= 1e-2 * np.abs(ref).max()),
+                        "sequences": sample_b}
+
+    # --- CPU baseline: the oracle on this machine's host cores --------------------------
+    if not args.no_cpu:
+        Kc = K0.float().cpu().numpy().astype(np.float64)
+        Vc = V0.float().cpu().numpy().astype(np.float64)
+        qc = q.float().cpu().numpy().astype(np.float64)
+        times = []
+        budget_end = time.perf_counter() + 12.0
+        while len(times) < 3 or (time.perf_counter() < budget_end and len(times) < 50):
+            c0 = time.perf_counter()
+            oracle.attend(qc, Kc, Vc, t, 0, scale)
+            times.append(time.perf_counter() - c0)
+        med = sorted(times)[len(times) // 2]
+        result["cpu_baseline"] = {
+            "value": round(step_bytes / med / 1e9, 3),
+            "unit": "GB/s",
+            "cores": oracle.threads(),
+            "kind": "oracle",
+            "sample": f"full batch of 16 sequences at t=4095 (one layer, attention only), "
+                      f"median of {len(times)} runs, {med * 1e3:.1f} ms per step",
+        }
+        del Kc, Vc
+
+    # --- extras: per-t curve and a whole decode run with real per-step appends ------
+    if not args.no_extras:
+        curve = {}
+        for tt in (255, 511, 1023, 2047, 4095):
+            n = 100
+            for i in range(10):
+                stores[i % R].attend_causal(q, outs[i % R], tt)
+            torch.cuda.synchronize()
+            c0 = time.perf_counter()
+            for i in range(n):
+                st = stores[i % R]
+                st.append(st.k_last, st.v_last, tt)
+                st.attend_causal(q, outs[i % R], tt)
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - c0) / n
+            curve[str(tt)] = {"us_per_step": round(dt * 1e6, 2),
+                              "kv_gbs": round(B * (tt + 1) * kv_bytes_per_token / dt / 1e9, 1)}
+        result["curve_t"] = curve
+        # whole run t = 0..4095 on one layer: append step t, attend step t
+        K0c, V0c = K0.transpose(0, 1).contiguous(), V0.transpose(0, 1).contiguous()  # [T][B][Hkv][D]
+        st = stores[0]
+        torch.cuda.synchronize()
+        c0 = time.perf_counter()
+        for tt in range(T_len):
+            st.append(K0c[tt], V0c[tt], tt)
+            st.attend_causal(q, outs[0], tt)
+        torch.cuda.synchronize()
+        run = time.perf_counter() - c0
+        total_bytes = B * kv_bytes_per_token * T_len * (T_len + 1) // 2
+        result["whole_run"] = {"steps": T_len, "seconds": round(run, 4),
+                               "steps_per_s": round(T_len / run, 1),
+                               "kv_gbs": round(total_bytes / run / 1e9, 1),
+                               "note": "one layer, 256 MiB pool (partly cache resident at small t)"}
+
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
