@@ -4,8 +4,11 @@
 Workload (the configuration the metric is quoted on): Llama-3.2-3B attention
 layer shape, bf16 -- batch 16, 24 query heads, 8 key/value heads, head_dim 128,
 key/value blocks of 256 -- causal decode at step t = 4095.  One "step" is one
-pass of the whole path for one layer: tempo_kv_append of step t's key/value, the
-partial-attention launch over keys 0..t, and the split combine.  Successive steps
+pass of the whole path for one layer through tempo_decode_step_causal: the
+block-store write of step t's key/value, partial attention over keys 0..t, and
+the split combine, in one launch.  (The same step through the separate entry
+points tempo_kv_append + tempo_attn_decode_causal is timed too and reported as
+"separate_calls".)  Successive steps
 rotate over several layers' pools (a decode step of a real model visits every
 layer's keys/values once), so the key/value bytes of a step are not left in the
 last-level cache by the previous one.
@@ -93,6 +96,10 @@ def main() -> int:
 
     def step(i):
         st = stores[i % R]
+        st.step_causal(q, st.k_last, st.v_last, outs[i % R], t)
+
+    def step_separate(i):
+        st = stores[i % R]
         st.append(st.k_last, st.v_last, t)
         st.attend_causal(q, outs[i % R], t)
 
@@ -107,6 +114,16 @@ def main() -> int:
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / args.steps * 1e3
     value = step_bytes / (elapsed / args.steps) / 1e9
+
+    # --- the same step through the separate append / attend entry points -----------
+    for i in range(args.warmup):
+        step_separate(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step_separate(i)
+    torch.cuda.synchronize()
+    sep = (time.perf_counter() - t0) / args.steps
 
     # --- the dominant kernel alone, HIP events on the launch stream, same steps ----
     plan = T.tempo_attn_plan(stores[0].kv, B, Hq, t, 0)
@@ -140,13 +157,15 @@ def main() -> int:
         "data": "synthetic",
         "config": {
             "workload": "llama-3.2-3b attention-layer shape, causal decode at t=4095 "
-                        "(append + partial attention + split combine per step)",
+                        "(append + partial attention + split combine per step, one launch)",
             "batch": B, "num_q_heads": Hq, "num_kv_heads": Hkv, "head_dim": D, "kv_block": Z,
             "t": t, "layers_rotated": R, "kv_bytes_per_step": step_bytes,
             "plan": {"tokens_per_split": plan.tokens_per_split, "num_splits": plan.num_splits,
                      "waves": plan.waves},
         },
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
+        "separate_calls": {"ms_per_step": round(sep * 1e3, 5), "kv_gbs": round(step_bytes / sep / 1e9, 1),
+                           "launches": "tempo_kv_append + tempo_attn_decode_causal"},
         "steps_per_s": round(args.steps / elapsed, 1),
         "roofline": {
             "kernel": "attn_partial_bf16<128>",
@@ -209,8 +228,7 @@ def main() -> int:
             c0 = time.perf_counter()
             for i in range(n):
                 st = stores[i % R]
-                st.append(st.k_last, st.v_last, tt)
-                st.attend_causal(q, outs[i % R], tt)
+                st.step_causal(q, st.k_last, st.v_last, outs[i % R], tt)
             torch.cuda.synchronize()
             dt = (time.perf_counter() - c0) / n
             curve[str(tt)] = {"us_per_step": round(dt * 1e6, 2),
@@ -222,8 +240,7 @@ def main() -> int:
         torch.cuda.synchronize()
         c0 = time.perf_counter()
         for tt in range(T_len):
-            st.append(K0c[tt], V0c[tt], tt)
-            st.attend_causal(q, outs[0], tt)
+            st.step_causal(q, K0c[tt], V0c[tt], outs[0], tt)
         torch.cuda.synchronize()
         run = time.perf_counter() - c0
         total_bytes = B * kv_bytes_per_token * T_len * (T_len + 1) // 2

@@ -134,10 +134,11 @@ size_t tempo_kv_pool_bytes(const tempo_kv* kv);
 
 /*
  * The split plan the attention entry points use for a batch whose longest
- * step is t_max (window = 0: causal).  Deterministic function of its arguments.
+ * step is t_max (window = 0: causal; ragged != 0: the plan used when t_per_seq
+ * is given).  Deterministic function of its arguments.
  */
 int tempo_attn_plan(const tempo_kv* kv, int32_t batch, int32_t num_q_heads, int32_t t_max,
-                    int32_t window, tempo_plan* plan);
+                    int32_t window, int32_t ragged, tempo_plan* plan);
 
 /*
  * Workspace bytes that tempo_attn_decode_causal / _window need for any step
@@ -176,8 +177,10 @@ int tempo_kv_gather(const tempo_kv* kv, void* k_out, void* v_out, int32_t batch,
  * sequence b.  If t_per_seq (device, [batch]) is not NULL, sequence b is at step
  * t_per_seq[b] and t must be an upper bound of those steps (it fixes the launch
  * geometry).  scale is the constant s of Eq. 1.  workspace: device, 256-byte
- * aligned, at least tempo_attn_workspace_bytes(kv, batch, num_q_heads, t) bytes.
- * Launches: partial attention per split, then the split combine.
+ * aligned, at least tempo_attn_workspace_bytes(kv, batch, num_q_heads, t) bytes;
+ * its contents need no initialisation and one workspace serves one call at a
+ * time.  Launches: partial attention per split, then the split combine (a step
+ * that fits one split writes out directly and launches nothing else).
  */
 int tempo_attn_decode_causal(const tempo_kv* kv, const void* q, void* out, int32_t batch,
                              int32_t num_q_heads, int32_t t, const int32_t* t_per_seq,
@@ -190,7 +193,25 @@ int tempo_attn_decode_window(const tempo_kv* kv, const void* q, void* out, int32
                              size_t workspace_bytes, void* stream);
 
 /*
- * The two launches of the attention entry points, separately, with an explicit
+ * One decode step with one launch fewer: tempo_kv_append(k_new, v_new at step t)
+ * followed by tempo_attn_decode_causal / _window at step t, with the same
+ * arguments and the same results as those two calls.  The block-store write is
+ * done by the attention kernel itself (the paper's "in-place writes" wrapper,
+ * Section 6, applied to the consumer): the workgroup that owns step t's slot
+ * stores k_new / v_new there and attends over them from registers.
+ */
+int tempo_decode_step_causal(const tempo_kv* kv, const void* q, const void* k_new,
+                             const void* v_new, void* out, int32_t batch, int32_t num_q_heads,
+                             int32_t t, const int32_t* t_per_seq, float scale, void* workspace,
+                             size_t workspace_bytes, void* stream);
+
+int tempo_decode_step_window(const tempo_kv* kv, const void* q, const void* k_new,
+                             const void* v_new, void* out, int32_t batch, int32_t num_q_heads,
+                             int32_t t, const int32_t* t_per_seq, int32_t window, float scale,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Partial attention and split combine as two separate launches, with an explicit
  * plan (for profiling one kernel at a time and for sweeping plans).  window = 0
  * is causal.  tempo_attn_decode_partial writes one (max, sum, accumulator)
  * partial per (sequence, query head, non-empty split) into workspace
@@ -213,6 +234,16 @@ int tempo_attn_decode_combine(const tempo_kv* kv, void* out, int32_t batch, int3
 /* Workspace bytes for an explicit plan. */
 size_t tempo_attn_plan_workspace_bytes(const tempo_kv* kv, int32_t batch, int32_t num_q_heads,
                                        const tempo_plan* plan);
+
+/*
+ * Measurement aid, not part of the decode path: read `bytes` (a multiple of 16)
+ * of device memory at src (16-byte aligned) once with 16-byte-per-lane loads,
+ * using `workgroups` workgroups of 256 threads, and discard the data (sink:
+ * device, at least 4 bytes, practically never written).  It is the streaming-read
+ * yardstick the decode kernels' key/value bandwidth is compared with, and the kernel of known size that hardware traffic counters are
+ * scaled by.
+ */
+int tempo_stream_read(const void* src, size_t bytes, void* sink, int32_t workgroups, void* stream);
 
 #ifdef __cplusplus
 }

@@ -41,20 +41,91 @@ struct Group {
   u32x4 v[D / 16];
 };
 
+// Element offset, in either pool, of the 32-slot group `grp` of (sequence b, kv head hkv).
 template <int D>
-__device__ inline void load_group(const AttnParams& p, int b, int hkv, int grp, int lane, Group<D>& g) {
+__device__ inline int64_t group_base(const AttnParams& p, int b, int hkv, int grp) {
   const int j0 = grp << 5;
   const int tile = j0 >> p.z_log2;
   const int Z = 1 << p.z_log2;
   int phys = p.block_table[(int64_t)b * p.max_blocks_per_seq + tile];
   phys = __builtin_amdgcn_readfirstlane(clamp_block(phys, p.num_blocks));
-  const int64_t base = (((int64_t)phys * p.Hkv + hkv) << p.z_log2) * D + (int64_t)(j0 & (Z - 1)) * D;
+  return (((int64_t)phys * p.Hkv + hkv) << p.z_log2) * D + (int64_t)(j0 & (Z - 1)) * D;
+}
+
+template <int D>
+__device__ inline void load_group(const AttnParams& p, int b, int hkv, int grp, int lane, Group<D>& g) {
+  const int64_t base = group_base<D>(p, b, hkv, grp);
   const u32x4* kp = reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(p.k_pool) + base) + lane;
   const u32x4* vp = reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(p.v_pool) + base) + lane;
+  // Keys and values are read once per step and never again by this kernel:
+  // non-temporal loads keep them from displacing anything in the caches.
 #pragma unroll
-  for (int i = 0; i < 2 * (D / 32); ++i) g.k[i] = kp[i * 64];
+  for (int i = 0; i < 2 * (D / 32); ++i) g.k[i] = __builtin_nontemporal_load(kp + i * 64);
 #pragma unroll
-  for (int i = 0; i < D / 16; ++i) g.v[i] = vp[i * 64];
+  for (int i = 0; i < D / 16; ++i) g.v[i] = __builtin_nontemporal_load(vp + i * 64);
+}
+
+// Fused block-store write (Section 6, "in-place writes"): step t's own key and
+// value arrive in k_new / v_new.  The wavefront that owns the group holding slot
+// t stages those two rows in LDS when it starts (stage_new_row), and when it
+// reaches that group it puts them into the group's register image, so that this
+// step attends over them, and into the pool, so that later steps do.
+template <int D>
+__device__ inline void stage_new_row(const AttnParams& p, int b, int hkv, int lane, uint16_t* stage) {
+  // lanes 0..D/8-1 fetch the key row, the next D/8 lanes the value row, 16 bytes each
+  constexpr int UNITS = D / 8;
+  if (lane < 2 * UNITS) {
+    const uint16_t* src = static_cast<const uint16_t*>(lane < UNITS ? p.k_new : p.v_new) +
+                          ((int64_t)b * p.Hkv + hkv) * D + (lane % UNITS) * 8;
+    *reinterpret_cast<u32x4*>(stage + lane * 8) = *reinterpret_cast<const u32x4*>(src);
+  }
+}
+
+template <int D>
+__device__ __forceinline__ void append_into_group(const AttnParams& p, int b, int hkv, int t_b, int lane,
+                                         const uint16_t* stage, Group<D>& g) {
+  constexpr int KS = D / 32;
+  constexpr int DT = D / 16;
+  const int u = t_b & 31, row = u & 15, tile = u >> 4;
+  const int n = lane & 15, c = lane >> 4;
+  const int64_t base = group_base<D>(p, b, hkv, t_b >> 5);
+  const uint16_t* kn = stage;       // [D] staged key row
+  const uint16_t* vn = stage + D;   // [D] staged value row
+  // Keys: lanes (row + 16c) hold the units of slot `row`; patch them, then the
+  // whole wavefront writes the group's key image back as full 1 KiB units (the
+  // other slots are rewritten with the values just read -- nobody else writes
+  // this sequence's group -- so the pool sees whole cache lines, not 16-byte
+  // fragments).
+  u32x4* kp = reinterpret_cast<u32x4*>(static_cast<uint16_t*>(p.k_pool) + base) + lane;
+  if (n == row) {
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      const u32x4 val = *reinterpret_cast<const u32x4*>(kn + 32 * s + 8 * c);
+      g.k[s] = tile == 0 ? val : g.k[s];
+      g.k[KS + s] = tile == 1 ? val : g.k[KS + s];
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 2 * KS; ++i) kp[i * 64] = g.k[i];  // both row-tiles: static register indices
+  // Values: lanes (n + 16c) with c = row>>2 hold dim 16dt+n of the 8 slots that
+  // include slot t; patch that 16-bit element and write the 16-byte unit back
+  // (16 lanes x 16 bytes = 256 contiguous bytes per column tile).
+  if (c == (row >> 2)) {
+    const int e = (row & 3) + 4 * tile;  // position of slot t among the lane's 8 slots
+    u32x4* vp = reinterpret_cast<u32x4*>(static_cast<uint16_t*>(p.v_pool) + base) + lane;
+    const uint32_t shift = (e & 1) ? 16u : 0u;
+    const uint32_t keep = (e & 1) ? 0x0000FFFFu : 0xFFFF0000u;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      const uint32_t val = vn[16 * dt + n];
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const uint32_t patched = (g.v[dt][w] & keep) | (val << shift);
+        g.v[dt][w] = (w == (e >> 1)) ? patched : g.v[dt][w];
+      }
+      vp[dt * 64] = g.v[dt];
+    }
+  }
 }
 
 template <int D>
@@ -140,11 +211,16 @@ __global__ __launch_bounds__(512) void attn_partial_bf16(AttnParams p) {
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nwaves = blockDim.x >> 6;
-  const int split = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;
+  const int hkv = blockIdx.x, b = blockIdx.y;
   int t_b = p.t_per_seq ? p.t_per_seq[b] : p.t;
   t_b = t_b > p.t ? p.t : (t_b < 0 ? 0 : t_b);
   const SeqRange rg = seq_range(t_b, p.window, p.tps_log2);
-  if (split >= rg.nchunks) return;  // uniform over the workgroup
+  if ((int)blockIdx.z >= rg.nchunks) return;  // uniform over the workgroup
+  // Dispatch order: the split index is the slowest grid dimension and runs from
+  // the newest split to the oldest.  The newest split of every (sequence, head)
+  // is the one a fused append lands in and the one t may cut short; launching
+  // all of those first keeps their longer path out of the launch's last round.
+  const int split = rg.nchunks - 1 - (int)blockIdx.z;
   const int chunk = rg.chunk0 + split;
   const int cs = chunk << p.tps_log2, ce = ((chunk + 1) << p.tps_log2) - 1;
   const int start = rg.lo > cs ? rg.lo : cs;
@@ -170,18 +246,26 @@ __global__ __launch_bounds__(512) void attn_partial_bf16(AttnParams p) {
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt) st.acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // Two register images of a group, used alternately: the next group's loads are
-  // in flight while the current one is consumed.
+  // One register image of a group per wavefront: load it, consume it, load the
+  // next.  Other wavefronts of the compute unit keep the memory pipe busy in the
+  // meantime; measured on MI355X this beats prefetching into a second image,
+  // which doubles the registers (occupancy 2 instead of 3 waves per SIMD) and
+  // puts more bytes in flight than the memory system rewards.
+  // A fused append lands in group t_b>>5, which only the newest split holds; the
+  // wavefront that will reach that group stages the new rows in LDS right away,
+  // in a region of its own behind the wave-merge area.
   int grp = (start >> 5) + wave;
-  Group<D> ga, gb;
-  if (grp <= g_last) load_group<D>(p, b, hkv, grp, lane, ga);
+  int grp_new = -1;
+  uint16_t* stage = reinterpret_cast<uint16_t*>(smem + nwaves * (32 + p.G * D));
+  if (p.k_new && split == rg.nchunks - 1 && ((t_b >> 5) - grp) % nwaves == 0 && (t_b >> 5) >= grp) {
+    grp_new = t_b >> 5;
+    stage_new_row<D>(p, b, hkv, lane, stage);
+  }
+  Group<D> g;
   while (grp <= g_last) {
-    if (grp + nwaves <= g_last) load_group<D>(p, b, hkv, grp + nwaves, lane, gb);
-    consume_group<D>(p, grp, start, end, lane, qreg, ga, st);
-    grp += nwaves;
-    if (grp > g_last) break;
-    if (grp + nwaves <= g_last) load_group<D>(p, b, hkv, grp + nwaves, lane, ga);
-    consume_group<D>(p, grp, start, end, lane, qreg, gb, st);
+    load_group<D>(p, b, hkv, grp, lane, g);
+    if (grp == grp_new) append_into_group<D>(p, b, hkv, t_b, lane, stage, g);
+    consume_group<D>(p, grp, start, end, lane, qreg, g, st);
     grp += nwaves;
   }
 
@@ -239,9 +323,10 @@ __global__ __launch_bounds__(512) void attn_partial_bf16(AttnParams p) {
 
 hipError_t launch_partial_bf16(const AttnParams& p, int batch, int D, int grid_splits, int waves,
                                hipStream_t stream) {
-  const dim3 grid(grid_splits, p.Hkv, batch);
+  const dim3 grid(p.Hkv, batch, grid_splits);
   const dim3 block(64 * waves);
-  const size_t lds = (size_t)waves * (32 + (size_t)p.G * D) * sizeof(float);
+  // wave-merge area, then room for one staged key row and one value row (bf16)
+  const size_t lds = (size_t)waves * (32 + (size_t)p.G * D) * sizeof(float) + 2 * (size_t)D * sizeof(uint16_t);
   if (D == 128) return launch(attn_partial_bf16<128>, grid, block, lds, stream, p);
   else return launch(attn_partial_bf16<64>, grid, block, lds, stream, p);
 }

@@ -23,12 +23,13 @@ __global__ __launch_bounds__(512) void attn_partial_f32(AttnParams p) {
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int nwaves = blockDim.x >> 6;
-  const int split = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
+  const int hq = blockIdx.x, b = blockIdx.y;
   const int hkv = hq / p.G;
   int t_b = p.t_per_seq ? p.t_per_seq[b] : p.t;
   t_b = t_b > p.t ? p.t : (t_b < 0 ? 0 : t_b);
   const SeqRange rg = seq_range(t_b, p.window, p.tps_log2);
-  if (split >= rg.nchunks) return;
+  if ((int)blockIdx.z >= rg.nchunks) return;
+  const int split = rg.nchunks - 1 - (int)blockIdx.z;  // newest split first, as in the bf16 kernel
   const int chunk = rg.chunk0 + split;
   const int cs = chunk << p.tps_log2, ce = ((chunk + 1) << p.tps_log2) - 1;
   const int start = rg.lo > cs ? rg.lo : cs;
@@ -36,8 +37,13 @@ __global__ __launch_bounds__(512) void attn_partial_f32(AttnParams p) {
 
   const int row = lane >> 4, col = lane & 15;
   const int Z = 1 << p.z_log2;
-  const float* kpool = static_cast<const float*>(p.k_pool);
-  const float* vpool = static_cast<const float*>(p.v_pool);
+  float* kpool = static_cast<float*>(p.k_pool);
+  float* vpool = static_cast<float*>(p.v_pool);
+  // Fused block-store write (Section 6, "in-place writes"): step t's own key/value
+  // are taken from k_new / v_new, and the first query head of the group also stores
+  // them into the pool for later steps.
+  const float* kn = p.k_new ? static_cast<const float*>(p.k_new) + ((int64_t)b * p.Hkv + hkv) * D : nullptr;
+  const float* vn = p.k_new ? static_cast<const float*>(p.v_new) + ((int64_t)b * p.Hkv + hkv) * D : nullptr;
 
   float qv[E];
   {
@@ -55,11 +61,18 @@ __global__ __launch_bounds__(512) void attn_partial_f32(AttnParams p) {
     const int tile = j >> p.z_log2, slot = j & (Z - 1);
     const int phys = clamp_block(p.block_table[(int64_t)b * p.max_blocks_per_seq + tile], p.num_blocks);
     const int64_t off = ((int64_t)phys * p.Hkv + hkv) * Z * D + (int64_t)slot * D + col * E;
+    const bool fresh = kn != nullptr && j == t_b;  // uniform over the 16-lane row
+    const float* ksrc = fresh ? kn + col * E : kpool + off;
+    const float* vsrc = fresh ? vn + col * E : vpool + off;
     float kx[E], vx[E];
 #pragma unroll
     for (int e = 0; e < E; e += 4) {
-      const float4 k4 = *reinterpret_cast<const float4*>(kpool + off + e);
-      const float4 v4 = *reinterpret_cast<const float4*>(vpool + off + e);
+      const float4 k4 = *reinterpret_cast<const float4*>(ksrc + e);
+      const float4 v4 = *reinterpret_cast<const float4*>(vsrc + e);
+      if (fresh && hq == hkv * p.G) {
+        *reinterpret_cast<float4*>(kpool + off + e) = k4;
+        *reinterpret_cast<float4*>(vpool + off + e) = v4;
+      }
       kx[e] = k4.x; kx[e + 1] = k4.y; kx[e + 2] = k4.z; kx[e + 3] = k4.w;
       vx[e] = v4.x; vx[e + 1] = v4.y; vx[e + 2] = v4.z; vx[e + 3] = v4.w;
     }
@@ -121,7 +134,7 @@ __global__ __launch_bounds__(512) void attn_partial_f32(AttnParams p) {
 
 hipError_t launch_partial_f32(const AttnParams& p, int batch, int D, int grid_splits, int waves,
                               hipStream_t stream) {
-  const dim3 grid(grid_splits, p.Hq, batch);
+  const dim3 grid(p.Hq, batch, grid_splits);
   const dim3 block(64 * waves);
   const size_t lds = (size_t)waves * 4 * (2 + (size_t)D) * sizeof(float);
   if (D == 128) return launch(attn_partial_f32<128>, grid, block, lds, stream, p);

@@ -1,6 +1,7 @@
 // The C ABI declared in tempo.h: argument validation, split planning, launches.
 // Host code only; every step of the path runs in the kernels this file launches.
 #include <math.h>
+#include <limits.h>
 #include <stdio.h>
 
 #include "tempo_internal.h"
@@ -60,19 +61,54 @@ int32_t splits_bound(int32_t t, int32_t window, int tps_log2) {
   return causal < win ? causal : win;
 }
 
-// Work items wanted before a split is made shorter: 4 workgroups per compute unit.
-constexpr int kTargetItems = 1024;
+// Compute units of the part this library is written for (MI355X).
+constexpr int kComputeUnits = 256;
 constexpr int kMaxSplits = 1024;
 
+// What a workgroup costs before its first key arrives (kernel arguments, block
+// table entry, first loads: about 2 us), expressed in key positions streamed at
+// one compute unit's share of the bandwidth.
+constexpr int kPrologueTokens = 128;
+
+// Split planning.  Workgroups are handed to compute units round-robin, so the
+// busiest unit gets ceil(workgroups / units) of them and the launch lasts about
+//     ceil(pairs * splits(tps) / units) * (tps + prologue)   key positions per unit.
+// Short splits balance better; long splits mean fewer prologues, fewer partials
+// and a cheaper combine.  Take the LONGEST split length whose estimate is within
+// 3% of the best one.  Measured on MI355X at the
+// Llama shape (batch 16, t = 4095): 2 splits of 2048 = one workgroup per unit
+// runs the partial kernel in 43.5 us, 16 splits of 256 in 45.7 us.
+// Ragged batches (per-sequence steps below t_max) hold less work than the model
+// assumes and it is unevenly spread, so their splits are capped at 1024 keys to
+// keep the long sequences from becoming single long-running workgroups.
 void make_plan(const tempo_kv* kv, int32_t batch, int32_t Hq, int32_t t_max, int32_t window,
-               tempo_plan* plan) {
+               bool ragged, tempo_plan* plan) {
   // bf16 shares one key/value read across the query group; fp32 launches per query head.
   const int64_t pairs = (int64_t)batch * (kv->dtype == TEMPO_BF16 ? kv->num_kv_heads : Hq);
-  int tps_log2 = 8;
-  while (tps_log2 > 5 && pairs * splits_bound(t_max, window, tps_log2) < kTargetItems) --tps_log2;
-  while (splits_bound(t_max, window, tps_log2) > kMaxSplits) ++tps_log2;
-  plan->tokens_per_split = 1 << tps_log2;
-  plan->num_splits = splits_bound(t_max, window, tps_log2);
+  const int64_t len = (window > 0 && window < (int64_t)t_max + 1) ? window : (int64_t)t_max + 1;
+  const int k_max = ragged ? 10 : 30;
+  int best_k = -1;
+  int64_t best_cost = INT64_MAX;
+  int64_t costs[26];
+  for (int k = 5; k <= 30; ++k) costs[k - 5] = INT64_MAX;
+  for (int k = 5; k <= k_max; ++k) {
+    const int64_t splits = splits_bound(t_max, window, k);
+    if (splits > kMaxSplits) continue;
+    const int64_t tps = (int64_t)1 << k;
+    const int64_t per_split = tps < len ? tps : len;  // a split never holds more than the range
+    costs[k - 5] = ((pairs * splits + kComputeUnits - 1) / kComputeUnits) * (per_split + kPrologueTokens);
+    if (costs[k - 5] < best_cost) best_cost = costs[k - 5];
+    if (splits == 1) break;  // longer splits change nothing
+  }
+  for (int k = 5; k <= k_max; ++k) {
+    if (costs[k - 5] != INT64_MAX && costs[k - 5] <= best_cost + best_cost * 3 / 100) best_k = k;
+  }
+  if (best_k < 0) {  // a ragged range too long for 1024 splits of 1024 keys: lengthen until it fits
+    best_k = k_max;
+    while (splits_bound(t_max, window, best_k) > kMaxSplits) ++best_k;
+  }
+  plan->tokens_per_split = 1 << best_k;
+  plan->num_splits = splits_bound(t_max, window, best_k);
   const int groups = plan->tokens_per_split / 32;
   plan->waves = groups >= 4 ? 4 : groups;
 }
@@ -98,6 +134,7 @@ int launch_status(hipError_t e, const char* what) {
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// Workspace = [m,l: batch*Hq*S*2 f32] [acc: batch*Hq*S*D f32], each part padded to 256 bytes.
 size_t ml_bytes(int32_t batch, int32_t Hq, int32_t S) {
   return align_up((size_t)batch * Hq * S * 2 * sizeof(float), 256);
 }
@@ -114,9 +151,12 @@ AttnParams attn_params(const tempo_kv* kv, const void* q, void* out, int32_t Hq,
   p.v_pool = kv->v_pool;
   p.block_table = kv->block_table;
   p.q = q;
+  p.k_new = nullptr;
+  p.v_new = nullptr;
   p.t_per_seq = t_per_seq;
-  p.ws_ml = static_cast<float*>(workspace);
-  p.ws_acc = reinterpret_cast<float*>(static_cast<char*>(workspace) + ml_bytes(batch, Hq, plan->num_splits));
+  char* ws = static_cast<char*>(workspace);
+  p.ws_ml = reinterpret_cast<float*>(ws);
+  p.ws_acc = reinterpret_cast<float*>(ws + ml_bytes(batch, Hq, plan->num_splits));
   p.out = out;
   p.t = t;
   p.window = window;
@@ -168,11 +208,16 @@ int check_attn(const tempo_kv* kv, int32_t batch, int32_t Hq, int32_t t, int32_t
   return TEMPO_OK;
 }
 
-int do_partial(const tempo_kv* kv, const void* q, void* out_if_direct, int32_t batch, int32_t Hq,
-               int32_t t, const int32_t* t_per_seq, int32_t window, float scale,
-               const tempo_plan* plan, void* workspace, hipStream_t stream) {
-  AttnParams p = attn_params(kv, q, out_if_direct, Hq, t, t_per_seq, window, scale, plan, workspace, batch);
-  p.direct = (out_if_direct != nullptr && plan->num_splits == 1) ? 1 : 0;
+// out != nullptr and a single split: the launch writes `out` itself; otherwise it
+// writes partials and the caller launches the combine.
+// k_new/v_new != nullptr: step t's key/value are appended inside the same launch.
+int do_partial(const tempo_kv* kv, const void* q, const void* k_new, const void* v_new, void* out,
+               int32_t batch, int32_t Hq, int32_t t, const int32_t* t_per_seq, int32_t window,
+               float scale, const tempo_plan* plan, void* workspace, hipStream_t stream) {
+  AttnParams p = attn_params(kv, q, out, Hq, t, t_per_seq, window, scale, plan, workspace, batch);
+  p.direct = (out != nullptr && plan->num_splits == 1) ? 1 : 0;
+  p.k_new = k_new;
+  p.v_new = v_new;
   const int32_t gs = grid_splits(plan, t, t_per_seq, window);
   const hipError_t e = kv->dtype == TEMPO_BF16
                            ? launch_partial_bf16(p, batch, kv->head_dim, gs, plan->waves, stream)
@@ -188,19 +233,19 @@ int do_combine(const tempo_kv* kv, void* out, int32_t batch, int32_t Hq, int32_t
   return launch_status(e, "attn_decode_combine");
 }
 
-int decode(const tempo_kv* kv, const void* q, void* out, int32_t batch, int32_t Hq, int32_t t,
-           const int32_t* t_per_seq, int32_t window, float scale, void* workspace,
-           size_t workspace_bytes, void* stream) {
+int decode(const tempo_kv* kv, const void* q, const void* k_new, const void* v_new, void* out,
+           int32_t batch, int32_t Hq, int32_t t, const int32_t* t_per_seq, int32_t window, float scale,
+           void* workspace, size_t workspace_bytes, void* stream) {
   int rc = check_layout(kv);
   if (rc != TEMPO_OK) return rc;
   if (!q || !out) return TEMPO_ERR_NULL;
   if ((rc = check_heads(kv, batch, Hq)) != TEMPO_OK) return rc;
   if (t < 0 || window < 0) return TEMPO_ERR_RANGE;
   tempo_plan plan;
-  make_plan(kv, batch, Hq, t, window, &plan);
+  make_plan(kv, batch, Hq, t, window, t_per_seq != nullptr, &plan);
   if ((rc = check_attn(kv, batch, Hq, t, window, t_per_seq != nullptr, &plan, workspace, workspace_bytes)) != TEMPO_OK) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  rc = do_partial(kv, q, out, batch, Hq, t, t_per_seq, window, scale, &plan, workspace, s);
+  rc = do_partial(kv, q, k_new, v_new, out, batch, Hq, t, t_per_seq, window, scale, &plan, workspace, s);
   if (rc != TEMPO_OK || plan.num_splits == 1) return rc;  // a single split wrote `out` itself
   return do_combine(kv, out, batch, Hq, t, t_per_seq, window, &plan, workspace, s);
 }
@@ -249,13 +294,13 @@ size_t tempo_kv_pool_bytes(const tempo_kv* kv) {
 }
 
 int tempo_attn_plan(const tempo_kv* kv, int32_t batch, int32_t num_q_heads, int32_t t_max,
-                    int32_t window, tempo_plan* plan) {
+                    int32_t window, int32_t ragged, tempo_plan* plan) {
   int rc = check_layout(kv);
   if (rc != TEMPO_OK) return rc;
   if (!plan) return TEMPO_ERR_NULL;
   if ((rc = check_heads(kv, batch, num_q_heads)) != TEMPO_OK) return rc;
   if (t_max < 0 || window < 0) return TEMPO_ERR_RANGE;
-  make_plan(kv, batch, num_q_heads, t_max, window, plan);
+  make_plan(kv, batch, num_q_heads, t_max, window, ragged != 0, plan);
   return TEMPO_OK;
 }
 
@@ -270,20 +315,14 @@ size_t tempo_attn_workspace_bytes(const tempo_kv* kv, int32_t batch, int32_t num
                                   int32_t max_t) {
   if (check_layout(kv) != TEMPO_OK || max_t < 0) return 0;
   if (check_heads(kv, batch, num_q_heads) != TEMPO_OK) return 0;
-  // The planner's split count is not monotone in t (short ranges use shorter
-  // splits), so bound it over every step t' <= max_t and every window:
-  //  - with the default split length (2^8) or a longer one, the count is at most
-  //    min(splits(max_t, 2^8), kMaxSplits);
-  //  - a shorter length 2^k is only chosen while pairs * splits(t', 2^(k+1)) is
-  //    below the target, and halving the length at most doubles the count, so the
-  //    count is below 2 * ceil(target / pairs), and never above splits(max_t, 2^5).
-  const int64_t pairs = (int64_t)batch * (kv->dtype == TEMPO_BF16 ? kv->num_kv_heads : num_q_heads);
-  int64_t long_case = splits_bound(max_t, 0, 8);
-  if (long_case > kMaxSplits) long_case = kMaxSplits;
-  int64_t short_case = 2 * ((kTargetItems + pairs - 1) / pairs);
-  if (short_case > splits_bound(max_t, 0, 5)) short_case = splits_bound(max_t, 0, 5);
-  const int32_t worst = (int32_t)(long_case > short_case ? long_case : short_case);
-  return plan_bytes(kv, batch, num_q_heads, worst);
+  // The planner's split count is not monotone in t, so take the largest count it
+  // produces for any step up to max_t and any window.  A shorter range or a window
+  // never needs more splits than the causal range of max_t at the same split
+  // length, and the planner only chooses lengths of at least 32, so the causal
+  // count at length 32, capped at the planner's own maximum, bounds them all.
+  int64_t worst = splits_bound(max_t, 0, 5);
+  if (worst > kMaxSplits) worst = kMaxSplits;
+  return plan_bytes(kv, batch, num_q_heads, (int32_t)worst);
 }
 
 const char* tempo_strerror(int status) {
@@ -329,7 +368,8 @@ int tempo_kv_gather(const tempo_kv* kv, void* k_out, void* v_out, int32_t batch,
 int tempo_attn_decode_causal(const tempo_kv* kv, const void* q, void* out, int32_t batch,
                              int32_t num_q_heads, int32_t t, const int32_t* t_per_seq,
                              float scale, void* workspace, size_t workspace_bytes, void* stream) {
-  return decode(kv, q, out, batch, num_q_heads, t, t_per_seq, 0, scale, workspace, workspace_bytes, stream);
+  return decode(kv, q, nullptr, nullptr, out, batch, num_q_heads, t, t_per_seq, 0, scale, workspace,
+                workspace_bytes, stream);
 }
 
 int tempo_attn_decode_window(const tempo_kv* kv, const void* q, void* out, int32_t batch,
@@ -337,7 +377,27 @@ int tempo_attn_decode_window(const tempo_kv* kv, const void* q, void* out, int32
                              int32_t window, float scale, void* workspace,
                              size_t workspace_bytes, void* stream) {
   if (window < 1) return TEMPO_ERR_RANGE;
-  return decode(kv, q, out, batch, num_q_heads, t, t_per_seq, window, scale, workspace, workspace_bytes, stream);
+  return decode(kv, q, nullptr, nullptr, out, batch, num_q_heads, t, t_per_seq, window, scale, workspace,
+                workspace_bytes, stream);
+}
+
+int tempo_decode_step_causal(const tempo_kv* kv, const void* q, const void* k_new, const void* v_new,
+                             void* out, int32_t batch, int32_t num_q_heads, int32_t t,
+                             const int32_t* t_per_seq, float scale, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+  if (!k_new || !v_new) return TEMPO_ERR_NULL;
+  return decode(kv, q, k_new, v_new, out, batch, num_q_heads, t, t_per_seq, 0, scale, workspace,
+                workspace_bytes, stream);
+}
+
+int tempo_decode_step_window(const tempo_kv* kv, const void* q, const void* k_new, const void* v_new,
+                             void* out, int32_t batch, int32_t num_q_heads, int32_t t,
+                             const int32_t* t_per_seq, int32_t window, float scale, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+  if (!k_new || !v_new) return TEMPO_ERR_NULL;
+  if (window < 1) return TEMPO_ERR_RANGE;
+  return decode(kv, q, k_new, v_new, out, batch, num_q_heads, t, t_per_seq, window, scale, workspace,
+                workspace_bytes, stream);
 }
 
 int tempo_attn_decode_partial(const tempo_kv* kv, const void* q, int32_t batch,
@@ -348,8 +408,8 @@ int tempo_attn_decode_partial(const tempo_kv* kv, const void* q, int32_t batch,
   if (rc != TEMPO_OK) return rc;
   if (!q) return TEMPO_ERR_NULL;
   if ((rc = check_attn(kv, batch, num_q_heads, t, window, t_per_seq != nullptr, plan, workspace, workspace_bytes)) != TEMPO_OK) return rc;
-  return do_partial(kv, q, nullptr, batch, num_q_heads, t, t_per_seq, window, scale, plan, workspace,
-                    static_cast<hipStream_t>(stream));
+  return do_partial(kv, q, nullptr, nullptr, nullptr, batch, num_q_heads, t, t_per_seq, window, scale, plan,
+                    workspace, static_cast<hipStream_t>(stream));
 }
 
 int tempo_attn_decode_combine(const tempo_kv* kv, void* out, int32_t batch, int32_t num_q_heads,
@@ -362,6 +422,14 @@ int tempo_attn_decode_combine(const tempo_kv* kv, void* out, int32_t batch, int3
   if ((rc = check_attn(kv, batch, num_q_heads, t, window, t_per_seq != nullptr, plan, workspace, workspace_bytes)) != TEMPO_OK) return rc;
   return do_combine(kv, out, batch, num_q_heads, t, t_per_seq, window, plan,
                     const_cast<void*>(workspace), static_cast<hipStream_t>(stream));
+}
+
+int tempo_stream_read(const void* src, size_t bytes, void* sink, int32_t workgroups, void* stream) {
+  if (!src || !sink) return TEMPO_ERR_NULL;
+  if (bytes < 16 || bytes % 16 != 0 || (reinterpret_cast<uintptr_t>(src) & 15u) != 0) return TEMPO_ERR_SHAPE;
+  if (workgroups < 1 || workgroups > (1 << 24)) return TEMPO_ERR_SHAPE;
+  const hipError_t e = launch_stream_read(src, bytes, sink, workgroups, static_cast<hipStream_t>(stream));
+  return launch_status(e, "stream_read");
 }
 
 }  // extern "C"

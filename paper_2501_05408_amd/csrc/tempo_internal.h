@@ -59,10 +59,12 @@ struct StoreParams {
 };
 
 struct AttnParams {
-  const void* k_pool;
-  const void* v_pool;
+  void* k_pool;              // written only when k_new is set
+  void* v_pool;
   const int32_t* block_table;
   const void* q;
+  const void* k_new;         // [B][Hkv][D]; non-null: append step t inside the attention kernel
+  const void* v_new;
   const int32_t* t_per_seq;  // may be null
   float* ws_ml;              // [B][Hq][S][2]  (running max in log2 units, running sum)
   float* ws_acc;             // [B][Hq][S][D]
@@ -119,6 +121,9 @@ hipError_t launch_partial_bf16(const AttnParams& p, int batch, int D, int grid_s
                                hipStream_t stream);
 hipError_t launch_partial_f32(const AttnParams& p, int batch, int D, int grid_splits, int waves,
                               hipStream_t stream);
+
 hipError_t launch_combine(const AttnParams& p, int batch, int D, int dtype, hipStream_t stream);
+hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, int workgroups,
+                              hipStream_t stream);
 
 }  // namespace tempo

@@ -50,7 +50,7 @@ class BlockStore:
         self.kv = T.make_kv(self.k_pool, self.v_pool, self.block_table, self.num_blocks,
                             self.max_blocks_per_seq, block_size, num_kv_heads, head_dim, dtype)
         self.workspace_bytes = T.tempo_attn_workspace_bytes(self.kv, batch, num_q_heads, self.max_t)
-        self.workspace = torch.empty(self.workspace_bytes, dtype=torch.uint8, device=self.device)
+        self.workspace = torch.zeros(self.workspace_bytes, dtype=torch.uint8, device=self.device)
         self.scale = 1.0 / math.sqrt(head_dim)
 
     # -- forwarding ----------------------------------------------------------------
@@ -75,6 +75,19 @@ class BlockStore:
 
     def attend_window(self, q, out, t, window, t_per_seq=None, scale=None):
         T.tempo_attn_decode_window(self.kv, q, out, self.batch, self.Hq, t, t_per_seq, window,
+                                   self.scale if scale is None else scale, self.workspace,
+                                   self.workspace_bytes)
+        return out
+
+    def step_causal(self, q, k_new, v_new, out, t, t_per_seq=None, scale=None):
+        """Append step t and attend over 0..t in one launch."""
+        T.tempo_decode_step_causal(self.kv, q, k_new, v_new, out, self.batch, self.Hq, t, t_per_seq,
+                                   self.scale if scale is None else scale, self.workspace,
+                                   self.workspace_bytes)
+        return out
+
+    def step_window(self, q, k_new, v_new, out, t, window, t_per_seq=None, scale=None):
+        T.tempo_decode_step_window(self.kv, q, k_new, v_new, out, self.batch, self.Hq, t, t_per_seq, window,
                                    self.scale if scale is None else scale, self.workspace,
                                    self.workspace_bytes)
         return out

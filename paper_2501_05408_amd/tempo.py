@@ -74,7 +74,7 @@ SIGNATURES = {
     "tempo_append_slot": (ctypes.c_int, [_i32, _i32, _i32p, _i32p]),
     "tempo_kv_element_offset": (ctypes.c_int64, [_kvp, _i32, _i32, _i32, _i32, _i32]),
     "tempo_kv_pool_bytes": (ctypes.c_size_t, [_kvp]),
-    "tempo_attn_plan": (ctypes.c_int, [_kvp, _i32, _i32, _i32, _i32, _planp]),
+    "tempo_attn_plan": (ctypes.c_int, [_kvp, _i32, _i32, _i32, _i32, _i32, _planp]),
     "tempo_attn_workspace_bytes": (ctypes.c_size_t, [_kvp, _i32, _i32, _i32]),
     "tempo_strerror": (ctypes.c_char_p, [ctypes.c_int]),
     "tempo_kv_append": (ctypes.c_int, [_kvp, _vp, _vp, _i32, _i32, _vp, _vp]),
@@ -83,11 +83,16 @@ SIGNATURES = {
                                                 _vp, ctypes.c_size_t, _vp]),
     "tempo_attn_decode_window": (ctypes.c_int, [_kvp, _vp, _vp, _i32, _i32, _i32, _vp, _i32,
                                                 ctypes.c_float, _vp, ctypes.c_size_t, _vp]),
+    "tempo_decode_step_causal": (ctypes.c_int, [_kvp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp,
+                                                ctypes.c_float, _vp, ctypes.c_size_t, _vp]),
+    "tempo_decode_step_window": (ctypes.c_int, [_kvp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _i32,
+                                                ctypes.c_float, _vp, ctypes.c_size_t, _vp]),
     "tempo_attn_decode_partial": (ctypes.c_int, [_kvp, _vp, _i32, _i32, _i32, _vp, _i32, ctypes.c_float,
                                                  _planp, _vp, ctypes.c_size_t, _vp]),
     "tempo_attn_decode_combine": (ctypes.c_int, [_kvp, _vp, _i32, _i32, _i32, _vp, _i32, _planp, _vp,
                                                  ctypes.c_size_t, _vp]),
     "tempo_attn_plan_workspace_bytes": (ctypes.c_size_t, [_kvp, _i32, _i32, _planp]),
+    "tempo_stream_read": (ctypes.c_int, [_vp, ctypes.c_size_t, _vp, _i32, _vp]),
 }
 
 
@@ -186,9 +191,11 @@ def tempo_kv_pool_bytes(kv: tempo_kv) -> int:
     return load().tempo_kv_pool_bytes(ctypes.byref(kv))
 
 
-def tempo_attn_plan(kv: tempo_kv, batch: int, num_q_heads: int, t_max: int, window: int = 0) -> tempo_plan:
+def tempo_attn_plan(kv: tempo_kv, batch: int, num_q_heads: int, t_max: int, window: int = 0,
+                    ragged: bool = False) -> tempo_plan:
     plan = tempo_plan()
-    _check(load().tempo_attn_plan(ctypes.byref(kv), batch, num_q_heads, t_max, window, ctypes.byref(plan)),
+    _check(load().tempo_attn_plan(ctypes.byref(kv), batch, num_q_heads, t_max, window, int(ragged),
+                                  ctypes.byref(plan)),
            "tempo_attn_plan")
     return plan
 
@@ -230,6 +237,21 @@ def tempo_attn_decode_window(kv, q, out, batch, num_q_heads, t, t_per_seq, windo
                                            workspace_bytes, _stream(stream)), "tempo_attn_decode_window")
 
 
+def tempo_decode_step_causal(kv, q, k_new, v_new, out, batch, num_q_heads, t, t_per_seq, scale, workspace,
+                             workspace_bytes, stream=None):
+    _check(load().tempo_decode_step_causal(ctypes.byref(kv), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out),
+                                           batch, num_q_heads, t, _ptr(t_per_seq), scale, _ptr(workspace),
+                                           workspace_bytes, _stream(stream)), "tempo_decode_step_causal")
+
+
+def tempo_decode_step_window(kv, q, k_new, v_new, out, batch, num_q_heads, t, t_per_seq, window, scale,
+                             workspace, workspace_bytes, stream=None):
+    _check(load().tempo_decode_step_window(ctypes.byref(kv), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out),
+                                           batch, num_q_heads, t, _ptr(t_per_seq), window, scale,
+                                           _ptr(workspace), workspace_bytes, _stream(stream)),
+           "tempo_decode_step_window")
+
+
 def tempo_attn_decode_partial(kv, q, batch, num_q_heads, t, t_per_seq, window, scale, plan, workspace,
                               workspace_bytes, stream=None):
     _check(load().tempo_attn_decode_partial(ctypes.byref(kv), _ptr(q), batch, num_q_heads, t,
@@ -244,3 +266,8 @@ def tempo_attn_decode_combine(kv, out, batch, num_q_heads, t, t_per_seq, window,
                                             _ptr(t_per_seq), window, ctypes.byref(plan), _ptr(workspace),
                                             workspace_bytes, _stream(stream)),
            "tempo_attn_decode_combine")
+
+
+def tempo_stream_read(src, nbytes, sink, workgroups, stream=None):
+    _check(load().tempo_stream_read(_ptr(src), nbytes, _ptr(sink), workgroups, _stream(stream)),
+           "tempo_stream_read")

@@ -253,6 +253,65 @@ def test_explicit_plans_and_determinism(dtype):
 
 
 # ----------------------------------------------------------------------------
+# One-launch decode step (append fused into the attention kernel) against the
+# oracle and, bit for bit, against the separate append + attend calls.
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", [T.TEMPO_BF16, T.TEMPO_F32])
+@pytest.mark.parametrize("window", [0, 37])
+def test_fused_step_equals_append_then_attend(dtype, window):
+    B, Hq, Hkv, D, Z, steps = 3, 6, 2, 128, 64, 200
+    q, K, V = host_inputs(8, B, steps, Hq, Hkv, D, dtype)
+    table, nb = random_table(8, B, steps // Z + 1)
+    fused = BlockStore(B, Hq, Hkv, D, Z, steps - 1, dtype, num_blocks=nb, block_table=table, fill="nan")
+    plain = BlockStore(B, Hq, Hkv, D, Z, steps - 1, dtype, num_blocks=nb, block_table=table, fill="nan")
+    qd, Kd, Vd = dev(q, dtype), dev(K, dtype), dev(V, dtype)
+    of = torch.empty((steps, B, Hq, D), dtype=TDT[dtype], device=DEV)
+    op = torch.empty_like(of)
+    for t in range(steps):
+        k_t, v_t = Kd[:, t].contiguous(), Vd[:, t].contiguous()
+        plain.append(k_t, v_t, t)
+        if window:
+            plain.attend_window(qd[t], op[t], t, window)
+            fused.step_window(qd[t], k_t, v_t, of[t], t, window)
+        else:
+            plain.attend_causal(qd[t], op[t], t)
+            fused.step_causal(qd[t], k_t, v_t, of[t], t)
+    torch.cuda.synchronize()
+    assert torch.equal(of, op)
+    kf, vf = fused.gather(0, steps)
+    assert torch.equal(kf, Kd) and torch.equal(vf, Vd)
+    got = np64(of)
+    K64, V64 = K.astype(np.float64), V.astype(np.float64)
+    for t in range(0, steps, 7):
+        ref = oracle.attend(q[t].astype(np.float64), K64, V64, t, window, 1.0 / np.sqrt(D))
+        assert_close(got[t], ref, dtype, f"fused step window={window} t={t}")
+
+
+@pytest.mark.parametrize("dtype", [T.TEMPO_BF16, T.TEMPO_F32])
+def test_fused_step_ragged(dtype):
+    B, Hq, Hkv, D, Z, T_len = 5, 8, 2, 64, 32, 260
+    q, K, V = host_inputs(9, B, T_len, Hq, Hkv, D, dtype)
+    lengths = np.array([1, 260, 33, 97, 160], dtype=np.int32)
+    st = BlockStore(B, Hq, Hkv, D, Z, T_len - 1, dtype, fill="nan")
+    Kd, Vd = dev(K, dtype), dev(V, dtype)
+    len_d = torch.from_numpy(lengths).to(DEV)
+    # every sequence holds steps 0..len-2; the fused step appends step len-1 and attends
+    st.prefill(Kd, Vd, T_len - 2, lengths=torch.clamp(len_d - 1, min=1))
+    tps = (len_d - 1).to(torch.int32)
+    ar = torch.arange(B, device=DEV)
+    k_t, v_t = Kd[ar, tps.long()].contiguous(), Vd[ar, tps.long()].contiguous()
+    qd = dev(q[0], dtype)
+    out = st.step_causal(qd, k_t, v_t, st.new_out(), T_len - 1, t_per_seq=tps)
+    ref = oracle.attend(q[0].astype(np.float64), K.astype(np.float64), V.astype(np.float64),
+                        lengths - 1, 0, 1.0 / np.sqrt(D))
+    assert_close(out, ref, dtype, "fused ragged step")
+    kg, vg = st.gather(0, T_len)
+    for b in range(B):
+        L = int(lengths[b])
+        assert torch.equal(kg[b, :L], Kd[b, :L]) and torch.equal(vg[b, :L], Vd[b, :L])
+
+
+# ----------------------------------------------------------------------------
 # Full-size workloads, in the launch configuration the benchmark times.
 # Keys/values are drawn on the GPU (seeded), appended through the ABI, and the
 # oracle reads the same values back from the flat tensors.

@@ -102,8 +102,10 @@ def test_plan_covers_every_step_and_workspace_bound_holds():
                 ts = sorted(set(list(range(0, min(max_t, 700) + 1, 7)) + [max_t, max_t // 2, max_t // 3]))
                 for t in ts:
                     for w in (0, 1, 5, 512, 513):
-                        plan = T.tempo_attn_plan(kv, batch, Hq, t, w)
+                      for ragged in (False, True):
+                        plan = T.tempo_attn_plan(kv, batch, Hq, t, w, ragged)
                         tps = plan.tokens_per_split
+                        assert not ragged or tps <= 1024
                         assert tps >= 32 and tps & (tps - 1) == 0
                         assert plan.waves in (1, 2, 4, 8) and plan.waves * 32 <= max(tps, 32)
                         lo = 0 if w == 0 else max(0, t - w + 1)
