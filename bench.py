@@ -37,9 +37,10 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 
 # HBM bytes per launch of the partial-attention kernel at the benchmark workload,
-# from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/), scaled by what
-# the same counters read for a copy kernel of known size.  None until measured.
-MEASURED_TRAFFIC_BYTES = None
+# from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of `bench.py --counters`
+# (profiles/attn_partial_bf16_llama_t4095_hbm_traffic.txt), each scaled by what the
+# same counter reads for the 256 MiB copy kernel: 268,687,325 fetched + 1,711,886 written.
+MEASURED_TRAFFIC_BYTES = 270399211
 
 
 def main() -> int:
@@ -50,6 +51,10 @@ def main() -> int:
     ap.add_argument("--layers", type=int, default=8, help="pools rotated over (cache defeat)")
     ap.add_argument("--no-extras", action="store_true", help="skip the per-t curve and whole-run legs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    ap.add_argument("--counters", action="store_true",
+                    help="short run to put under rocprofv3 --pmc: pools filled directly with N(0,1), "
+                         "W+K decode steps, then 4 copy launches of 256 MiB (the known-size kernel the "
+                         "traffic counters are scaled by); no timing, no oracle")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -79,7 +84,17 @@ def main() -> int:
 
     # --- build R layers: flat K/V drawn on the GPU, written through the ABI -------
     stores, keep_flat = [], None
-    for layer in range(R):
+    for layer in range(R if args.counters else 0):
+        # hardware-counter mode: traffic does not depend on values, so skip the per-step appends
+        perm = synth.permutation(7, layer, B * (T_len // Z))
+        st = BlockStore(B, Hq, Hkv, D, Z, t, T.TEMPO_BF16, device=dev,
+                        block_table=torch.from_numpy(perm.reshape(B, T_len // Z).copy()))
+        st.k_pool.normal_()
+        st.v_pool.normal_()
+        st.k_last = synth.device_normal((B, Hkv, D), 500 + layer, torch.bfloat16, dev)
+        st.v_last = synth.device_normal((B, Hkv, D), 600 + layer, torch.bfloat16, dev)
+        stores.append(st)
+    for layer in range(0 if args.counters else R):
         K = synth.device_normal((B, T_len, Hkv, D), 1000 + 2 * layer, torch.bfloat16, dev)
         V = synth.device_normal((B, T_len, Hkv, D), 1001 + 2 * layer, torch.bfloat16, dev)
         perm = synth.permutation(7, layer, B * (T_len // Z))
@@ -103,6 +118,18 @@ def main() -> int:
         st.append(st.k_last, st.v_last, t)
         st.attend_causal(q, outs[i % R], t)
 
+    if args.counters:
+        for i in range(args.warmup + args.steps):
+            step(i)
+        src = torch.empty(128 << 20, dtype=torch.bfloat16, device=dev).normal_()   # 256 MiB
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            T.tempo_stream_copy(src, dst, 2 * src.numel(), 2048)
+        torch.cuda.synchronize()
+        print(json.dumps({"mode": "counters", "steps": args.warmup + args.steps,
+                          "kv_bytes_per_step": step_bytes, "copy_bytes": 2 * src.numel(), "copies": 4}))
+        return 0
+
     # --- the timed region: W warm-up steps, then exactly K steps -------------------
     for i in range(args.warmup):
         step(i)
@@ -125,22 +152,45 @@ def main() -> int:
     torch.cuda.synchronize()
     sep = (time.perf_counter() - t0) / args.steps
 
-    # --- the dominant kernel alone, HIP events on the launch stream, same steps ----
+    # --- the dominant kernel alone: the step's partial-attention launch (fused append
+    # included), K launches back to back on the launch stream between one pair of HIP
+    # events, rotating over the same pools.  Its average period is what a kernel trace
+    # of this command reports as that kernel's average duration.
     plan = T.tempo_attn_plan(stores[0].kv, B, Hq, t, 0)
     ws_bytes = stores[0].workspace_bytes
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-          for _ in range(args.steps)]
-    for i in range(args.steps):
+
+    def partial_only(i):
         st = stores[i % R]
-        st.append(st.k_last, st.v_last, t)
-        ev[i][0].record()
-        T.tempo_attn_decode_partial(st.kv, q, B, Hq, t, None, 0, scale, plan, st.workspace, ws_bytes)
-        ev[i][1].record()
-        T.tempo_attn_decode_combine(st.kv, outs[i % R], B, Hq, t, None, 0, plan, st.workspace, ws_bytes)
+        T.tempo_attn_decode_partial(st.kv, q, st.k_last, st.v_last, B, Hq, t, None, 0, scale, plan,
+                                    st.workspace, ws_bytes)
+
+    for i in range(args.warmup):
+        partial_only(i)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(args.steps):
+        partial_only(i)
+    e1.record()
     torch.cuda.synchronize()
-    kernel_ms = [a.elapsed_time(b) for a, b in ev]
-    kernel_avg_ms = sum(kernel_ms) / len(kernel_ms)
+    kernel_avg_ms = e0.elapsed_time(e1) / args.steps
     achieved = step_bytes / (kernel_avg_ms * 1e-3) / 1e9
+
+    # --- the streaming-read yardstick over the same bytes (one layer's two pools) -----
+    sink = torch.zeros(16, dtype=torch.int32, device=dev)
+
+    def stream_only(i):
+        st = stores[i % R]
+        T.tempo_stream_read(st.k_pool, 2 * st.k_pool.numel(), sink, 512)
+        T.tempo_stream_read(st.v_pool, 2 * st.v_pool.numel(), sink, 512)
+
+    for i in range(args.warmup):
+        stream_only(i)
+    e0.record()
+    for i in range(args.steps):
+        stream_only(i)
+    e1.record()
+    torch.cuda.synchronize()
+    stream_ms = e0.elapsed_time(e1) / args.steps
 
     result = {
         "metric": "decode-attention KV GB/s (% of HBM peak) + steps/s, Llama-3.2-3B shape",
@@ -176,8 +226,10 @@ def main() -> int:
             "frac": round(achieved / HBM_PEAK_GBS, 4),
             "traffic": MEASURED_TRAFFIC_BYTES,
             "kernel_avg_us": round(kernel_avg_ms * 1e3, 2),
-            "kernel_min_us": round(min(kernel_ms) * 1e3, 2),
             "algorithmic_bytes_per_launch": step_bytes,
+            "stream_read_same_bytes": {"us": round(stream_ms * 1e3, 2),
+                                       "gbs": round(step_bytes / (stream_ms * 1e-3) / 1e9, 1),
+                                       "note": "two plain read launches (K pool, V pool) of one layer"},
         },
     }
 

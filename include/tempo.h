@@ -213,7 +213,9 @@ int tempo_decode_step_window(const tempo_kv* kv, const void* q, const void* k_ne
 /*
  * Partial attention and split combine as two separate launches, with an explicit
  * plan (for profiling one kernel at a time and for sweeping plans).  window = 0
- * is causal.  tempo_attn_decode_partial writes one (max, sum, accumulator)
+ * is causal.  k_new / v_new are both NULL (the pool already holds step t) or both
+ * set (step t is appended by this launch, as in tempo_decode_step_*).
+ * tempo_attn_decode_partial writes one (max, sum, accumulator)
  * partial per (sequence, query head, non-empty split) into workspace
  * (Section 4.3: per-tile reductions under -inf / 0 masks);
  * tempo_attn_decode_combine sums the partials into out (Section 4.3: "sums
@@ -221,10 +223,11 @@ int tempo_decode_step_window(const tempo_kv* kv, const void* q, const void* k_ne
  * of step t, at least (t div tps) - (lo div tps) + 1 splits, and with t_per_seq
  * the range of any step up to t (what tempo_attn_plan returns).
  */
-int tempo_attn_decode_partial(const tempo_kv* kv, const void* q, int32_t batch,
-                              int32_t num_q_heads, int32_t t, const int32_t* t_per_seq,
-                              int32_t window, float scale, const tempo_plan* plan,
-                              void* workspace, size_t workspace_bytes, void* stream);
+int tempo_attn_decode_partial(const tempo_kv* kv, const void* q, const void* k_new,
+                              const void* v_new, int32_t batch, int32_t num_q_heads, int32_t t,
+                              const int32_t* t_per_seq, int32_t window, float scale,
+                              const tempo_plan* plan, void* workspace, size_t workspace_bytes,
+                              void* stream);
 
 int tempo_attn_decode_combine(const tempo_kv* kv, void* out, int32_t batch, int32_t num_q_heads,
                               int32_t t, const int32_t* t_per_seq, int32_t window,
@@ -244,6 +247,10 @@ size_t tempo_attn_plan_workspace_bytes(const tempo_kv* kv, int32_t batch, int32_
  * scaled by.
  */
 int tempo_stream_read(const void* src, size_t bytes, void* sink, int32_t workgroups, void* stream);
+
+/* The same walk, copying src to dst (both device, 16-byte aligned, `bytes` each):
+ * reads `bytes` and writes `bytes`, which is what traffic counters are checked against. */
+int tempo_stream_copy(const void* src, void* dst, size_t bytes, int32_t workgroups, void* stream);
 
 #ifdef __cplusplus
 }

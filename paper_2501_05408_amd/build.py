@@ -8,6 +8,7 @@ from __future__ import annotations
 
 import concurrent.futures
 import os
+import re
 import subprocess
 import sys
 
@@ -23,6 +24,7 @@ SOURCES = ["tempo_api.hip", "kv_store.hip", "attn_partial_bf16.hip", "attn_parti
 HEADERS = [os.path.join(CSRC, "tempo_internal.h"), os.path.join(ROOT, "include", "tempo.h")]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
+         "-Rpass-analysis=kernel-resource-usage",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
@@ -43,14 +45,42 @@ def _stale() -> bool:
     return any(os.path.getmtime(d) > lib_m for d in deps)
 
 
+def _drop_remarks(lines):
+    """Remove the resource-usage remarks (and their source excerpts) from hipcc's stderr."""
+    out, skip = [], 0
+    for l in lines:
+        if "[-Rpass-analysis=kernel-resource-usage]" in l:
+            skip = 2 if "Function Name" in l else 0   # the excerpt and caret lines follow the first remark
+            continue
+        if skip and (re.match(r"\s*\d+ \| ", l) or re.match(r"\s*\|\s*\^", l)):
+            skip -= 1
+            continue
+        skip = 0
+        out.append(l)
+    return out
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(OBJDIR, os.path.splitext(src)[0] + ".o")
     cmd = [_hipcc()] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
-    err = "\n".join(l for l in r.stderr.splitlines() if noise not in l)
+    lines = [l for l in r.stderr.splitlines() if noise not in l]
+    # Resource remarks: a kernel that falls back to scratch memory (a register array
+    # the compiler could not keep in registers) is several times slower; refuse it.
+    kernel, spilled = None, []
+    for l in lines:
+        m = re.search(r"remark: Function Name: (\S+)", l)
+        if m:
+            kernel = m.group(1)
+        m = re.search(r"remark:\s+ScratchSize \[bytes/lane\]: (\d+)", l)
+        if m and int(m.group(1)) > 0:
+            spilled.append(f"{kernel}: {m.group(1)} bytes/lane of scratch")
+    err = "\n".join(_drop_remarks(lines))
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{err}")
+    if spilled:
+        raise RuntimeError(f"{src}: kernels must not use scratch memory:\n  " + "\n  ".join(spilled))
     if err.strip():
         sys.stderr.write(err + "\n")
     return obj

@@ -400,15 +400,16 @@ int tempo_decode_step_window(const tempo_kv* kv, const void* q, const void* k_ne
                 workspace_bytes, stream);
 }
 
-int tempo_attn_decode_partial(const tempo_kv* kv, const void* q, int32_t batch,
-                              int32_t num_q_heads, int32_t t, const int32_t* t_per_seq,
-                              int32_t window, float scale, const tempo_plan* plan,
-                              void* workspace, size_t workspace_bytes, void* stream) {
+int tempo_attn_decode_partial(const tempo_kv* kv, const void* q, const void* k_new,
+                              const void* v_new, int32_t batch, int32_t num_q_heads, int32_t t,
+                              const int32_t* t_per_seq, int32_t window, float scale,
+                              const tempo_plan* plan, void* workspace, size_t workspace_bytes,
+                              void* stream) {
   int rc = check_layout(kv);
   if (rc != TEMPO_OK) return rc;
-  if (!q) return TEMPO_ERR_NULL;
+  if (!q || ((k_new == nullptr) != (v_new == nullptr))) return TEMPO_ERR_NULL;
   if ((rc = check_attn(kv, batch, num_q_heads, t, window, t_per_seq != nullptr, plan, workspace, workspace_bytes)) != TEMPO_OK) return rc;
-  return do_partial(kv, q, nullptr, nullptr, nullptr, batch, num_q_heads, t, t_per_seq, window, scale, plan,
+  return do_partial(kv, q, k_new, v_new, nullptr, batch, num_q_heads, t, t_per_seq, window, scale, plan,
                     workspace, static_cast<hipStream_t>(stream));
 }
 
@@ -430,6 +431,16 @@ int tempo_stream_read(const void* src, size_t bytes, void* sink, int32_t workgro
   if (workgroups < 1 || workgroups > (1 << 24)) return TEMPO_ERR_SHAPE;
   const hipError_t e = launch_stream_read(src, bytes, sink, workgroups, static_cast<hipStream_t>(stream));
   return launch_status(e, "stream_read");
+}
+
+int tempo_stream_copy(const void* src, void* dst, size_t bytes, int32_t workgroups, void* stream) {
+  if (!src || !dst) return TEMPO_ERR_NULL;
+  if (bytes < 16 || bytes % 16 != 0 || (reinterpret_cast<uintptr_t>(src) & 15u) != 0 ||
+      (reinterpret_cast<uintptr_t>(dst) & 15u) != 0)
+    return TEMPO_ERR_SHAPE;
+  if (workgroups < 1 || workgroups > (1 << 24)) return TEMPO_ERR_SHAPE;
+  const hipError_t e = launch_stream_copy(src, dst, bytes, workgroups, static_cast<hipStream_t>(stream));
+  return launch_status(e, "stream_copy");
 }
 
 }  // extern "C"

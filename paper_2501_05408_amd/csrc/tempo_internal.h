@@ -125,5 +125,7 @@ hipError_t launch_partial_f32(const AttnParams& p, int batch, int D, int grid_sp
 hipError_t launch_combine(const AttnParams& p, int batch, int D, int dtype, hipStream_t stream);
 hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, int workgroups,
                               hipStream_t stream);
+hipError_t launch_stream_copy(const void* src, void* dst, size_t bytes, int workgroups,
+                              hipStream_t stream);
 
 }  // namespace tempo

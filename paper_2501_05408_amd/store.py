@@ -98,7 +98,7 @@ class BlockStore:
         if getattr(self, "_plan_ws", None) is None or self._plan_ws.numel() < nbytes:
             self._plan_ws = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
         s = self.scale if scale is None else scale
-        T.tempo_attn_decode_partial(self.kv, q, self.batch, self.Hq, t, t_per_seq, window, s, plan,
+        T.tempo_attn_decode_partial(self.kv, q, None, None, self.batch, self.Hq, t, t_per_seq, window, s, plan,
                                     self._plan_ws, nbytes)
         T.tempo_attn_decode_combine(self.kv, out, self.batch, self.Hq, t, t_per_seq, window, plan,
                                     self._plan_ws, nbytes)

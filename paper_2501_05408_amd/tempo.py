@@ -87,12 +87,13 @@ SIGNATURES = {
                                                 ctypes.c_float, _vp, ctypes.c_size_t, _vp]),
     "tempo_decode_step_window": (ctypes.c_int, [_kvp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _i32,
                                                 ctypes.c_float, _vp, ctypes.c_size_t, _vp]),
-    "tempo_attn_decode_partial": (ctypes.c_int, [_kvp, _vp, _i32, _i32, _i32, _vp, _i32, ctypes.c_float,
-                                                 _planp, _vp, ctypes.c_size_t, _vp]),
+    "tempo_attn_decode_partial": (ctypes.c_int, [_kvp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _i32,
+                                                 ctypes.c_float, _planp, _vp, ctypes.c_size_t, _vp]),
     "tempo_attn_decode_combine": (ctypes.c_int, [_kvp, _vp, _i32, _i32, _i32, _vp, _i32, _planp, _vp,
                                                  ctypes.c_size_t, _vp]),
     "tempo_attn_plan_workspace_bytes": (ctypes.c_size_t, [_kvp, _i32, _i32, _planp]),
     "tempo_stream_read": (ctypes.c_int, [_vp, ctypes.c_size_t, _vp, _i32, _vp]),
+    "tempo_stream_copy": (ctypes.c_int, [_vp, _vp, ctypes.c_size_t, _i32, _vp]),
 }
 
 
@@ -252,9 +253,10 @@ def tempo_decode_step_window(kv, q, k_new, v_new, out, batch, num_q_heads, t, t_
            "tempo_decode_step_window")
 
 
-def tempo_attn_decode_partial(kv, q, batch, num_q_heads, t, t_per_seq, window, scale, plan, workspace,
-                              workspace_bytes, stream=None):
-    _check(load().tempo_attn_decode_partial(ctypes.byref(kv), _ptr(q), batch, num_q_heads, t,
+def tempo_attn_decode_partial(kv, q, k_new, v_new, batch, num_q_heads, t, t_per_seq, window, scale, plan,
+                              workspace, workspace_bytes, stream=None):
+    _check(load().tempo_attn_decode_partial(ctypes.byref(kv), _ptr(q), _ptr(k_new), _ptr(v_new), batch,
+                                            num_q_heads, t,
                                             _ptr(t_per_seq), window, scale, ctypes.byref(plan),
                                             _ptr(workspace), workspace_bytes, _stream(stream)),
            "tempo_attn_decode_partial")
@@ -271,3 +273,8 @@ def tempo_attn_decode_combine(kv, out, batch, num_q_heads, t, t_per_seq, window,
 def tempo_stream_read(src, nbytes, sink, workgroups, stream=None):
     _check(load().tempo_stream_read(_ptr(src), nbytes, _ptr(sink), workgroups, _stream(stream)),
            "tempo_stream_read")
+
+
+def tempo_stream_copy(src, dst, nbytes, workgroups, stream=None):
+    _check(load().tempo_stream_copy(_ptr(src), _ptr(dst), nbytes, workgroups, _stream(stream)),
+           "tempo_stream_copy")

@@ -155,10 +155,12 @@ def test_bad_arguments_are_refused_before_any_launch():
     assert window(good, -3) == T.TEMPO_ERR_RANGE
 
     bad_plan = T.tempo_plan(48, 1, 1)
-    assert lib.tempo_attn_decode_partial(ctypes.byref(good), fake, 2, 6, 5, None, 0, 0.1,
+    assert lib.tempo_attn_decode_partial(ctypes.byref(good), fake, None, None, 2, 6, 5, None, 0, 0.1,
                                          ctypes.byref(bad_plan), fake << 4, 1 << 30, None) == T.TEMPO_ERR_SHAPE
+    assert lib.tempo_attn_decode_partial(ctypes.byref(good), fake, fake, None, 2, 6, 5, None, 0, 0.1,
+                                         ctypes.byref(bad_plan), fake << 4, 1 << 30, None) == T.TEMPO_ERR_NULL
     short_plan = T.tempo_plan(32, 1, 1)                          # step 100 needs 4 splits of 32
-    assert lib.tempo_attn_decode_partial(ctypes.byref(good), fake, 2, 6, 100, None, 0, 0.1,
+    assert lib.tempo_attn_decode_partial(ctypes.byref(good), fake, None, None, 2, 6, 100, None, 0, 0.1,
                                          ctypes.byref(short_plan), fake << 4, 1 << 30, None) == T.TEMPO_ERR_RANGE
     assert lib.tempo_kv_gather(ctypes.byref(good), fake, fake, 2, 0, 4 * 64 + 1, None) == T.TEMPO_ERR_RANGE
     assert T.tempo_attn_workspace_bytes(kv_desc(T.TEMPO_BF16, D=96), 2, 6, 100) == 0

@@ -119,7 +119,7 @@ def test_p3_uniform_weights_give_mean():
 
 
 # ----------------------------------------------------------------------------
-# P4  dynamic length == padded to T' and masked (workaround (c) of Section 2.2).
+# P4  dynamic length == padded to T' and masked (workaround (c) of Section 2.1).
 # ----------------------------------------------------------------------------
 def test_p4_padded_masked_formulation():
     B, T, Hq, Hkv, D = 2, 23, 6, 3, 8
