@@ -43,6 +43,101 @@ HBM_PEAK_GBS = 8000.0
 MEASURED_TRAFFIC_BYTES = 270399211
 
 
+def _timed(torch, fn, n, warm):
+    for i in range(warm):
+        fn(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(n):
+        fn(i)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / n
+
+
+def other_workloads(torch, T, BlockStore, synth, dev, kv_bytes_per_token):
+    """Sliding-window decode, a long single sequence, and the ragged 28-layer step, at their real
+    shapes.  Pools are filled directly with N(0,1) (any layout of i.i.d. values is i.i.d.), fresh
+    keys/values are appended by the step itself; each step visits a different layer's pool."""
+    Hq, Hkv, D, Z = 24, 8, 128, 256
+    out = {}
+    q16 = synth.device_normal((16, Hq, D), 71, torch.bfloat16, dev)
+    k16 = synth.device_normal((16, Hkv, D), 72, torch.bfloat16, dev)
+    v16 = synth.device_normal((16, Hkv, D), 73, torch.bfloat16, dev)
+
+    def layers(n, batch, max_t):
+        sts = []
+        for layer in range(n):
+            st = BlockStore(batch, Hq, Hkv, D, Z, max_t, T.TEMPO_BF16, device=dev)
+            st.k_pool.normal_()
+            st.v_pool.normal_()
+            sts.append(st)
+        return sts
+
+    # sliding window 512, batch 16, steady state (t >= 511), unaligned window position
+    sts = layers(8, 16, 16383)
+    o = sts[0].new_out()
+    for t in (8191, 16383 - 100):
+        dt = _timed(torch, lambda i: sts[i % 8].step_window(q16, k16, v16, o, t, 512), 200, 20)
+        plan = T.tempo_attn_plan(sts[0].kv, 16, Hq, t, 512)
+        out[f"window512_b16_t{t}"] = {"us_per_step": round(dt * 1e6, 2),
+                                      "kv_gbs": round(16 * 512 * kv_bytes_per_token / dt / 1e9, 1),
+                                      "splits": plan.num_splits, "tokens_per_split": plan.tokens_per_split}
+    del sts
+    torch.cuda.empty_cache()
+
+    # long single sequence
+    sts = layers(8, 1, 65535)
+    q1, k1, v1 = q16[:1].contiguous(), k16[:1].contiguous(), v16[:1].contiguous()
+    o = sts[0].new_out()
+    for t in (8191, 32767, 65535):
+        dt = _timed(torch, lambda i: sts[i % 8].step_causal(q1, k1, v1, o, t), 200, 20)
+        plan = T.tempo_attn_plan(sts[0].kv, 1, Hq, t, 0)
+        out[f"long_b1_t{t}"] = {"us_per_step": round(dt * 1e6, 2),
+                                "kv_gbs": round((t + 1) * kv_bytes_per_token / dt / 1e9, 1),
+                                "splits": plan.num_splits, "work_items": plan.num_splits * Hkv}
+    del sts
+    torch.cuda.empty_cache()
+
+    # ragged multi-layer: 28 layers, batch 64, lengths uniform in [1, 8192], one shared pool with
+    # exactly the blocks the sequences need, a random block table per layer
+    import numpy as np
+    n_layers, B = 28, 64
+    lengths = synth.integers(24, 1, B, 1, 8192)
+    need = (lengths.astype(np.int64) + Z - 1) // Z                       # blocks per sequence
+    per_layer = int(need.sum())
+    nb = n_layers * per_layer
+    k_pool = torch.empty((nb, Hkv, Z * D), dtype=torch.bfloat16, device=dev).normal_()
+    v_pool = torch.empty((nb, Hkv, Z * D), dtype=torch.bfloat16, device=dev).normal_()
+    perm = synth.permutation(24, 2, nb)
+    sts = []
+    for layer in range(n_layers):
+        table = np.zeros((B, 8192 // Z), dtype=np.int32)
+        ids = perm[layer * per_layer:(layer + 1) * per_layer]
+        pos = 0
+        for b in range(B):
+            table[b, :need[b]] = ids[pos:pos + need[b]]
+            pos += int(need[b])
+        sts.append(BlockStore(B, Hq, Hkv, D, Z, 8191, T.TEMPO_BF16, device=dev, num_blocks=nb,
+                              block_table=torch.from_numpy(table), pools=(k_pool, v_pool)))
+    tps = torch.from_numpy(lengths - 1).to(dev).to(torch.int32)
+    q64 = synth.device_normal((B, Hq, D), 74, torch.bfloat16, dev)
+    k64 = synth.device_normal((B, Hkv, D), 75, torch.bfloat16, dev)
+    v64 = synth.device_normal((B, Hkv, D), 76, torch.bfloat16, dev)
+    o = sts[0].new_out()
+
+    def ragged_step(_):
+        for st in sts:
+            st.step_causal(q64, k64, v64, o, 8191, t_per_seq=tps)
+
+    dt = _timed(torch, ragged_step, 10, 2)
+    step_bytes = n_layers * int(lengths.astype(np.int64).sum()) * kv_bytes_per_token
+    plan = T.tempo_attn_plan(sts[0].kv, B, Hq, 8191, 0, True)
+    out["ragged_28layers_b64"] = {"ms_per_step": round(dt * 1e3, 3), "kv_gbs": round(step_bytes / dt / 1e9, 1),
+                                  "kv_bytes_per_step": step_bytes, "pool_gib": round(2 * k_pool.numel() * 2 / 2**30, 1),
+                                  "splits": plan.num_splits, "tokens_per_split": plan.tokens_per_split}
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -300,6 +395,12 @@ def main() -> int:
                                "steps_per_s": round(T_len / run, 1),
                                "kv_gbs": round(total_bytes / run / 1e9, 1),
                                "note": "one layer, 256 MiB pool (partly cache resident at small t)"}
+
+    # --- the other workloads of the metric's family (timing only; their parity is in tests/) -----
+    if not args.no_extras:
+        del stores, outs, keep_flat
+        torch.cuda.empty_cache()
+        result["other_workloads"] = other_workloads(torch, T, BlockStore, synth, dev, kv_bytes_per_token)
 
     print(json.dumps(result))
     return 0

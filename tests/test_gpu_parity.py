@@ -328,8 +328,18 @@ def test_llama_shape_causal_bf16_full_size():
     K, V = flat_kv(21, B, T_len, Hkv, D)
     table, nb = random_table(21, B, T_len // Z, extra=0)
     st = BlockStore(B, Hq, Hkv, D, Z, T_len - 1, dtype, num_blocks=nb, block_table=table, fill="nan")
-    st.prefill(K, V, T_len - 1)
+    st.prefill(K, V, T_len - 2)
     K64, V64 = np64(K), np64(V)
+    # the benchmark's own launch: the fused step at t = 4095 (append + partial + combine)
+    t = T_len - 1
+    q = synth.device_normal((B, Hq, D), 2100 + t, torch.bfloat16, DEV)
+    out = st.step_causal(q, K[:, t].contiguous(), V[:, t].contiguous(), st.new_out(), t)
+    ref = oracle.attend(np64(q), K64, V64, t, 0, 1.0 / np.sqrt(D))
+    assert_close(out, ref, dtype, "llama causal fused step t=4095")
+    plan = T.tempo_attn_plan(st.kv, B, Hq, t, 0)
+    assert (plan.tokens_per_split, plan.num_splits, plan.waves) == (2048, 2, 4)
+    kg, vg = st.gather(t, 1)
+    assert torch.equal(kg[:, 0], K[:, t]) and torch.equal(vg[:, 0], V[:, t])
     steps = [0, 1, 31, 32, 255, 256, 257, 1000, 2047, 2048, 3000, 4094, 4095]
     for t in steps:
         q = synth.device_normal((B, Hq, D), 2100 + t, torch.bfloat16, DEV)
@@ -397,9 +407,12 @@ def test_ragged_multi_layer_shared_pool_bf16():
         K, V = flat_kv(240 + layer, B, T_max, Hkv, D)
         st = BlockStore(B, Hq, Hkv, D, Z, T_max - 1, dtype, num_blocks=nb, block_table=tables[layer],
                         pools=(k_pool, v_pool))
-        st.prefill(K, V, T_max - 1, lengths=len_d)
+        # every sequence holds its steps 0..L-2; the fused ragged step appends step L-1 and attends
+        st.prefill(K, V, T_max - 2, lengths=torch.clamp(len_d - 1, min=1))
+        ar = torch.arange(B, device=DEV)
         q = synth.device_normal((B, Hq, D), 2400 + layer, torch.bfloat16, DEV)
-        out = st.attend_causal(q, st.new_out(), T_max - 1, t_per_seq=tps)
+        out = st.step_causal(q, K[ar, tps.long()].contiguous(), V[ar, tps.long()].contiguous(),
+                             st.new_out(), T_max - 1, t_per_seq=tps)
         for b in sample:
             L = int(lengths[b])
             ref = oracle.attend(np64(q[b:b + 1]), np64(K[b:b + 1, :L]), np64(V[b:b + 1, :L]), L - 1, 0,
@@ -407,3 +420,41 @@ def test_ragged_multi_layer_shared_pool_bf16():
             assert_close(out[b:b + 1], ref, dtype, f"layer {layer} seq {b} len {L}")
         assert torch.isfinite(out.float()).all()
         del K, V
+
+
+# ----------------------------------------------------------------------------
+# The entry points allocate nothing and never synchronise, so a step can be
+# captured in a HIP graph; every replay must give the eager result.
+# ----------------------------------------------------------------------------
+def test_step_replayed_from_a_hip_graph():
+    B, Hq, Hkv, D, Z, T_len = 4, 12, 4, 128, 64, 600
+    dtype = T.TEMPO_BF16
+    q, K, V = host_inputs(10, B, T_len, Hq, Hkv, D, dtype)
+    st = BlockStore(B, Hq, Hkv, D, Z, T_len - 1, dtype, fill="nan")
+    qd, Kd, Vd = dev(q, dtype), dev(K, dtype), dev(V, dtype)
+    t = T_len - 1
+    st.prefill(Kd, Vd, t - 1)
+    k_t, v_t = Kd[:, t].contiguous(), Vd[:, t].contiguous()
+    q_buf = qd[0].clone()
+    eager = st.step_causal(q_buf, k_t, v_t, st.new_out(), t).clone()
+    assert T.tempo_attn_plan(st.kv, B, Hq, t, 0).num_splits > 1      # partial + combine are both captured
+    out = st.new_out()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        st.step_causal(q_buf, k_t, v_t, out, t)                       # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    with torch.cuda.graph(graph):
+        st.step_causal(q_buf, k_t, v_t, out, t)
+    for rep in range(4):
+        out.zero_()
+        q_buf.copy_(qd[rep % 2])                                       # new query, same graph
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        want = st.step_causal(qd[rep % 2], k_t, v_t, st.new_out(), t)
+        assert torch.equal(out, want)
+    ref = oracle.attend(q[0].astype(np.float64), K.astype(np.float64), V.astype(np.float64), t, 0,
+                        1.0 / np.sqrt(D))
+    assert_close(eager, ref, dtype, "graph test eager")
