@@ -22,6 +22,13 @@
 // contraction slots per lane as {4c..4c+3, 16+4c..16+4c+3}.
 // Only G of the 16 head columns carry data (G = 3 for the Llama shape): the MFMA
 // is mostly padding, which is free here -- the kernel is bound by HBM reads.
+//
+// Pipeline.  A wavefront owns ONE register image of a group (keys: 2*D/32 units,
+// values: D/16 units) and refills each half as soon as the MFMAs that read it
+// have been issued: the next group's keys are requested right after Q.K^T, its
+// values right after P.V.  About one group (16 KiB) per wavefront is therefore in
+// flight all the time, without a second register image; how many bytes a compute
+// unit keeps in flight is then set by the number of resident wavefronts.
 #include "tempo_internal.h"
 
 namespace tempo {
@@ -30,6 +37,12 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// The block table is not written while a launch is in flight.  Reading it
+// through the constant address space lets the compiler use scalar loads, whose
+// completion is tracked apart from the key/value vector loads, although the
+// kernel also stores to global memory.
+typedef const int32_t __attribute__((address_space(4))) * const_i32_ptr;
 
 __device__ inline bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
@@ -41,75 +54,94 @@ struct Group {
   u32x4 v[D / 16];
 };
 
-// Element offset, in either pool, of the 32-slot group `grp` of (sequence b, kv head hkv).
+template <int D>
+struct WaveState {
+  float m;              // running max (log2 units) of head lane&15
+  float l;              // running sum over this lane's slots
+  f32x4 acc[D / 16];    // lane (n + 16c): dims 16*dt + n of heads 4c..4c+3
+};
+
+// Element offset, in either pool, of 32-slot group `grp` of (sequence b, kv head hkv).
 template <int D>
 __device__ inline int64_t group_base(const AttnParams& p, int b, int hkv, int grp) {
-  const int j0 = grp << 5;
-  const int tile = j0 >> p.z_log2;
   const int Z = 1 << p.z_log2;
-  int phys = p.block_table[(int64_t)b * p.max_blocks_per_seq + tile];
-  phys = __builtin_amdgcn_readfirstlane(clamp_block(phys, p.num_blocks));
-  return (((int64_t)phys * p.Hkv + hkv) << p.z_log2) * D + (int64_t)(j0 & (Z - 1)) * D;
+  const_i32_ptr table = (const_i32_ptr)p.block_table;
+  const int entry = table[(int64_t)b * p.max_blocks_per_seq + ((grp << 5) >> p.z_log2)];
+  const int phys = clamp_block(entry, p.num_blocks);
+  return (((int64_t)phys * p.Hkv + hkv) << p.z_log2) * D + (int64_t)((grp << 5) & (Z - 1)) * D;
+}
+
+// Keys and values are read once per step and never again by this kernel:
+// non-temporal loads keep them from displacing anything in the caches.
+template <int D>
+__device__ inline void load_keys(const AttnParams& p, int64_t base, int lane, Group<D>& g) {
+  const u32x4* kp = reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(p.k_pool) + base) + lane;
+#pragma unroll
+  for (int i = 0; i < 2 * (D / 32); ++i) g.k[i] = __builtin_nontemporal_load(kp + i * 64);
 }
 
 template <int D>
-__device__ inline void load_group(const AttnParams& p, int b, int hkv, int grp, int lane, Group<D>& g) {
-  const int64_t base = group_base<D>(p, b, hkv, grp);
-  const u32x4* kp = reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(p.k_pool) + base) + lane;
+__device__ inline void load_values(const AttnParams& p, int64_t base, int lane, Group<D>& g) {
   const u32x4* vp = reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(p.v_pool) + base) + lane;
-  // Keys and values are read once per step and never again by this kernel:
-  // non-temporal loads keep them from displacing anything in the caches.
-#pragma unroll
-  for (int i = 0; i < 2 * (D / 32); ++i) g.k[i] = __builtin_nontemporal_load(kp + i * 64);
 #pragma unroll
   for (int i = 0; i < D / 16; ++i) g.v[i] = __builtin_nontemporal_load(vp + i * 64);
 }
 
-// Fused block-store write (Section 6, "in-place writes"): step t's own key and
-// value arrive in k_new / v_new.  The wavefront that owns the group holding slot
-// t stages those two rows in LDS when it starts (stage_new_row), and when it
-// reaches that group it puts them into the group's register image, so that this
-// step attends over them, and into the pool, so that later steps do.
+// ---- fused block-store write (Section 6, "in-place writes") --------------------
+// Step t's own key and value arrive in k_new / v_new.  The wavefront that owns the
+// group holding slot t fetches those two rows when it starts, and when it reaches
+// that group it puts them into the group's register image, so that this step
+// attends over them, and into the pool, so that later steps do.
+
+// Lanes 0..D/8-1 fetch the new key row, the next D/8 lanes the new value row, 16
+// bytes each.  Nothing waits for this load until the group is reached.
 template <int D>
-__device__ inline void stage_new_row(const AttnParams& p, int b, int hkv, int lane, uint16_t* stage) {
-  // lanes 0..D/8-1 fetch the key row, the next D/8 lanes the value row, 16 bytes each
+__device__ inline u32x4 fetch_new_row(const AttnParams& p, int b, int hkv, int lane) {
   constexpr int UNITS = D / 8;
+  u32x4 v = {0u, 0u, 0u, 0u};
   if (lane < 2 * UNITS) {
     const uint16_t* src = static_cast<const uint16_t*>(lane < UNITS ? p.k_new : p.v_new) +
                           ((int64_t)b * p.Hkv + hkv) * D + (lane % UNITS) * 8;
-    *reinterpret_cast<u32x4*>(stage + lane * 8) = *reinterpret_cast<const u32x4*>(src);
+    v = *reinterpret_cast<const u32x4*>(src);
   }
+  return v;
 }
 
+// Keys: lanes (row + 16c) hold the units of slot `row`; patch them, then the whole
+// wavefront writes the group's key image back as full 1 KiB units (the other slots
+// are rewritten with the values just read -- nobody else writes this sequence's
+// group -- so the pool sees whole cache lines, not 16-byte fragments).
 template <int D>
-__device__ __forceinline__ void append_into_group(const AttnParams& p, int b, int hkv, int t_b, int lane,
-                                         const uint16_t* stage, Group<D>& g) {
+__device__ __forceinline__ void append_keys(const AttnParams& p, int64_t base, int t_b, int lane,
+                                            u32x4 fetched, uint16_t* stage, Group<D>& g) {
   constexpr int KS = D / 32;
-  constexpr int DT = D / 16;
   const int u = t_b & 31, row = u & 15, tile = u >> 4;
   const int n = lane & 15, c = lane >> 4;
-  const int64_t base = group_base<D>(p, b, hkv, t_b >> 5);
-  const uint16_t* kn = stage;       // [D] staged key row
-  const uint16_t* vn = stage + D;   // [D] staged value row
-  // Keys: lanes (row + 16c) hold the units of slot `row`; patch them, then the
-  // whole wavefront writes the group's key image back as full 1 KiB units (the
-  // other slots are rewritten with the values just read -- nobody else writes
-  // this sequence's group -- so the pool sees whole cache lines, not 16-byte
-  // fragments).
-  u32x4* kp = reinterpret_cast<u32x4*>(static_cast<uint16_t*>(p.k_pool) + base) + lane;
+  // the two fetched rows go through LDS to reach the lanes that need them
+  if (lane < 2 * (D / 8)) *reinterpret_cast<u32x4*>(stage + lane * 8) = fetched;
   if (n == row) {
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
-      const u32x4 val = *reinterpret_cast<const u32x4*>(kn + 32 * s + 8 * c);
+      const u32x4 val = *reinterpret_cast<const u32x4*>(stage + 32 * s + 8 * c);
       g.k[s] = tile == 0 ? val : g.k[s];
       g.k[KS + s] = tile == 1 ? val : g.k[KS + s];
     }
   }
+  u32x4* kp = reinterpret_cast<u32x4*>(static_cast<uint16_t*>(p.k_pool) + base) + lane;
 #pragma unroll
   for (int i = 0; i < 2 * KS; ++i) kp[i * 64] = g.k[i];  // both row-tiles: static register indices
-  // Values: lanes (n + 16c) with c = row>>2 hold dim 16dt+n of the 8 slots that
-  // include slot t; patch that 16-bit element and write the 16-byte unit back
-  // (16 lanes x 16 bytes = 256 contiguous bytes per column tile).
+}
+
+// Values: lanes (n + 16c) with c = row>>2 hold dim 16dt+n of the 8 slots that
+// include slot t; patch that 16-bit element and write the 16-byte unit back
+// (16 lanes x 16 bytes = 256 contiguous bytes per column tile).  Called after
+// append_keys of the same group, which staged the value row at stage[D..2D).
+template <int D>
+__device__ __forceinline__ void append_values(const AttnParams& p, int64_t base, int t_b, int lane,
+                                              const uint16_t* stage, Group<D>& g) {
+  constexpr int DT = D / 16;
+  const int u = t_b & 31, row = u & 15, tile = u >> 4;
+  const int n = lane & 15, c = lane >> 4;
   if (c == (row >> 2)) {
     const int e = (row & 3) + 4 * tile;  // position of slot t among the lane's 8 slots
     u32x4* vp = reinterpret_cast<u32x4*>(static_cast<uint16_t*>(p.v_pool) + base) + lane;
@@ -117,7 +149,7 @@ __device__ __forceinline__ void append_into_group(const AttnParams& p, int b, in
     const uint32_t keep = (e & 1) ? 0x0000FFFFu : 0xFFFF0000u;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
-      const uint32_t val = vn[16 * dt + n];
+      const uint32_t val = stage[D + 16 * dt + n];
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
         const uint32_t patched = (g.v[dt][w] & keep) | (val << shift);
@@ -128,51 +160,50 @@ __device__ __forceinline__ void append_into_group(const AttnParams& p, int b, in
   }
 }
 
-template <int D>
-struct WaveState {
-  float m;              // running max (log2 units) of head lane&15
-  float l;              // running sum over this lane's slots
-  f32x4 acc[D / 16];    // lane (n + 16c): dims 16*dt + n of heads 4c..4c+3
-};
+// ---- the phases of a group ---------------------------------------------------------
 
+// Q.K^T for the group's two row tiles; logits in base-2 units.
 template <int D>
-__device__ inline void consume_group(const AttnParams& p, int grp, int start, int end, int lane,
-                                     const u32x4* qreg, Group<D>& g, WaveState<D>& st) {
+__device__ inline void logits_of_group(const AttnParams& p, const u32x4* qreg, const Group<D>& g, float* x) {
   constexpr int KS = D / 32;
-  constexpr int DT = D / 16;
-  const int c = lane >> 4;
   f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int s = 0; s < KS; ++s) {
     sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(g.k[s]), as_bf16x8(qreg[s]), sa, 0, 0, 0);
     sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(g.k[KS + s]), as_bf16x8(qreg[s]), sb, 0, 0, 0);
   }
-  float x[8];
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
     x[r] = sa[r] * p.scale_log2e;
     x[4 + r] = sb[r] * p.scale_log2e;
   }
+}
+
+// Index masks for a group cut by lo, by t, or by the split's ends (wave-uniform
+// branch): -inf on the logits; `keep` = bit masks that zero the value slots.
+__device__ inline bool edge_masks(int grp, int start, int end, int lane, float* x, uint32_t* keep) {
   const int j0 = grp << 5;
-  if (j0 < start || j0 + 31 > end) {  // wave-uniform: a group cut by lo, by t, or by the split
-    uint32_t keep[4];
+  if (j0 >= start && j0 + 31 <= end) return false;
+  const int c = lane >> 4;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int ja = j0 + 4 * c + r, jb = ja + 16;
-      const bool va = ja >= start && ja <= end, vb = jb >= start && jb <= end;
-      x[r] = va ? x[r] : -INFINITY;          // -inf mask under the max
-      x[4 + r] = vb ? x[4 + r] : -INFINITY;
-      // value slot e of this lane: e<4 -> slot 4c+e, e>=4 -> slot 16+4c+e-4
-      const uint32_t ma = va ? 0xFFFFu : 0u, mb = vb ? 0xFFFFu : 0u;
-      if ((r & 1) == 0) { keep[r >> 1] = ma; keep[2 + (r >> 1)] = mb; }
-      else { keep[r >> 1] |= ma << 16; keep[2 + (r >> 1)] |= mb << 16; }
-    }
-    // 0 mask under the sums: unwritten slots may hold NaN, and 0 * NaN is NaN
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt) {
-      g.v[dt].x &= keep[0]; g.v[dt].y &= keep[1]; g.v[dt].z &= keep[2]; g.v[dt].w &= keep[3];
-    }
+  for (int r = 0; r < 4; ++r) {
+    const int ja = j0 + 4 * c + r, jb = ja + 16;
+    const bool va = ja >= start && ja <= end, vb = jb >= start && jb <= end;
+    x[r] = va ? x[r] : -INFINITY;          // -inf mask under the max
+    x[4 + r] = vb ? x[4 + r] : -INFINITY;
+    // value slot e of this lane: e<4 -> slot 4c+e, e>=4 -> slot 16+4c+e-4
+    const uint32_t ma = va ? 0xFFFFu : 0u, mb = vb ? 0xFFFFu : 0u;
+    if ((r & 1) == 0) { keep[r >> 1] = ma; keep[2 + (r >> 1)] = mb; }
+    else { keep[r >> 1] |= ma << 16; keep[2 + (r >> 1)] |= mb << 16; }
   }
+  return true;
+}
+
+// Online-softmax update of (m, l), rescale of acc, and the bf16 weights of this group.
+template <int D>
+__device__ inline bf16x8 softmax_update(const float* x, int lane, WaveState<D>& st) {
+  constexpr int DT = D / 16;
+  const int c = lane >> 4;
   float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
   mx = fmaxf(mx, __shfl_xor(mx, 16));
   mx = fmaxf(mx, __shfl_xor(mx, 32));
@@ -198,9 +229,7 @@ __device__ inline void consume_group(const AttnParams& p, int grp, int start, in
       for (int r = 0; r < 4; ++r) st.acc[dt][r] *= a[r];
     }
   }
-#pragma unroll
-  for (int dt = 0; dt < DT; ++dt)
-    st.acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, as_bf16x8(g.v[dt]), st.acc[dt], 0, 0, 0);
+  return pa;
 }
 
 template <int D>
@@ -212,7 +241,7 @@ __global__ __launch_bounds__(512) void attn_partial_bf16(AttnParams p) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nwaves = blockDim.x >> 6;
   const int hkv = blockIdx.x, b = blockIdx.y;
-  int t_b = p.t_per_seq ? p.t_per_seq[b] : p.t;
+  int t_b = p.t_per_seq ? ((const_i32_ptr)p.t_per_seq)[b] : p.t;
   t_b = t_b > p.t ? p.t : (t_b < 0 ? 0 : t_b);
   const SeqRange rg = seq_range(t_b, p.window, p.tps_log2);
   if ((int)blockIdx.z >= rg.nchunks) return;  // uniform over the workgroup
@@ -227,16 +256,38 @@ __global__ __launch_bounds__(512) void attn_partial_bf16(AttnParams p) {
   const int end = rg.hi < ce ? rg.hi : ce;
   const int g_last = end >> 5;
 
+  // The first group's keys and values are requested before anything else.
+  int grp = (start >> 5) + wave;
+  Group<D> g;
+  int64_t base = 0;
+  if (grp <= g_last) {
+    base = group_base<D>(p, b, hkv, grp);
+    load_keys<D>(p, base, lane, g);
+    load_values<D>(p, base, lane, g);
+  }
+
+  // A fused append lands in group t_b>>5, which only the newest split holds; the
+  // wavefront that will reach that group fetches the new rows right away.  Its LDS
+  // staging area is a region of its own behind the wave-merge area.
+  int grp_new = -1;
+  uint16_t* stage = reinterpret_cast<uint16_t*>(smem + nwaves * (32 + p.G * D));
+  u32x4 fetched = {0u, 0u, 0u, 0u};
+  if (p.k_new && split == rg.nchunks - 1 && ((t_b >> 5) - grp) % nwaves == 0 && (t_b >> 5) >= grp) {
+    grp_new = t_b >> 5;
+    fetched = fetch_new_row<D>(p, b, hkv, lane);
+  }
+
   // Query operand: lane (j + 16c) holds dims 32s + 8c .. +7 of head j of the group (0 beyond G).
   u32x4 qreg[KS];
   {
     const int j = lane & 15, c = lane >> 4;
     const uint16_t* qp = static_cast<const uint16_t*>(p.q) +
-                         ((int64_t)b * p.Hq + (int64_t)hkv * p.G + j) * D + 8 * c;
+                         ((int64_t)b * p.Hq + (int64_t)hkv * p.G + (j < p.G ? j : 0)) * D + 8 * c;
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
       const u32x4 zero = {0u, 0u, 0u, 0u};
-      qreg[s] = j < p.G ? *reinterpret_cast<const u32x4*>(qp + 32 * s) : zero;
+      const u32x4 v = *reinterpret_cast<const u32x4*>(qp + 32 * s);
+      qreg[s] = j < p.G ? v : zero;
     }
   }
 
@@ -246,27 +297,34 @@ __global__ __launch_bounds__(512) void attn_partial_bf16(AttnParams p) {
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt) st.acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // One register image of a group per wavefront: load it, consume it, load the
-  // next.  Other wavefronts of the compute unit keep the memory pipe busy in the
-  // meantime; measured on MI355X this beats prefetching into a second image,
-  // which doubles the registers (occupancy 2 instead of 3 waves per SIMD) and
-  // puts more bytes in flight than the memory system rewards.
-  // A fused append lands in group t_b>>5, which only the newest split holds; the
-  // wavefront that will reach that group stages the new rows in LDS right away,
-  // in a region of its own behind the wave-merge area.
-  int grp = (start >> 5) + wave;
-  int grp_new = -1;
-  uint16_t* stage = reinterpret_cast<uint16_t*>(smem + nwaves * (32 + p.G * D));
-  if (p.k_new && split == rg.nchunks - 1 && ((t_b >> 5) - grp) % nwaves == 0 && (t_b >> 5) >= grp) {
-    grp_new = t_b >> 5;
-    stage_new_row<D>(p, b, hkv, lane, stage);
-  }
-  Group<D> g;
   while (grp <= g_last) {
-    load_group<D>(p, b, hkv, grp, lane, g);
-    if (grp == grp_new) append_into_group<D>(p, b, hkv, t_b, lane, stage, g);
-    consume_group<D>(p, grp, start, end, lane, qreg, g, st);
-    grp += nwaves;
+    const int nxt = grp + nwaves;
+    const bool more = nxt <= g_last;
+    const int64_t base_nxt = more ? group_base<D>(p, b, hkv, nxt) : 0;  // scalar loads, off the vector path
+    if (grp == grp_new) append_keys<D>(p, base, t_b, lane, fetched, stage, g);
+
+    float x[8];
+    logits_of_group<D>(p, qreg, g, x);
+    if (more) load_keys<D>(p, base_nxt, lane, g);  // the key registers are free again
+
+    uint32_t keep[4];
+    const bool cut = edge_masks(grp, start, end, lane, x, keep);
+    const bf16x8 pa = softmax_update<D>(x, lane, st);
+
+    if (grp == grp_new) append_values<D>(p, base, t_b, lane, stage, g);
+    if (cut) {  // 0 mask under the sums: unwritten slots may hold NaN, and 0 * NaN is NaN
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) {
+        g.v[dt].x &= keep[0]; g.v[dt].y &= keep[1]; g.v[dt].z &= keep[2]; g.v[dt].w &= keep[3];
+      }
+    }
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+      st.acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, as_bf16x8(g.v[dt]), st.acc[dt], 0, 0, 0);
+    if (more) load_values<D>(p, base_nxt, lane, g);  // the value registers are free again
+
+    grp = nxt;
+    base = base_nxt;
   }
 
   // Wave result -> LDS.  Heads live in lane&15 for (m, l) and in (4c + r) for acc.
@@ -283,10 +341,10 @@ __global__ __launch_bounds__(512) void attn_partial_bf16(AttnParams p) {
     const int n = lane & 15, c = lane >> 4;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const int g = 4 * c + r;
-      if (g < p.G) {
+      const int gq = 4 * c + r;
+      if (gq < p.G) {
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) sm_acc[(wave * p.G + g) * D + 16 * dt + n] = st.acc[dt][r];
+        for (int dt = 0; dt < DT; ++dt) sm_acc[(wave * p.G + gq) * D + 16 * dt + n] = st.acc[dt][r];
       }
     }
   }
@@ -294,18 +352,18 @@ __global__ __launch_bounds__(512) void attn_partial_bf16(AttnParams p) {
 
   // Merge the wavefronts of the workgroup (same rule the split combine uses).
   for (int idx = threadIdx.x; idx < p.G * D; idx += blockDim.x) {
-    const int g = idx / D, d = idx - g * D;
+    const int gq = idx / D, d = idx - gq * D;
     float M = -INFINITY;
-    for (int w = 0; w < nwaves; ++w) M = fmaxf(M, sm_m[w * 16 + g]);
+    for (int w = 0; w < nwaves; ++w) M = fmaxf(M, sm_m[w * 16 + gq]);
     float num = 0.f, den = 0.f;
     for (int w = 0; w < nwaves; ++w) {
-      const float mw = sm_m[w * 16 + g];
+      const float mw = sm_m[w * 16 + gq];
       if (mw == -INFINITY) continue;  // a wavefront that had no group
       const float wgt = fast_exp2(mw - M);
-      num += wgt * sm_acc[(w * p.G + g) * D + d];
-      den += wgt * sm_l[w * 16 + g];
+      num += wgt * sm_acc[(w * p.G + gq) * D + d];
+      den += wgt * sm_l[w * 16 + gq];
     }
-    const int64_t row = (int64_t)b * p.Hq + (int64_t)hkv * p.G + g;
+    const int64_t row = (int64_t)b * p.Hq + (int64_t)hkv * p.G + gq;
     if (p.direct) {
       static_cast<__bf16*>(p.out)[row * D + d] = (__bf16)(num / den);
     } else {

@@ -150,10 +150,21 @@ def _ptr(x):
     return int(x)
 
 
+_raw_stream = None
+
+
 def _stream(stream):
+    """hipStream_t of `stream` (a torch stream, a raw handle, or None = torch's current stream)."""
+    global _raw_stream
     if stream is None:
-        import torch
-        return torch.cuda.current_stream().cuda_stream
+        if _raw_stream is None:
+            import torch
+            fast = getattr(torch._C, "_cuda_getCurrentRawStream", None)
+            if fast is not None:
+                _raw_stream = lambda: fast(torch.cuda.current_device())
+            else:
+                _raw_stream = lambda: torch.cuda.current_stream().cuda_stream
+        return _raw_stream()
     return _ptr(getattr(stream, "cuda_stream", stream))
 
 

@@ -337,7 +337,7 @@ def test_llama_shape_causal_bf16_full_size():
     ref = oracle.attend(np64(q), K64, V64, t, 0, 1.0 / np.sqrt(D))
     assert_close(out, ref, dtype, "llama causal fused step t=4095")
     plan = T.tempo_attn_plan(st.kv, B, Hq, t, 0)
-    assert (plan.tokens_per_split, plan.num_splits, plan.waves) == (2048, 2, 4)
+    assert (plan.tokens_per_split, plan.num_splits, plan.waves) == (2048, 2, 8)
     kg, vg = st.gather(t, 1)
     assert torch.equal(kg[:, 0], K[:, t]) and torch.equal(vg[:, 0], V[:, t])
     steps = [0, 1, 31, 32, 255, 256, 257, 1000, 2047, 2048, 3000, 4094, 4095]
