@@ -85,6 +85,23 @@ def other_workloads(torch, T, BlockStore, synth, dev, kv_bytes_per_token):
     del sts
     torch.cuda.empty_cache()
 
+    # the same window on a ring (window) store: 4 blocks per sequence whatever t is
+    sts = []
+    for layer in range(8):
+        st = BlockStore(16, Hq, Hkv, D, Z, 2**30, T.TEMPO_BF16, device=dev, ring_blocks=4)
+        st.k_pool.normal_()
+        st.v_pool.normal_()
+        sts.append(st)
+    o = sts[0].new_out()
+    t = 1000000
+    dt = _timed(torch, lambda i: sts[i % 8].step_window(q16, k16, v16, o, t, 512), 200, 20)
+    out[f"window512_ring4_b16_t{t}"] = {"us_per_step": round(dt * 1e6, 2),
+                                        "kv_gbs": round(16 * 512 * kv_bytes_per_token / dt / 1e9, 1),
+                                        "pool_mib_per_layer": round(2 * sts[0].k_pool.numel() * 2 / 2**20, 1),
+                                        "linear_store_would_need_mib": round(16 * (t // Z + 1) * Hkv * Z * D * 2 * 2 / 2**20, 1)}
+    del sts
+    torch.cuda.empty_cache()
+
     # long single sequence
     sts = layers(8, 1, 65535)
     q1, k1, v1 = q16[:1].contiguous(), k16[:1].contiguous(), v16[:1].contiguous()

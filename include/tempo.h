@@ -56,7 +56,8 @@ typedef enum {
   TEMPO_OK = 0,
   TEMPO_ERR_NULL = -1,      /* a required pointer is NULL */
   TEMPO_ERR_SHAPE = -2,     /* unsupported head_dim / block_size / head counts / batch */
-  TEMPO_ERR_RANGE = -3,     /* t < 0, window < 1, or step t does not fit max_blocks_per_seq */
+  TEMPO_ERR_RANGE = -3,     /* t < 0, window < 1, step t does not fit max_blocks_per_seq, or a
+                               ring store no longer holds the visible range */
   TEMPO_ERR_WORKSPACE = -4, /* workspace NULL, misaligned or too small */
   TEMPO_ERR_DTYPE = -5,     /* dtype is not a tempo_dtype */
   TEMPO_ERR_LAUNCH = -6     /* the HIP runtime refused a launch */
@@ -92,7 +93,23 @@ typedef struct tempo_kv {
   int32_t num_kv_heads;       /* Hkv */
   int32_t head_dim;           /* D */
   int32_t dtype;              /* tempo_dtype of pools, q, k_new, v_new and out */
+  int32_t ring_blocks;        /* 0: linear store, tile n -> block_table[b][n].
+                                 R > 0 (a power of two, <= max_blocks_per_seq): window store,
+                                 tile n -> block_table[b][n mod R]; see below */
 } tempo_kv;
+
+/*
+ * Window store (Section 6: a window-accessed tensor lives in a pre-allocated
+ * circular buffer, so windowed decode runs in constant memory for any number of
+ * steps).  With ring_blocks = R a sequence owns R blocks that are reused in turn:
+ * step t is written to block_table[b][(t div Z) mod R], over the block that held
+ * steps t-R*Z.. .  No mirrored second write is needed: reads are per tile with index
+ * masks, never one contiguous slice.  A ring answers a step only if every tile of
+ * its visible range is still resident: windowed attention needs
+ * ceil((window-1)/Z)+1 <= R, causal attention needs (t div Z)+1 <= R; otherwise the
+ * attention entry points return TEMPO_ERR_RANGE.  tempo_kv_gather on a ring returns
+ * whatever the addressed slots hold now.
+ */
 
 /* How a step's visible range is cut into independent partial-attention work
  * items ("splits"), each a run of tokens_per_split consecutive key positions

@@ -66,7 +66,7 @@ template <int D>
 __device__ inline int64_t group_base(const AttnParams& p, int b, int hkv, int grp) {
   const int Z = 1 << p.z_log2;
   const_i32_ptr table = (const_i32_ptr)p.block_table;
-  const int entry = table[(int64_t)b * p.max_blocks_per_seq + ((grp << 5) >> p.z_log2)];
+  const int entry = table[(int64_t)b * p.max_blocks_per_seq + (((grp << 5) >> p.z_log2) & p.tile_mask)];
   const int phys = clamp_block(entry, p.num_blocks);
   return (((int64_t)phys * p.Hkv + hkv) << p.z_log2) * D + (int64_t)((grp << 5) & (Z - 1)) * D;
 }

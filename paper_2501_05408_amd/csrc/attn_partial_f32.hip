@@ -59,7 +59,7 @@ __global__ __launch_bounds__(512) void attn_partial_f32(AttnParams p) {
   // below only exchanges data inside one 16-lane row, whose lanes share j.
   for (int j = start + 4 * wave + row; j <= end; j += 4 * nwaves) {
     const int tile = j >> p.z_log2, slot = j & (Z - 1);
-    const int phys = clamp_block(p.block_table[(int64_t)b * p.max_blocks_per_seq + tile], p.num_blocks);
+    const int phys = clamp_block(p.block_table[(int64_t)b * p.max_blocks_per_seq + (tile & p.tile_mask)], p.num_blocks);
     const int64_t off = ((int64_t)phys * p.Hkv + hkv) * Z * D + (int64_t)slot * D + col * E;
     const bool fresh = kn != nullptr && j == t_b;  // uniform over the 16-lane row
     const float* ksrc = fresh ? kn + col * E : kpool + off;

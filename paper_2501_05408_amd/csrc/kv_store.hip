@@ -31,7 +31,7 @@ __global__ __launch_bounds__(256) void kv_append_bf16(StoreParams p, const uint1
   const int t = step_of(p, b);
   const int Z = 1 << p.z_log2;
   const int tile = t >> p.z_log2, slot = t & (Z - 1);
-  const int phys = clamp_block(p.block_table[(int64_t)b * p.max_blocks_per_seq + tile], p.num_blocks);
+  const int phys = clamp_block(p.block_table[(int64_t)b * p.max_blocks_per_seq + (tile & p.tile_mask)], p.num_blocks);
   const int64_t base = ((int64_t)phys * p.Hkv + head) * Z * D;
   uint16_t* vp = static_cast<uint16_t*>(p.v_pool);
   vp[base + tile_off_v_bf16(D, slot, d)] = v_new[idx];
@@ -55,7 +55,7 @@ __global__ __launch_bounds__(256) void kv_append_f32(StoreParams p, const float*
   const int t = step_of(p, b);
   const int Z = 1 << p.z_log2;
   const int tile = t >> p.z_log2, slot = t & (Z - 1);
-  const int phys = clamp_block(p.block_table[(int64_t)b * p.max_blocks_per_seq + tile], p.num_blocks);
+  const int phys = clamp_block(p.block_table[(int64_t)b * p.max_blocks_per_seq + (tile & p.tile_mask)], p.num_blocks);
   const int64_t off = ((int64_t)phys * p.Hkv + head) * Z * D + tile_off_f32(D, slot, d);
   const int64_t src = ((int64_t)b * p.Hkv + head) * D + d;
   *reinterpret_cast<float4*>(static_cast<float*>(p.k_pool) + off) =
@@ -78,7 +78,7 @@ __global__ __launch_bounds__(256) void kv_gather(StoreParams p, T* __restrict__ 
   const int j = j0 + jj;
   const int Z = 1 << p.z_log2;
   const int tile = j >> p.z_log2, slot = j & (Z - 1);
-  const int phys = clamp_block(p.block_table[(int64_t)b * p.max_blocks_per_seq + tile], p.num_blocks);
+  const int phys = clamp_block(p.block_table[(int64_t)b * p.max_blocks_per_seq + (tile & p.tile_mask)], p.num_blocks);
   const int64_t base = ((int64_t)phys * p.Hkv + head) * Z * D;
   if (k_out) {
     const int64_t off = kBf16 ? tile_off_k_bf16(D, slot, d) : tile_off_f32(D, slot, d);

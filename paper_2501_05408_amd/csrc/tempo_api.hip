@@ -28,6 +28,9 @@ int check_layout(const tempo_kv* kv) {
   if (kv->dtype == TEMPO_F32 && kv->block_size < 4) return TEMPO_ERR_SHAPE;
   if (kv->num_kv_heads < 1 || kv->num_kv_heads > 65535) return TEMPO_ERR_SHAPE;
   if (kv->num_blocks < 1 || kv->max_blocks_per_seq < 1) return TEMPO_ERR_SHAPE;
+  if (kv->ring_blocks != 0 &&
+      (ilog2_exact(kv->ring_blocks) < 0 || kv->ring_blocks > kv->max_blocks_per_seq))
+    return TEMPO_ERR_SHAPE;
   return TEMPO_OK;
 }
 
@@ -45,11 +48,27 @@ int check_heads(const tempo_kv* kv, int32_t batch, int32_t Hq) {
   return TEMPO_OK;
 }
 
+// A linear store must have a table column for step t's tile; a ring store reuses
+// its columns, so any step can be written.
 int check_step(const tempo_kv* kv, int32_t t) {
   if (t < 0) return TEMPO_ERR_RANGE;
-  if (t / kv->block_size >= kv->max_blocks_per_seq) return TEMPO_ERR_RANGE;
+  if (kv->ring_blocks == 0 && t / kv->block_size >= kv->max_blocks_per_seq) return TEMPO_ERR_RANGE;
   return TEMPO_OK;
 }
+
+// What a ring store can still answer: every tile of the visible range of step t
+// (and of any earlier step with the same window) must be resident, i.e. the range
+// may touch at most ring_blocks tiles.
+int check_ring_covers(const tempo_kv* kv, int32_t t, int32_t window) {
+  if (kv->ring_blocks == 0) return TEMPO_OK;
+  const int64_t Z = kv->block_size;
+  int64_t tiles;
+  if (window == 0 || window > (int64_t)t + 1) tiles = t / Z + 1;           // the whole history
+  else tiles = window <= 1 ? 1 : ((int64_t)window - 2 + Z) / Z + 1;         // worst alignment
+  return tiles <= kv->ring_blocks ? TEMPO_OK : TEMPO_ERR_RANGE;
+}
+
+int32_t tile_mask_of(const tempo_kv* kv) { return kv->ring_blocks ? kv->ring_blocks - 1 : INT32_MAX; }
 
 // Upper bound of the number of splits any step t' <= t can need with this tps.
 int32_t splits_bound(int32_t t, int32_t window, int tps_log2) {
@@ -167,6 +186,7 @@ AttnParams attn_params(const tempo_kv* kv, const void* q, void* out, int32_t Hq,
   p.window = window;
   p.z_log2 = ilog2_exact(kv->block_size);
   p.max_blocks_per_seq = kv->max_blocks_per_seq;
+  p.tile_mask = tile_mask_of(kv);
   p.num_blocks = kv->num_blocks;
   p.Hkv = kv->num_kv_heads;
   p.Hq = Hq;
@@ -187,6 +207,7 @@ StoreParams store_params(const tempo_kv* kv, int32_t batch, int32_t t, const int
   p.t = t;
   p.z_log2 = ilog2_exact(kv->block_size);
   p.max_blocks_per_seq = kv->max_blocks_per_seq;
+  p.tile_mask = tile_mask_of(kv);
   p.num_blocks = kv->num_blocks;
   p.Hkv = kv->num_kv_heads;
   p.batch = batch;
@@ -207,6 +228,7 @@ int check_attn(const tempo_kv* kv, int32_t batch, int32_t Hq, int32_t t, int32_t
   if ((rc = check_heads(kv, batch, Hq)) != TEMPO_OK) return rc;
   if (window < 0) return TEMPO_ERR_RANGE;
   if ((rc = check_step(kv, t)) != TEMPO_OK) return rc;
+  if ((rc = check_ring_covers(kv, t, window)) != TEMPO_OK) return rc;
   if ((rc = check_plan(plan, t, window, ragged)) != TEMPO_OK) return rc;
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return TEMPO_ERR_WORKSPACE;
   if (workspace_bytes < plan_bytes(kv, batch, Hq, plan->num_splits)) return TEMPO_ERR_WORKSPACE;
@@ -364,6 +386,7 @@ int tempo_kv_gather(const tempo_kv* kv, void* k_out, void* v_out, int32_t batch,
   if (count == 0) return TEMPO_OK;
   if ((int64_t)j0 + count - 1 > INT32_MAX) return TEMPO_ERR_RANGE;
   if ((rc = check_step(kv, j0 + count - 1)) != TEMPO_OK) return rc;
+  if (kv->ring_blocks && (int64_t)count > (int64_t)kv->ring_blocks * kv->block_size) return TEMPO_ERR_RANGE;
   const StoreParams p = store_params(kv, batch, 0, nullptr);
   const hipError_t e = launch_gather(p, k_out, v_out, kv->head_dim, kv->dtype, j0, count,
                                      static_cast<hipStream_t>(stream));

@@ -53,6 +53,7 @@ struct StoreParams {
   int32_t t;                 // uniform step / upper bound
   int32_t z_log2;
   int32_t max_blocks_per_seq;
+  int32_t tile_mask;         // ring_blocks-1 for a ring store, INT32_MAX otherwise: table column = tile & mask
   int32_t num_blocks;
   int32_t Hkv;
   int32_t batch;
@@ -73,6 +74,7 @@ struct AttnParams {
   int32_t window;            // 0 = causal
   int32_t z_log2;
   int32_t max_blocks_per_seq;
+  int32_t tile_mask;         // as in StoreParams
   int32_t num_blocks;
   int32_t Hkv;
   int32_t Hq;

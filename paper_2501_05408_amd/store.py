@@ -24,12 +24,15 @@ class BlockStore:
     """
 
     def __init__(self, batch, num_q_heads, num_kv_heads, head_dim, block_size, max_t, dtype,
-                 device="cuda:0", num_blocks=None, block_table=None, fill="zero", pools=None):
+                 device="cuda:0", num_blocks=None, block_table=None, fill="zero", pools=None,
+                 ring_blocks=0):
         self.batch, self.Hq, self.Hkv, self.D, self.Z = batch, num_q_heads, num_kv_heads, head_dim, block_size
         self.dtype = dtype
         self.device = torch.device(device)
-        self.max_blocks_per_seq = max_t // block_size + 1
-        self.max_t = self.max_blocks_per_seq * block_size - 1
+        self.ring_blocks = ring_blocks
+        # a ring (window) store keeps ring_blocks blocks per sequence whatever max_t is
+        self.max_blocks_per_seq = ring_blocks if ring_blocks else max_t // block_size + 1
+        self.max_t = max_t if ring_blocks else self.max_blocks_per_seq * block_size - 1
         self.num_blocks = num_blocks if num_blocks is not None else batch * self.max_blocks_per_seq
         tdt = _TORCH_DTYPE[dtype]
         shape = (self.num_blocks, num_kv_heads, block_size * head_dim)
@@ -48,7 +51,7 @@ class BlockStore:
         self.block_table = block_table.to(device=self.device, dtype=torch.int32).contiguous()
         assert tuple(self.block_table.shape) == (batch, self.max_blocks_per_seq)
         self.kv = T.make_kv(self.k_pool, self.v_pool, self.block_table, self.num_blocks,
-                            self.max_blocks_per_seq, block_size, num_kv_heads, head_dim, dtype)
+                            self.max_blocks_per_seq, block_size, num_kv_heads, head_dim, dtype, ring_blocks)
         self.workspace_bytes = T.tempo_attn_workspace_bytes(self.kv, batch, num_q_heads, self.max_t)
         self.workspace = torch.zeros(self.workspace_bytes, dtype=torch.uint8, device=self.device)
         self.scale = 1.0 / math.sqrt(head_dim)

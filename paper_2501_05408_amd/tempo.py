@@ -39,6 +39,7 @@ class tempo_kv(ctypes.Structure):
         ("num_kv_heads", ctypes.c_int32),
         ("head_dim", ctypes.c_int32),
         ("dtype", ctypes.c_int32),
+        ("ring_blocks", ctypes.c_int32),
     ]
 
 
@@ -174,10 +175,10 @@ def _check(rc: int, where: str):
 
 
 def make_kv(k_pool, v_pool, block_table, num_blocks, max_blocks_per_seq, block_size, num_kv_heads,
-            head_dim, dtype) -> tempo_kv:
+            head_dim, dtype, ring_blocks=0) -> tempo_kv:
     """Fill a tempo_kv descriptor; the caller keeps the tensors alive."""
     return tempo_kv(_ptr(k_pool), _ptr(v_pool), _ptr(block_table), num_blocks, max_blocks_per_seq,
-                    block_size, num_kv_heads, head_dim, dtype)
+                    block_size, num_kv_heads, head_dim, dtype, ring_blocks)
 
 
 # ---- pure host functions -------------------------------------------------------

@@ -312,6 +312,52 @@ def test_fused_step_ragged(dtype):
 
 
 # ----------------------------------------------------------------------------
+# Window store: a ring of R blocks per sequence, reused in turn, answers windowed
+# decode for any number of steps in constant memory -- same bits as the linear
+# store, and the oracle's values.
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,Z,R,window", [(T.TEMPO_BF16, 64, 4, 150), (T.TEMPO_BF16, 32, 2, 33),
+                                              (T.TEMPO_F32, 16, 4, 40), (T.TEMPO_BF16, 64, 4, 193)])
+@pytest.mark.parametrize("fused", [False, True])
+def test_ring_store_windowed_decode(dtype, Z, R, window, fused):
+    B, Hq, Hkv, D, steps = 2, 6, 2, 128, 700
+    q, K, V = host_inputs(12, B, steps, Hq, Hkv, D, dtype)
+    ring_table = torch.from_numpy(synth.permutation(12, 3, B * R).reshape(B, R).copy())
+    ring = BlockStore(B, Hq, Hkv, D, Z, steps - 1, dtype, num_blocks=B * R, block_table=ring_table,
+                      fill="nan", ring_blocks=R)
+    flat = BlockStore(B, Hq, Hkv, D, Z, steps - 1, dtype, fill="nan")
+    assert ring.k_pool.numel() == B * R * Hkv * Z * D          # constant memory
+    qd, Kd, Vd = dev(q, dtype), dev(K, dtype), dev(V, dtype)
+    o_ring = torch.empty((steps, B, Hq, D), dtype=TDT[dtype], device=DEV)
+    o_flat = torch.empty_like(o_ring)
+    for t in range(steps):
+        k_t, v_t = Kd[:, t].contiguous(), Vd[:, t].contiguous()
+        if fused:
+            ring.step_window(qd[t], k_t, v_t, o_ring[t], t, window)
+            flat.step_window(qd[t], k_t, v_t, o_flat[t], t, window)
+        else:
+            ring.append(k_t, v_t, t)
+            flat.append(k_t, v_t, t)
+            ring.attend_window(qd[t], o_ring[t], t, window)
+            flat.attend_window(qd[t], o_flat[t], t, window)
+    torch.cuda.synchronize()
+    assert torch.equal(o_ring, o_flat)
+    got = np64(o_ring)
+    K64, V64 = K.astype(np.float64), V.astype(np.float64)
+    for t in list(range(0, steps, 13)) + [R * Z - 1, R * Z, R * Z + 1, steps - 1]:
+        ref = oracle.attend(q[t].astype(np.float64), K64, V64, t, window, 1.0 / np.sqrt(D))
+        assert_close(got[t], ref, dtype, f"ring store t={t}")
+    # the ring holds the last R*Z steps at most; the newest ones read back exactly
+    kg, vg = ring.gather(steps - Z, Z)
+    assert torch.equal(kg, Kd[:, steps - Z:]) and torch.equal(vg, Vd[:, steps - Z:])
+    # a window the ring cannot hold any more is refused, not answered wrongly
+    with pytest.raises(T.TempoError):
+        ring.attend_window(qd[0], ring.new_out(), steps - 1, (R - 1) * Z + 2)
+    with pytest.raises(T.TempoError):
+        ring.attend_causal(qd[0], ring.new_out(), steps - 1)
+
+
+# ----------------------------------------------------------------------------
 # Full-size workloads, in the launch configuration the benchmark times.
 # Keys/values are drawn on the GPU (seeded), appended through the ABI, and the
 # oracle reads the same values back from the flat tensors.

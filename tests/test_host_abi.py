@@ -48,8 +48,8 @@ def test_visible_range_and_slot_match_oracle_bit_exact():
         T.tempo_append_slot(3, 0)
 
 
-def kv_desc(dtype, D=128, Z=64, Hkv=2, num_blocks=3, max_blocks=4, pools=(1 << 20, 1 << 21, 1 << 22)):
-    return T.tempo_kv(pools[0], pools[1], pools[2], num_blocks, max_blocks, Z, Hkv, D, dtype)
+def kv_desc(dtype, D=128, Z=64, Hkv=2, num_blocks=3, max_blocks=4, pools=(1 << 20, 1 << 21, 1 << 22), ring=0):
+    return T.tempo_kv(pools[0], pools[1], pools[2], num_blocks, max_blocks, Z, Hkv, D, dtype, ring)
 
 
 @pytest.mark.parametrize("D", [64, 128])
@@ -153,6 +153,26 @@ def test_bad_arguments_are_refused_before_any_launch():
 
     assert window(good, 0) == T.TEMPO_ERR_RANGE
     assert window(good, -3) == T.TEMPO_ERR_RANGE
+
+    # ring (window) stores: size must be a power of two within the table row; a step is
+    # answered only while every tile of its visible range is still resident
+    assert append(kv_desc(T.TEMPO_BF16, ring=3)) == T.TEMPO_ERR_SHAPE
+    assert append(kv_desc(T.TEMPO_BF16, ring=8)) == T.TEMPO_ERR_SHAPE          # row has 4 columns
+
+    def ring_window(t, w, ring=4):
+        kv = kv_desc(T.TEMPO_BF16, ring=ring)
+        return lib.tempo_attn_decode_window(ctypes.byref(kv), fake, fake, 2, 6, t, None, w, 0.1, None, 0, None)
+
+    def ring_causal(t, ring=4):
+        kv = kv_desc(T.TEMPO_BF16, ring=ring)
+        return lib.tempo_attn_decode_causal(ctypes.byref(kv), fake, fake, 2, 6, t, None, 0.1, None, 0, None)
+
+    # Z = 64, ring of 4: a window of up to 3*64+1 keys always fits, 3*64+2 may touch 5 tiles
+    assert ring_window(100000, 193) == T.TEMPO_ERR_WORKSPACE                  # passes the ring check
+    assert ring_window(100000, 194) == T.TEMPO_ERR_RANGE
+    assert ring_window(100, 5000) == T.TEMPO_ERR_WORKSPACE                    # window longer than history: 2 tiles
+    assert ring_causal(255) == T.TEMPO_ERR_WORKSPACE
+    assert ring_causal(256) == T.TEMPO_ERR_RANGE
 
     bad_plan = T.tempo_plan(48, 1, 1)
     assert lib.tempo_attn_decode_partial(ctypes.byref(good), fake, None, None, 2, 6, 5, None, 0, 0.1,
