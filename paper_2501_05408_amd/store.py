@@ -52,7 +52,10 @@ class BlockStore:
         assert tuple(self.block_table.shape) == (batch, self.max_blocks_per_seq)
         self.kv = T.make_kv(self.k_pool, self.v_pool, self.block_table, self.num_blocks,
                             self.max_blocks_per_seq, block_size, num_kv_heads, head_dim, dtype, ring_blocks)
-        self.workspace_bytes = T.tempo_attn_workspace_bytes(self.kv, batch, num_q_heads, self.max_t)
+        # a ring store only ever answers ranges of at most ring_blocks * block_size keys,
+        # which may straddle one more 32-key split than a range that starts at 0
+        ws_t = ring_blocks * block_size + 32 if ring_blocks else self.max_t
+        self.workspace_bytes = T.tempo_attn_workspace_bytes(self.kv, batch, num_q_heads, ws_t)
         self.workspace = torch.zeros(self.workspace_bytes, dtype=torch.uint8, device=self.device)
         self.scale = 1.0 / math.sqrt(head_dim)
 
