@@ -84,19 +84,33 @@ int32_t splits_bound(int32_t t, int32_t window, int tps_log2) {
 constexpr int kComputeUnits = 256;
 constexpr int kMaxSplits = 1024;
 
-// What a workgroup costs before its first key arrives (kernel arguments, block
-// table entry, first loads: about 2 us), expressed in key positions streamed at
-// one compute unit's share of the bandwidth.
-constexpr int kPrologueTokens = 128;
+// Split planning: a small time model of the launch, in nanoseconds, with constants
+// measured on MI355X.
+//   - Workgroups are handed to compute units round-robin, so the busiest unit gets
+//     rounds = ceil(workgroups / units) of them, one after the other.
+//   - A unit streams keys/values at its share of what the memory system sustains for
+//     this access pattern (about 6.9 TB/s over all units), but never faster than
+//     about 40 GB/s, so fewer than ~170 busy units cannot use the whole bandwidth.
+//   - A launch pays about 2 us once before its first key arrives (dispatch, kernel
+//     arguments, block table, first loads), about 0.3 us per round (merge, partial
+//     write), and about 3 us for the combine launch if there is more than one split.
+// Short splits balance better; long splits mean fewer rounds, fewer partials and,
+// at one split, no combine at all.  Take the LONGEST split length whose estimate is
+// within 3% of the best one.
+constexpr double kSustainedBytesPerNs = 6900.0;  // whole part, GB/s
+constexpr double kUnitBytesPerNs = 40.0;         // one compute unit, GB/s
+constexpr double kLaunchNs = 2000.0, kRoundNs = 300.0, kCombineNs = 3000.0;
 
-// Split planning.  Workgroups are handed to compute units round-robin, so the
-// busiest unit gets ceil(workgroups / units) of them and the launch lasts about
-//     ceil(pairs * splits(tps) / units) * (tps + prologue)   key positions per unit.
-// Short splits balance better; long splits mean fewer prologues, fewer partials
-// and a cheaper combine.  Take the LONGEST split length whose estimate is within
-// 3% of the best one.  Measured on MI355X at the
-// Llama shape (batch 16, t = 4095): 2 splits of 2048 = one workgroup per unit
-// runs the partial kernel in 43.5 us, 16 splits of 256 in 45.7 us.
+double plan_cost_ns(int64_t pairs, int64_t splits, int64_t keys_per_split, int bytes_per_key) {
+  const int64_t workgroups = pairs * splits;
+  const int64_t busy = workgroups < kComputeUnits ? workgroups : kComputeUnits;
+  const double share = kSustainedBytesPerNs / (double)busy;
+  const double rate = share < kUnitBytesPerNs ? share : kUnitBytesPerNs;
+  const int64_t rounds = (workgroups + kComputeUnits - 1) / kComputeUnits;
+  return kLaunchNs + (double)rounds * (kRoundNs + (double)keys_per_split * bytes_per_key / rate) +
+         (splits > 1 ? kCombineNs : 0.0);
+}
+
 // Ragged batches (per-sequence steps below t_max) hold less work than the model
 // assumes and it is unevenly spread, so their splits are capped at 1024 keys to
 // keep the long sequences from becoming single long-running workgroups.
@@ -105,22 +119,23 @@ void make_plan(const tempo_kv* kv, int32_t batch, int32_t Hq, int32_t t_max, int
   // bf16 shares one key/value read across the query group; fp32 launches per query head.
   const int64_t pairs = (int64_t)batch * (kv->dtype == TEMPO_BF16 ? kv->num_kv_heads : Hq);
   const int64_t len = (window > 0 && window < (int64_t)t_max + 1) ? window : (int64_t)t_max + 1;
+  const int bytes_per_key = 2 * kv->head_dim * (kv->dtype == TEMPO_BF16 ? 2 : 4);  // K and V of one head
   const int k_max = ragged ? 10 : 30;
   int best_k = -1;
-  int64_t best_cost = INT64_MAX;
-  int64_t costs[26];
-  for (int k = 5; k <= 30; ++k) costs[k - 5] = INT64_MAX;
+  double best_cost = -1.0;
+  double costs[26];
+  for (int k = 5; k <= 30; ++k) costs[k - 5] = -1.0;
   for (int k = 5; k <= k_max; ++k) {
     const int64_t splits = splits_bound(t_max, window, k);
     if (splits > kMaxSplits) continue;
     const int64_t tps = (int64_t)1 << k;
     const int64_t per_split = tps < len ? tps : len;  // a split never holds more than the range
-    costs[k - 5] = ((pairs * splits + kComputeUnits - 1) / kComputeUnits) * (per_split + kPrologueTokens);
-    if (costs[k - 5] < best_cost) best_cost = costs[k - 5];
+    costs[k - 5] = plan_cost_ns(pairs, splits, per_split, bytes_per_key);
+    if (best_cost < 0.0 || costs[k - 5] < best_cost) best_cost = costs[k - 5];
     if (splits == 1) break;  // longer splits change nothing
   }
   for (int k = 5; k <= k_max; ++k) {
-    if (costs[k - 5] != INT64_MAX && costs[k - 5] <= best_cost + best_cost * 3 / 100) best_k = k;
+    if (costs[k - 5] >= 0.0 && costs[k - 5] <= best_cost * 1.03) best_k = k;
   }
   if (best_k < 0) {  // a ragged range too long for 1024 splits of 1024 keys: lengthen until it fits
     best_k = k_max;
