@@ -73,6 +73,27 @@ def other_workloads(torch, T, BlockStore, synth, dev, kv_bytes_per_token):
             sts.append(st)
         return sts
 
+    # block of 5 query steps (5 x 3 heads = 15 of the 16 tile columns) over the headline
+    # shape: append 5 steps, then one attention call answers steps 4091..4095
+    sts = layers(8, 16, 4095)
+    qb = synth.device_normal((16, 5, Hq, D), 77, torch.bfloat16, dev)
+    kb = synth.device_normal((16, 5, Hkv, D), 78, torch.bfloat16, dev)
+    vb = synth.device_normal((16, 5, Hkv, D), 79, torch.bfloat16, dev)
+    ob = torch.empty_like(qb)
+
+    def block_step(i):
+        sts[i % 8].append_block(kb, vb, 4091, 5)
+        sts[i % 8].attend_block(qb, ob, 4091, 5)
+
+    dt = _timed(torch, block_step, 200, 20)
+    plan = T.tempo_attn_block_plan(sts[0].kv, 16, Hq, 5, 4091, 0)
+    out["block5_b16_t4091"] = {"us_per_call": round(dt * 1e6, 2), "us_per_query_step": round(dt * 1e6 / 5, 2),
+                               "kv_gbs": round(16 * 4096 * kv_bytes_per_token / dt / 1e9, 1),
+                               "splits": plan.num_splits, "tokens_per_split": plan.tokens_per_split,
+                               "waves": plan.waves}
+    del sts
+    torch.cuda.empty_cache()
+
     # sliding window 512, batch 16, steady state (t >= 511), unaligned window position
     sts = layers(8, 16, 16383)
     o = sts[0].new_out()

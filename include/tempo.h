@@ -228,6 +228,53 @@ int tempo_decode_step_window(const tempo_kv* kv, const void* q, const void* k_ne
                              void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Block of queries (Section 2: the block access pattern and prompt processing;
+ * Section 4.3: a tile of timesteps evaluated together).  `queries` = C consecutive
+ * steps t .. t+C-1 of every sequence are answered by one call: query c attends
+ * over keys 0 .. t+c (causal) or max(0, t+c-window+1) .. t+c (window), exactly as
+ * C single-step calls would, while the keys and values are read once.  The store
+ * must already hold keys/values up to step t+C-1 (tempo_kv_append_block).
+ *   q, out   device, [batch][queries][num_q_heads][head_dim], kv->dtype
+ *   t        first step of the block (uniform), or with t_per_seq the upper bound of
+ *            the per-sequence first steps t_per_seq[b]
+ * Limits: queries >= 1 and queries * (num_q_heads / num_kv_heads) <= 16
+ * (TEMPO_ERR_SHAPE otherwise).  workspace: device, 256-byte aligned, at least
+ * tempo_attn_block_workspace_bytes(kv, batch, num_q_heads, queries, t) bytes.
+ * Other arguments, launches and errors as tempo_attn_decode_causal / _window.
+ */
+int tempo_attn_block_causal(const tempo_kv* kv, const void* q, void* out, int32_t batch,
+                            int32_t num_q_heads, int32_t queries, int32_t t,
+                            const int32_t* t_per_seq, float scale, void* workspace,
+                            size_t workspace_bytes, void* stream);
+
+int tempo_attn_block_window(const tempo_kv* kv, const void* q, void* out, int32_t batch,
+                            int32_t num_q_heads, int32_t queries, int32_t t,
+                            const int32_t* t_per_seq, int32_t window, float scale, void* workspace,
+                            size_t workspace_bytes, void* stream);
+
+/* The plan tempo_attn_block_* use for a block whose first step is t_max (host
+ * only): tempo_attn_plan for the union of the queries' ranges, with fewer
+ * wavefronts where the per-column accumulators would not fit the workgroup's LDS.
+ * Its workspace holds batch * queries * num_q_heads rows of num_splits partials. */
+int tempo_attn_block_plan(const tempo_kv* kv, int32_t batch, int32_t num_q_heads, int32_t queries,
+                          int32_t t_max, int32_t window, int32_t ragged, tempo_plan* plan);
+
+/* Workspace bound for blocks of `queries` steps whose first step is at most max_t
+ * (host only; 0 on unsupported arguments). */
+size_t tempo_attn_block_workspace_bytes(const tempo_kv* kv, int32_t batch, int32_t num_q_heads,
+                                        int32_t queries, int32_t max_t);
+
+/*
+ * In-place write of `count` consecutive steps per sequence (Section 6, block
+ * store): row c of sequence b goes to step t + c (t_per_seq[b] + c if given, with
+ * t their upper bound).  k_new, v_new: device, [batch][count][num_kv_heads][head_dim].
+ * A ring store accepts at most ring_blocks * block_size steps per call.  Errors as
+ * tempo_kv_append, for every step of the block.
+ */
+int tempo_kv_append_block(const tempo_kv* kv, const void* k_new, const void* v_new, int32_t batch,
+                          int32_t t, const int32_t* t_per_seq, int32_t count, void* stream);
+
+/*
  * Partial attention and split combine as two separate launches, with an explicit
  * plan (for profiling one kernel at a time and for sweeping plans).  window = 0
  * is causal.  k_new / v_new are both NULL (the pool already holds step t) or both

@@ -56,12 +56,15 @@ __device__ inline void combine_heads(const float* ml, const float* acc, int S, i
         float mb = mr;
 #pragma unroll
         for (int u = 0; u < U; ++u) mb = fmaxf(mb, m[u]);
-        const float keep = exp2f(mr - mb);  // first batch: exp2f(-inf) = 0
+        // With a block of queries a split may hold no key of this row (m = -inf,
+        // l = acc = 0); while nothing finite has been seen, weigh against 0.
+        const float ref = mb == -INFINITY ? 0.f : mb;
+        const float keep = exp2f(mr - ref);  // first batch: exp2f(-inf) = 0
         lr *= keep;
         ar.x *= keep; ar.y *= keep; ar.z *= keep; ar.w *= keep;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-          const float w = exp2f(m[u] - mb);
+          const float w = exp2f(m[u] - ref);
           lr = fmaf(w, l[u], lr);
           ar.x = fmaf(w, a[u].x, ar.x); ar.y = fmaf(w, a[u].y, ar.y);
           ar.z = fmaf(w, a[u].z, ar.z); ar.w = fmaf(w, a[u].w, ar.w);

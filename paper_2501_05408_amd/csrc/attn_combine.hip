@@ -15,12 +15,12 @@ namespace {
 template <int D, bool kBf16>
 __global__ __launch_bounds__(256) void attn_combine(AttnParams p) {
   extern __shared__ float smem[];
-  const int hq = blockIdx.x, b = blockIdx.y;
+  const int b = blockIdx.y;  // blockIdx.x runs over the sequence's (query step, query head) rows
   int t_b = p.t_per_seq ? p.t_per_seq[b] : p.t;
   t_b = t_b > p.t ? p.t : (t_b < 0 ? 0 : t_b);
-  const SeqRange rg = seq_range(t_b, p.window, p.tps_log2);
+  const SeqRange rg = seq_range(t_b, p.window, p.tps_log2, p.queries);
   const int n = rg.nchunks < p.num_splits ? rg.nchunks : p.num_splits;
-  const int64_t row = (int64_t)b * p.Hq + hq;
+  const int64_t row = (int64_t)b * gridDim.x + blockIdx.x;
   const int esz = kBf16 ? 2 : 4;
   combine_heads<D, kBf16>(p.ws_ml + row * p.num_splits * 2, p.ws_acc + row * p.num_splits * D,
                                  p.num_splits, n, 1, static_cast<char*>(p.out) + row * D * esz, smem);
@@ -33,10 +33,10 @@ __global__ __launch_bounds__(256) void attn_combine_few(AttnParams p, int rows) 
   const int idx = blockIdx.x * 256 + threadIdx.x;
   const int row = idx / C4, c4 = idx - row * C4;
   if (row >= rows) return;
-  const int b = row / p.Hq;
+  const int b = row / (p.Hq * p.queries);
   int t_b = p.t_per_seq ? p.t_per_seq[b] : p.t;
   t_b = t_b > p.t ? p.t : (t_b < 0 ? 0 : t_b);
-  const SeqRange rg = seq_range(t_b, p.window, p.tps_log2);
+  const SeqRange rg = seq_range(t_b, p.window, p.tps_log2, p.queries);
   const int n = rg.nchunks < p.num_splits ? rg.nchunks : p.num_splits;  // 1..8
   const float* ml = p.ws_ml + (int64_t)row * p.num_splits * 2;
   const float* acc = p.ws_acc + (int64_t)row * p.num_splits * D + 4 * c4;
@@ -50,6 +50,8 @@ __global__ __launch_bounds__(256) void attn_combine_few(AttnParams p, int rows) 
     a[u] = *reinterpret_cast<const float4*>(acc + (int64_t)s * D);
     if (u >= n) m[u] = -INFINITY;
   }
+  // With a block of queries a split may hold no key of this row: its partial is
+  // (-inf, 0, 0) and gets weight 0.  Every row sees its own key, so M is finite.
   float M = m[0];
 #pragma unroll
   for (int u = 1; u < U; ++u) M = fmaxf(M, m[u]);
@@ -80,7 +82,7 @@ __global__ __launch_bounds__(256) void attn_combine_few(AttnParams p, int rows) 
 hipError_t launch_combine(const AttnParams& p, int batch, int D, int dtype, hipStream_t stream) {
   const dim3 block(256);
   if (p.num_splits <= 8) {
-    const int rows = batch * p.Hq;
+    const int rows = batch * p.queries * p.Hq;
     const dim3 few((unsigned)(((int64_t)rows * (D / 4) + 255) / 256));
     if (dtype == TEMPO_BF16) {
       if (D == 128) return launch((attn_combine_few<128, true>), few, block, 0, stream, p, rows);
@@ -90,7 +92,7 @@ hipError_t launch_combine(const AttnParams& p, int batch, int D, int dtype, hipS
       else return launch((attn_combine_few<64, false>), few, block, 0, stream, p, rows);
     }
   }
-  const dim3 grid(p.Hq, batch);
+  const dim3 grid(p.Hq * p.queries, batch);
   const size_t lds = (size_t)combine_lds_floats(256, D) * sizeof(float);
   if (dtype == TEMPO_BF16) {
     if (D == 128) return launch((attn_combine<128, true>), grid, block, lds, stream, p);

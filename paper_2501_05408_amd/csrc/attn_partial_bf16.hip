@@ -23,6 +23,11 @@
 // Only G of the 16 head columns carry data (G = 3 for the Llama shape): the MFMA
 // is mostly padding, which is free here -- the kernel is bound by HBM reads.
 //
+// Block of queries.  The 16 columns can also hold C consecutive query steps of
+// the G heads (column = c*G + g, C*G <= 16): step t+c sees keys up to t+c (and
+// from its own window start), which is one more per-lane bound in the index mask.
+// The keys and values are still read once, now for C steps.
+//
 // Pipeline.  A wavefront owns ONE register image of a group (keys: 2*D/32 units,
 // values: D/16 units) and refills each half as soon as the MFMAs that read it
 // have been issued: the next group's keys are requested right after Q.K^T, its
@@ -179,24 +184,25 @@ __device__ inline void logits_of_group(const AttnParams& p, const u32x4* qreg, c
   }
 }
 
-// Index masks for a group cut by lo, by t, or by the split's ends (wave-uniform
-// branch): -inf on the logits; `keep` = bit masks that zero the value slots.
-__device__ inline bool edge_masks(int grp, int start, int end, int lane, float* x, uint32_t* keep) {
+// Index masks for a group that some column's range cuts (wave-uniform decision by
+// the caller).  Logits: -inf outside THIS lane's column range [lo_col, hi_col].
+// Values: `keep` zeroes the slots outside [v_lo, v_hi], the union of all columns'
+// ranges (a slot another column still sees must keep its value; this column's
+// weight for it is exactly 0).
+__device__ inline void edge_masks(int grp, int lo_col, int hi_col, int v_lo, int v_hi, int lane, float* x,
+                                  uint32_t* keep) {
   const int j0 = grp << 5;
-  if (j0 >= start && j0 + 31 <= end) return false;
   const int c = lane >> 4;
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
     const int ja = j0 + 4 * c + r, jb = ja + 16;
-    const bool va = ja >= start && ja <= end, vb = jb >= start && jb <= end;
-    x[r] = va ? x[r] : -INFINITY;          // -inf mask under the max
-    x[4 + r] = vb ? x[4 + r] : -INFINITY;
+    x[r] = (ja >= lo_col && ja <= hi_col) ? x[r] : -INFINITY;          // -inf mask under the max
+    x[4 + r] = (jb >= lo_col && jb <= hi_col) ? x[4 + r] : -INFINITY;
     // value slot e of this lane: e<4 -> slot 4c+e, e>=4 -> slot 16+4c+e-4
-    const uint32_t ma = va ? 0xFFFFu : 0u, mb = vb ? 0xFFFFu : 0u;
+    const uint32_t ma = (ja >= v_lo && ja <= v_hi) ? 0xFFFFu : 0u, mb = (jb >= v_lo && jb <= v_hi) ? 0xFFFFu : 0u;
     if ((r & 1) == 0) { keep[r >> 1] = ma; keep[2 + (r >> 1)] = mb; }
     else { keep[r >> 1] |= ma << 16; keep[2 + (r >> 1)] |= mb << 16; }
   }
-  return true;
 }
 
 // Online-softmax update of (m, l), rescale of acc, and the bf16 weights of this group.
@@ -208,12 +214,15 @@ __device__ inline bf16x8 softmax_update(const float* x, int lane, WaveState<D>& 
   mx = fmaxf(mx, __shfl_xor(mx, 16));
   mx = fmaxf(mx, __shfl_xor(mx, 32));
   const float m_new = fmaxf(st.m, mx);
-  const float alpha = fast_exp2(st.m - m_new);  // first group: exp2(-inf) = 0
+  // A column may have seen no key yet (block of queries: a group beyond an early
+  // query's step): keep -inf as its max but exponentiate against 0, never -inf - -inf.
+  const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+  const float alpha = fast_exp2(st.m - m_ref);  // first keys of a column: exp2(-inf) = 0
   bf16x8 pa;
   float psum = 0.f;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    const __bf16 pb = (__bf16)fast_exp2(x[i] - m_new);
+    const __bf16 pb = (__bf16)fast_exp2(x[i] - m_ref);
     pa[i] = pb;
     psum += (float)pb;  // the sum uses the rounded weights, so out stays a convex combination
   }
@@ -243,7 +252,7 @@ __global__ __launch_bounds__(512) void attn_partial_bf16(AttnParams p) {
   const int hkv = blockIdx.x, b = blockIdx.y;
   int t_b = p.t_per_seq ? ((const_i32_ptr)p.t_per_seq)[b] : p.t;
   t_b = t_b > p.t ? p.t : (t_b < 0 ? 0 : t_b);
-  const SeqRange rg = seq_range(t_b, p.window, p.tps_log2);
+  const SeqRange rg = seq_range(t_b, p.window, p.tps_log2, p.queries);
   if ((int)blockIdx.z >= rg.nchunks) return;  // uniform over the workgroup
   // Dispatch order: the split index is the slowest grid dimension and runs from
   // the newest split to the oldest.  The newest split of every (sequence, head)
@@ -270,24 +279,39 @@ __global__ __launch_bounds__(512) void attn_partial_bf16(AttnParams p) {
   // wavefront that will reach that group fetches the new rows right away.  Its LDS
   // staging area is a region of its own behind the wave-merge area.
   int grp_new = -1;
-  uint16_t* stage = reinterpret_cast<uint16_t*>(smem + nwaves * (32 + p.G * D));
+  uint16_t* stage = reinterpret_cast<uint16_t*>(smem + nwaves * (32 + p.queries * p.G * D));
   u32x4 fetched = {0u, 0u, 0u, 0u};
   if (p.k_new && split == rg.nchunks - 1 && ((t_b >> 5) - grp) % nwaves == 0 && (t_b >> 5) >= grp) {
     grp_new = t_b >> 5;
     fetched = fetch_new_row<D>(p, b, hkv, lane);
   }
 
-  // Query operand: lane (j + 16c) holds dims 32s + 8c .. +7 of head j of the group (0 beyond G).
+  // Columns: j = cq*G + gq for query step cq and head gq of the group; ncols = C*G <= 16.
+  // Lanes of unused columns behave like the last query step and carry q = 0.
+  const int ncols = p.queries * p.G;
+  const int col = lane & 15;
+  const int cq = col < ncols ? col / p.G : p.queries - 1;
+  const int gq = col < ncols ? col - cq * p.G : 0;
+  // This column's own range, cut to the split; and the bounds that decide whether a
+  // group is cut by any column (a group inside [all_lo, all_hi] needs no mask).
+  const int hi_col = (t_b + cq) < end ? (t_b + cq) : end;
+  int lo_q = (p.window > 0 && t_b + cq - p.window + 1 > 0) ? t_b + cq - p.window + 1 : 0;
+  const int lo_col = lo_q > start ? lo_q : start;
+  int lo_last = (p.window > 0 && rg.hi - p.window + 1 > 0) ? rg.hi - p.window + 1 : 0;
+  const int all_lo = lo_last > start ? lo_last : start;
+  const int all_hi = t_b < end ? t_b : end;
+
+  // Query operand: lane (j + 16c) holds dims 32s + 8c .. +7 of column j (0 for unused columns).
   u32x4 qreg[KS];
   {
-    const int j = lane & 15, c = lane >> 4;
+    const int c = lane >> 4;
     const uint16_t* qp = static_cast<const uint16_t*>(p.q) +
-                         ((int64_t)b * p.Hq + (int64_t)hkv * p.G + (j < p.G ? j : 0)) * D + 8 * c;
+                         (((int64_t)b * p.queries + cq) * p.Hq + (int64_t)hkv * p.G + gq) * D + 8 * c;
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
       const u32x4 zero = {0u, 0u, 0u, 0u};
       const u32x4 v = *reinterpret_cast<const u32x4*>(qp + 32 * s);
-      qreg[s] = j < p.G ? v : zero;
+      qreg[s] = col < ncols ? v : zero;
     }
   }
 
@@ -308,7 +332,8 @@ __global__ __launch_bounds__(512) void attn_partial_bf16(AttnParams p) {
     if (more) load_keys<D>(p, base_nxt, lane, g);  // the key registers are free again
 
     uint32_t keep[4];
-    const bool cut = edge_masks(grp, start, end, lane, x, keep);
+    const bool cut = (grp << 5) < all_lo || (grp << 5) + 31 > all_hi;  // wave-uniform
+    if (cut) edge_masks(grp, lo_col, hi_col, start, end, lane, x, keep);
     const bf16x8 pa = softmax_update<D>(x, lane, st);
 
     if (grp == grp_new) append_values<D>(p, base, t_b, lane, stage, g);
@@ -327,12 +352,12 @@ __global__ __launch_bounds__(512) void attn_partial_bf16(AttnParams p) {
     base = base_nxt;
   }
 
-  // Wave result -> LDS.  Heads live in lane&15 for (m, l) and in (4c + r) for acc.
+  // Wave result -> LDS.  Columns live in lane&15 for (m, l) and in (4c + r) for acc.
   float l_tot = st.l + __shfl_xor(st.l, 16);
   l_tot += __shfl_xor(l_tot, 32);
   float* sm_m = smem;                       // [nwaves][16]
   float* sm_l = smem + nwaves * 16;         // [nwaves][16]
-  float* sm_acc = smem + nwaves * 32;       // [nwaves][G][D]
+  float* sm_acc = smem + nwaves * 32;       // [nwaves][ncols][D]
   if (lane < 16) {
     sm_m[wave * 16 + lane] = st.m;
     sm_l[wave * 16 + lane] = l_tot;
@@ -341,29 +366,31 @@ __global__ __launch_bounds__(512) void attn_partial_bf16(AttnParams p) {
     const int n = lane & 15, c = lane >> 4;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const int gq = 4 * c + r;
-      if (gq < p.G) {
+      const int j = 4 * c + r;
+      if (j < ncols) {
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) sm_acc[(wave * p.G + gq) * D + 16 * dt + n] = st.acc[dt][r];
+        for (int dt = 0; dt < DT; ++dt) sm_acc[(wave * ncols + j) * D + 16 * dt + n] = st.acc[dt][r];
       }
     }
   }
   __syncthreads();
 
-  // Merge the wavefronts of the workgroup (same rule the split combine uses).
-  for (int idx = threadIdx.x; idx < p.G * D; idx += blockDim.x) {
-    const int gq = idx / D, d = idx - gq * D;
+  // Merge the wavefronts of the workgroup (same rule the split combine uses).  A
+  // column that saw no key in this split leaves (m, l, acc) = (-inf, 0, 0).
+  for (int idx = threadIdx.x; idx < ncols * D; idx += blockDim.x) {
+    const int j = idx / D, d = idx - j * D;
     float M = -INFINITY;
-    for (int w = 0; w < nwaves; ++w) M = fmaxf(M, sm_m[w * 16 + gq]);
+    for (int w = 0; w < nwaves; ++w) M = fmaxf(M, sm_m[w * 16 + j]);
     float num = 0.f, den = 0.f;
     for (int w = 0; w < nwaves; ++w) {
-      const float mw = sm_m[w * 16 + gq];
-      if (mw == -INFINITY) continue;  // a wavefront that had no group
+      const float mw = sm_m[w * 16 + j];
+      if (mw == -INFINITY) continue;  // a wavefront that saw no key of this column
       const float wgt = fast_exp2(mw - M);
-      num += wgt * sm_acc[(w * p.G + gq) * D + d];
-      den += wgt * sm_l[w * 16 + gq];
+      num += wgt * sm_acc[(w * ncols + j) * D + d];
+      den += wgt * sm_l[w * 16 + j];
     }
-    const int64_t row = (int64_t)b * p.Hq + (int64_t)hkv * p.G + gq;
+    const int jc = j / p.G, jg = j - jc * p.G;
+    const int64_t row = ((int64_t)b * p.queries + jc) * p.Hq + (int64_t)hkv * p.G + jg;
     if (p.direct) {
       static_cast<__bf16*>(p.out)[row * D + d] = (__bf16)(num / den);
     } else {
@@ -384,7 +411,8 @@ hipError_t launch_partial_bf16(const AttnParams& p, int batch, int D, int grid_s
   const dim3 grid(p.Hkv, batch, grid_splits);
   const dim3 block(64 * waves);
   // wave-merge area, then room for one staged key row and one value row (bf16)
-  const size_t lds = (size_t)waves * (32 + (size_t)p.G * D) * sizeof(float) + 2 * (size_t)D * sizeof(uint16_t);
+  const size_t lds = (size_t)waves * (32 + (size_t)p.queries * p.G * D) * sizeof(float) +
+                     2 * (size_t)D * sizeof(uint16_t);
   if (D == 128) return launch(attn_partial_bf16<128>, grid, block, lds, stream, p);
   else return launch(attn_partial_bf16<64>, grid, block, lds, stream, p);
 }

@@ -5,7 +5,9 @@
 // 4.3 masks): running max m, running sum l and accumulator acc in fp32, base-2
 // units.  One workgroup = one (sequence, QUERY head, split): the fp32 path is the
 // small-shape, tight-tolerance path, so it keeps every product in fp32 and does
-// not share key/value reads across the query group.
+// not share key/value reads across the query group.  With a block of C query
+// steps the grid's first axis runs over (step, query head) and each workgroup
+// masks by its own step's range inside the split.
 //
 // A wavefront looks at 4 key positions at a time: 16 lanes per position, each
 // lane holding D/16 consecutive dims.  The dot product is a 16-lane butterfly
@@ -23,17 +25,20 @@ __global__ __launch_bounds__(512) void attn_partial_f32(AttnParams p) {
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int nwaves = blockDim.x >> 6;
-  const int hq = blockIdx.x, b = blockIdx.y;
+  const int cq = blockIdx.x / p.Hq, hq = blockIdx.x - cq * p.Hq, b = blockIdx.y;  // cq < p.queries
   const int hkv = hq / p.G;
   int t_b = p.t_per_seq ? p.t_per_seq[b] : p.t;
   t_b = t_b > p.t ? p.t : (t_b < 0 ? 0 : t_b);
-  const SeqRange rg = seq_range(t_b, p.window, p.tps_log2);
+  const SeqRange rg = seq_range(t_b, p.window, p.tps_log2, p.queries);
   if ((int)blockIdx.z >= rg.nchunks) return;
   const int split = rg.nchunks - 1 - (int)blockIdx.z;  // newest split first, as in the bf16 kernel
   const int chunk = rg.chunk0 + split;
   const int cs = chunk << p.tps_log2, ce = ((chunk + 1) << p.tps_log2) - 1;
-  const int start = rg.lo > cs ? rg.lo : cs;
-  const int end = rg.hi < ce ? rg.hi : ce;
+  // this query step's own range, cut to the split (empty if they do not meet)
+  const int t_q = t_b + cq;
+  const int lo_q = (p.window > 0 && t_q - p.window + 1 > 0) ? t_q - p.window + 1 : 0;
+  const int start = lo_q > cs ? lo_q : cs;
+  const int end = t_q < ce ? t_q : ce;
 
   const int row = lane >> 4, col = lane & 15;
   const int Z = 1 << p.z_log2;
@@ -47,7 +52,7 @@ __global__ __launch_bounds__(512) void attn_partial_f32(AttnParams p) {
 
   float qv[E];
   {
-    const float* qp = static_cast<const float*>(p.q) + ((int64_t)b * p.Hq + hq) * D + col * E;
+    const float* qp = static_cast<const float*>(p.q) + (((int64_t)b * p.queries + cq) * p.Hq + hq) * D + col * E;
 #pragma unroll
     for (int e = 0; e < E; ++e) qv[e] = qp[e];
   }
@@ -111,12 +116,12 @@ __global__ __launch_bounds__(512) void attn_partial_f32(AttnParams p) {
     float num = 0.f, den = 0.f;
     for (int i = 0; i < nrows; ++i) {
       const float mi = sm_m[i];
-      if (mi == -INFINITY) continue;  // a row that saw no key
+      if (mi == -INFINITY) continue;  // a row that saw no key (all rows: the partial is (-inf, 0, 0))
       const float wgt = exp2f(mi - M);
       num += wgt * sm_acc[i * D + d];
       den += wgt * sm_l[i];
     }
-    const int64_t qrow = (int64_t)b * p.Hq + hq;
+    const int64_t qrow = ((int64_t)b * p.queries + cq) * p.Hq + hq;
     if (p.direct) {
       static_cast<float*>(p.out)[qrow * D + d] = num / den;
     } else {
@@ -134,7 +139,7 @@ __global__ __launch_bounds__(512) void attn_partial_f32(AttnParams p) {
 
 hipError_t launch_partial_f32(const AttnParams& p, int batch, int D, int grid_splits, int waves,
                               hipStream_t stream) {
-  const dim3 grid(p.Hq, batch, grid_splits);
+  const dim3 grid(p.Hq * p.queries, batch, grid_splits);
   const dim3 block(64 * waves);
   const size_t lds = (size_t)waves * 4 * (2 + (size_t)D) * sizeof(float);
   if (D == 128) return launch(attn_partial_f32<128>, grid, block, lds, stream, p);

@@ -4,7 +4,9 @@
 // block-sized buffers that are written one timestep at a time, in place; its
 // "in-place writes" kernel wrapper lets the producer write at index t directly.
 // Here step t of sequence b goes to physical block block_table[b][t div Z],
-// slot t mod Z (Section 4.3: tile n holds keys [nZ, (n+1)Z)).
+// slot t mod Z (Section 4.3: tile n holds keys [nZ, (n+1)Z)).  An append may
+// carry `count` consecutive steps per sequence (rows [B][count][Hkv][D]): row c
+// goes to step t + c.
 #include "tempo_internal.h"
 
 namespace tempo {
@@ -16,19 +18,20 @@ __device__ inline int step_of(const StoreParams& p, int b) {
   return t < 0 ? 0 : t;
 }
 
-// bf16: one thread per (b, head, d).  V is written element by element (the
+// bf16: one thread per (b, c, head, d).  V is written element by element (the
 // operand-major value layout interleaves 8 slots per 16-byte unit); the thread
 // with d % 8 == 0 also moves the 16-byte key unit that starts at d.
 template <int D>
 __global__ __launch_bounds__(256) void kv_append_bf16(StoreParams p, const uint16_t* __restrict__ k_new,
                                                       const uint16_t* __restrict__ v_new) {
   const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-  const int total = p.batch * p.Hkv * D;
+  const int total = p.batch * p.count * p.Hkv * D;
   if (idx >= total) return;
   const int d = idx % D;
   const int head = (idx / D) % p.Hkv;
-  const int b = idx / (D * p.Hkv);
-  const int t = step_of(p, b);
+  const int c = (idx / (D * p.Hkv)) % p.count;
+  const int b = idx / (D * p.Hkv * p.count);
+  const int t = step_of(p, b) + c;
   const int Z = 1 << p.z_log2;
   const int tile = t >> p.z_log2, slot = t & (Z - 1);
   const int phys = clamp_block(p.block_table[(int64_t)b * p.max_blocks_per_seq + (tile & p.tile_mask)], p.num_blocks);
@@ -42,22 +45,23 @@ __global__ __launch_bounds__(256) void kv_append_bf16(StoreParams p, const uint1
   }
 }
 
-// f32: one thread per float4 of (b, head, d..d+3); both pools are row-major.
+// f32: one thread per float4 of (b, c, head, d..d+3); both pools are row-major.
 template <int D>
 __global__ __launch_bounds__(256) void kv_append_f32(StoreParams p, const float* __restrict__ k_new,
                                                      const float* __restrict__ v_new) {
   const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-  const int total = p.batch * p.Hkv * (D / 4);
+  const int total = p.batch * p.count * p.Hkv * (D / 4);
   if (idx >= total) return;
   const int d = (idx % (D / 4)) * 4;
   const int head = (idx / (D / 4)) % p.Hkv;
-  const int b = idx / ((D / 4) * p.Hkv);
-  const int t = step_of(p, b);
+  const int c = (idx / ((D / 4) * p.Hkv)) % p.count;
+  const int b = idx / ((D / 4) * p.Hkv * p.count);
+  const int t = step_of(p, b) + c;
   const int Z = 1 << p.z_log2;
   const int tile = t >> p.z_log2, slot = t & (Z - 1);
   const int phys = clamp_block(p.block_table[(int64_t)b * p.max_blocks_per_seq + (tile & p.tile_mask)], p.num_blocks);
   const int64_t off = ((int64_t)phys * p.Hkv + head) * Z * D + tile_off_f32(D, slot, d);
-  const int64_t src = ((int64_t)b * p.Hkv + head) * D + d;
+  const int64_t src = (((int64_t)b * p.count + c) * p.Hkv + head) * D + d;
   *reinterpret_cast<float4*>(static_cast<float*>(p.k_pool) + off) =
       *reinterpret_cast<const float4*>(k_new + src);
   *reinterpret_cast<float4*>(static_cast<float*>(p.v_pool) + off) =
@@ -96,14 +100,14 @@ hipError_t launch_append(const StoreParams& p, const void* k_new, const void* v_
                          int dtype, hipStream_t stream) {
   const int threads = 256;
   if (dtype == TEMPO_BF16) {
-    const int total = p.batch * p.Hkv * D;
+    const int total = p.batch * p.count * p.Hkv * D;
     const dim3 grid((total + threads - 1) / threads);
     const uint16_t* k = static_cast<const uint16_t*>(k_new);
     const uint16_t* v = static_cast<const uint16_t*>(v_new);
     if (D == 128) return launch(kv_append_bf16<128>, grid, dim3(threads), 0, stream, p, k, v);
     else return launch(kv_append_bf16<64>, grid, dim3(threads), 0, stream, p, k, v);
   } else {
-    const int total = p.batch * p.Hkv * (D / 4);
+    const int total = p.batch * p.count * p.Hkv * (D / 4);
     const dim3 grid((total + threads - 1) / threads);
     const float* k = static_cast<const float*>(k_new);
     const float* v = static_cast<const float*>(v_new);

@@ -48,6 +48,20 @@ int check_heads(const tempo_kv* kv, int32_t batch, int32_t Hq) {
   return TEMPO_OK;
 }
 
+// A block of C consecutive query steps shares the 16 columns of the bf16 kernel's
+// tiles with the query group: C * (Hq / Hkv) <= 16 (the same limit for fp32).
+int check_queries(const tempo_kv* kv, int32_t Hq, int32_t queries) {
+  if (queries < 1 || queries > 16) return TEMPO_ERR_SHAPE;
+  if ((int64_t)queries * (Hq / kv->num_kv_heads) > 16) return TEMPO_ERR_SHAPE;
+  if ((int64_t)queries * Hq > 65535) return TEMPO_ERR_SHAPE;
+  return TEMPO_OK;
+}
+
+// The steps a block of queries starting at t touches: the last step, and the
+// window measured from the last step that spans the union of the queries' ranges.
+int32_t last_step(int32_t t, int32_t queries) { return t + (queries - 1); }
+int32_t union_window(int32_t window, int32_t queries) { return window > 0 ? window + (queries - 1) : 0; }
+
 // A linear store must have a table column for step t's tile; a ring store reuses
 // its columns, so any step can be written.
 int check_step(const tempo_kv* kv, int32_t t) {
@@ -153,13 +167,14 @@ void make_plan(const tempo_kv* kv, int32_t batch, int32_t Hq, int32_t t_max, int
 }
 
 // A uniform step needs its own split count; ragged steps (any t' <= t) need the bound.
-int check_plan(const tempo_plan* plan, int32_t t, int32_t window, bool ragged) {
+int check_plan(const tempo_plan* plan, int32_t t, int32_t window, bool ragged, int32_t queries) {
   if (!plan) return TEMPO_ERR_NULL;
   const int k = ilog2_exact(plan->tokens_per_split);
   if (k < 5) return TEMPO_ERR_SHAPE;
   if (plan->waves != 1 && plan->waves != 2 && plan->waves != 4 && plan->waves != 8) return TEMPO_ERR_SHAPE;
   if (plan->num_splits < 1 || plan->num_splits > 65535) return TEMPO_ERR_SHAPE;
-  const int32_t need = ragged ? splits_bound(t, window, k) : seq_range(t, window, k).nchunks;
+  const int32_t need = ragged ? splits_bound(last_step(t, queries), union_window(window, queries), k)
+                              : seq_range(t, window, k, queries).nchunks;
   if (plan->num_splits < need) return TEMPO_ERR_RANGE;
   return TEMPO_OK;
 }
@@ -173,18 +188,24 @@ int launch_status(hipError_t e, const char* what) {
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-// Workspace = [m,l: batch*Hq*S*2 f32] [acc: batch*Hq*S*D f32], each part padded to 256 bytes.
-size_t ml_bytes(int32_t batch, int32_t Hq, int32_t S) {
-  return align_up((size_t)batch * Hq * S * 2 * sizeof(float), 256);
+// Workspace = [m,l: rows*S*2 f32] [acc: rows*S*D f32], each part padded to 256 bytes;
+// rows = batch * queries * Hq.
+size_t ml_bytes(int64_t rows, int32_t S) { return align_up((size_t)rows * S * 2 * sizeof(float), 256); }
+
+size_t plan_bytes(const tempo_kv* kv, int64_t rows, int32_t S) {
+  return ml_bytes(rows, S) + align_up((size_t)rows * S * kv->head_dim * sizeof(float), 256);
 }
 
-size_t plan_bytes(const tempo_kv* kv, int32_t batch, int32_t Hq, int32_t S) {
-  return ml_bytes(batch, Hq, S) + align_up((size_t)batch * Hq * S * kv->head_dim * sizeof(float), 256);
+// LDS of the bf16 partial kernel: per wavefront 32 floats of (m, l) and one
+// accumulator row per column, plus the two staged rows of a fused append.
+size_t partial_bf16_lds(int waves, int columns, int D) {
+  return (size_t)waves * (32 + (size_t)columns * D) * sizeof(float) + 2 * (size_t)D * sizeof(uint16_t);
 }
+constexpr size_t kMaxLds = 64 * 1024;
 
 AttnParams attn_params(const tempo_kv* kv, const void* q, void* out, int32_t Hq, int32_t t,
                        const int32_t* t_per_seq, int32_t window, float scale,
-                       const tempo_plan* plan, void* workspace, int32_t batch) {
+                       const tempo_plan* plan, void* workspace, int32_t batch, int32_t queries) {
   AttnParams p;
   p.k_pool = kv->k_pool;
   p.v_pool = kv->v_pool;
@@ -195,7 +216,7 @@ AttnParams attn_params(const tempo_kv* kv, const void* q, void* out, int32_t Hq,
   p.t_per_seq = t_per_seq;
   char* ws = static_cast<char*>(workspace);
   p.ws_ml = reinterpret_cast<float*>(ws);
-  p.ws_acc = reinterpret_cast<float*>(ws + ml_bytes(batch, Hq, plan->num_splits));
+  p.ws_acc = reinterpret_cast<float*>(ws + ml_bytes((int64_t)batch * queries * Hq, plan->num_splits));
   p.out = out;
   p.t = t;
   p.window = window;
@@ -208,12 +229,14 @@ AttnParams attn_params(const tempo_kv* kv, const void* q, void* out, int32_t Hq,
   p.G = Hq / kv->num_kv_heads;
   p.tps_log2 = ilog2_exact(plan->tokens_per_split);
   p.num_splits = plan->num_splits;
+  p.queries = queries;
   p.direct = 0;
   p.scale_log2e = scale * 1.44269504088896340736f;
   return p;
 }
 
-StoreParams store_params(const tempo_kv* kv, int32_t batch, int32_t t, const int32_t* t_per_seq) {
+StoreParams store_params(const tempo_kv* kv, int32_t batch, int32_t t, const int32_t* t_per_seq,
+                         int32_t count = 1) {
   StoreParams p;
   p.k_pool = kv->k_pool;
   p.v_pool = kv->v_pool;
@@ -226,27 +249,34 @@ StoreParams store_params(const tempo_kv* kv, int32_t batch, int32_t t, const int
   p.num_blocks = kv->num_blocks;
   p.Hkv = kv->num_kv_heads;
   p.batch = batch;
+  p.count = count;
   return p;
 }
 
 // Splits to launch along grid.x: exact for a uniform step, the bound for ragged steps.
-int32_t grid_splits(const tempo_plan* plan, int32_t t, const int32_t* t_per_seq, int32_t window) {
+int32_t grid_splits(const tempo_plan* plan, int32_t t, const int32_t* t_per_seq, int32_t window,
+                    int32_t queries) {
   if (t_per_seq) return plan->num_splits;
-  const int32_t exact = seq_range(t, window, ilog2_exact(plan->tokens_per_split)).nchunks;
+  const int32_t exact = seq_range(t, window, ilog2_exact(plan->tokens_per_split), queries).nchunks;
   return exact < plan->num_splits ? exact : plan->num_splits;
 }
 
 int check_attn(const tempo_kv* kv, int32_t batch, int32_t Hq, int32_t t, int32_t window, bool ragged,
-               const tempo_plan* plan, const void* workspace, size_t workspace_bytes) {
+               const tempo_plan* plan, const void* workspace, size_t workspace_bytes,
+               int32_t queries = 1) {
   int rc = check_store(kv);
   if (rc != TEMPO_OK) return rc;
   if ((rc = check_heads(kv, batch, Hq)) != TEMPO_OK) return rc;
-  if (window < 0) return TEMPO_ERR_RANGE;
-  if ((rc = check_step(kv, t)) != TEMPO_OK) return rc;
-  if ((rc = check_ring_covers(kv, t, window)) != TEMPO_OK) return rc;
-  if ((rc = check_plan(plan, t, window, ragged)) != TEMPO_OK) return rc;
+  if ((rc = check_queries(kv, Hq, queries)) != TEMPO_OK) return rc;
+  if (window < 0 || t < 0 || t > INT32_MAX - 64) return TEMPO_ERR_RANGE;
+  if ((rc = check_step(kv, last_step(t, queries))) != TEMPO_OK) return rc;
+  if ((rc = check_ring_covers(kv, last_step(t, queries), union_window(window, queries))) != TEMPO_OK) return rc;
+  if ((rc = check_plan(plan, t, window, ragged, queries)) != TEMPO_OK) return rc;
+  if (kv->dtype == TEMPO_BF16 &&
+      partial_bf16_lds(plan->waves, queries * (Hq / kv->num_kv_heads), kv->head_dim) > kMaxLds)
+    return TEMPO_ERR_SHAPE;
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return TEMPO_ERR_WORKSPACE;
-  if (workspace_bytes < plan_bytes(kv, batch, Hq, plan->num_splits)) return TEMPO_ERR_WORKSPACE;
+  if (workspace_bytes < plan_bytes(kv, (int64_t)batch * queries * Hq, plan->num_splits)) return TEMPO_ERR_WORKSPACE;
   return TEMPO_OK;
 }
 
@@ -255,12 +285,13 @@ int check_attn(const tempo_kv* kv, int32_t batch, int32_t Hq, int32_t t, int32_t
 // k_new/v_new != nullptr: step t's key/value are appended inside the same launch.
 int do_partial(const tempo_kv* kv, const void* q, const void* k_new, const void* v_new, void* out,
                int32_t batch, int32_t Hq, int32_t t, const int32_t* t_per_seq, int32_t window,
-               float scale, const tempo_plan* plan, void* workspace, hipStream_t stream) {
-  AttnParams p = attn_params(kv, q, out, Hq, t, t_per_seq, window, scale, plan, workspace, batch);
+               float scale, const tempo_plan* plan, void* workspace, hipStream_t stream,
+               int32_t queries = 1) {
+  AttnParams p = attn_params(kv, q, out, Hq, t, t_per_seq, window, scale, plan, workspace, batch, queries);
   p.direct = (out != nullptr && plan->num_splits == 1) ? 1 : 0;
   p.k_new = k_new;
   p.v_new = v_new;
-  const int32_t gs = grid_splits(plan, t, t_per_seq, window);
+  const int32_t gs = grid_splits(plan, t, t_per_seq, window, queries);
   const hipError_t e = kv->dtype == TEMPO_BF16
                            ? launch_partial_bf16(p, batch, kv->head_dim, gs, plan->waves, stream)
                            : launch_partial_f32(p, batch, kv->head_dim, gs, plan->waves, stream);
@@ -269,27 +300,39 @@ int do_partial(const tempo_kv* kv, const void* q, const void* k_new, const void*
 
 int do_combine(const tempo_kv* kv, void* out, int32_t batch, int32_t Hq, int32_t t,
                const int32_t* t_per_seq, int32_t window, const tempo_plan* plan, void* workspace,
-               hipStream_t stream) {
-  AttnParams p = attn_params(kv, nullptr, out, Hq, t, t_per_seq, window, 1.0f, plan, workspace, batch);
+               hipStream_t stream, int32_t queries = 1) {
+  AttnParams p = attn_params(kv, nullptr, out, Hq, t, t_per_seq, window, 1.0f, plan, workspace, batch, queries);
   const hipError_t e = launch_combine(p, batch, kv->head_dim, kv->dtype, stream);
   return launch_status(e, "attn_decode_combine");
 }
 
+// Plan of a block of queries: the plan of the union range, with the wavefront count
+// cut down until the bf16 kernel's wave-merge area (one accumulator row per column
+// and wavefront) fits the LDS a workgroup may ask for.
+void make_block_plan(const tempo_kv* kv, int32_t batch, int32_t Hq, int32_t t, int32_t window,
+                     bool ragged, int32_t queries, tempo_plan* plan) {
+  make_plan(kv, batch, Hq, last_step(t, queries), union_window(window, queries), ragged, plan);
+  if (kv->dtype != TEMPO_BF16) return;
+  const int columns = queries * (Hq / kv->num_kv_heads);
+  while (plan->waves > 1 && partial_bf16_lds(plan->waves, columns, kv->head_dim) > kMaxLds) plan->waves /= 2;
+}
+
 int decode(const tempo_kv* kv, const void* q, const void* k_new, const void* v_new, void* out,
            int32_t batch, int32_t Hq, int32_t t, const int32_t* t_per_seq, int32_t window, float scale,
-           void* workspace, size_t workspace_bytes, void* stream) {
+           void* workspace, size_t workspace_bytes, void* stream, int32_t queries = 1) {
   int rc = check_layout(kv);
   if (rc != TEMPO_OK) return rc;
   if (!q || !out) return TEMPO_ERR_NULL;
   if ((rc = check_heads(kv, batch, Hq)) != TEMPO_OK) return rc;
-  if (t < 0 || window < 0) return TEMPO_ERR_RANGE;
+  if ((rc = check_queries(kv, Hq, queries)) != TEMPO_OK) return rc;
+  if (t < 0 || window < 0 || t > INT32_MAX - 64) return TEMPO_ERR_RANGE;
   tempo_plan plan;
-  make_plan(kv, batch, Hq, t, window, t_per_seq != nullptr, &plan);
-  if ((rc = check_attn(kv, batch, Hq, t, window, t_per_seq != nullptr, &plan, workspace, workspace_bytes)) != TEMPO_OK) return rc;
+  make_block_plan(kv, batch, Hq, t, window, t_per_seq != nullptr, queries, &plan);
+  if ((rc = check_attn(kv, batch, Hq, t, window, t_per_seq != nullptr, &plan, workspace, workspace_bytes, queries)) != TEMPO_OK) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  rc = do_partial(kv, q, k_new, v_new, out, batch, Hq, t, t_per_seq, window, scale, &plan, workspace, s);
+  rc = do_partial(kv, q, k_new, v_new, out, batch, Hq, t, t_per_seq, window, scale, &plan, workspace, s, queries);
   if (rc != TEMPO_OK || plan.num_splits == 1) return rc;  // a single split wrote `out` itself
-  return do_combine(kv, out, batch, Hq, t, t_per_seq, window, &plan, workspace, s);
+  return do_combine(kv, out, batch, Hq, t, t_per_seq, window, &plan, workspace, s, queries);
 }
 
 }  // namespace
@@ -350,7 +393,7 @@ size_t tempo_attn_plan_workspace_bytes(const tempo_kv* kv, int32_t batch, int32_
                                        const tempo_plan* plan) {
   if (check_layout(kv) != TEMPO_OK || !plan) return 0;
   if (check_heads(kv, batch, num_q_heads) != TEMPO_OK || plan->num_splits < 1) return 0;
-  return plan_bytes(kv, batch, num_q_heads, plan->num_splits);
+  return plan_bytes(kv, (int64_t)batch * num_q_heads, plan->num_splits);
 }
 
 size_t tempo_attn_workspace_bytes(const tempo_kv* kv, int32_t batch, int32_t num_q_heads,
@@ -364,7 +407,30 @@ size_t tempo_attn_workspace_bytes(const tempo_kv* kv, int32_t batch, int32_t num
   // count at length 32, capped at the planner's own maximum, bounds them all.
   int64_t worst = splits_bound(max_t, 0, 5);
   if (worst > kMaxSplits) worst = kMaxSplits;
-  return plan_bytes(kv, batch, num_q_heads, (int32_t)worst);
+  return plan_bytes(kv, (int64_t)batch * num_q_heads, (int32_t)worst);
+}
+
+int tempo_attn_block_plan(const tempo_kv* kv, int32_t batch, int32_t num_q_heads, int32_t queries,
+                          int32_t t_max, int32_t window, int32_t ragged, tempo_plan* plan) {
+  int rc = check_layout(kv);
+  if (rc != TEMPO_OK) return rc;
+  if (!plan) return TEMPO_ERR_NULL;
+  if ((rc = check_heads(kv, batch, num_q_heads)) != TEMPO_OK) return rc;
+  if ((rc = check_queries(kv, num_q_heads, queries)) != TEMPO_OK) return rc;
+  if (t_max < 0 || t_max > INT32_MAX - 64 || window < 0 || window > INT32_MAX - 64) return TEMPO_ERR_RANGE;
+  make_block_plan(kv, batch, num_q_heads, t_max, window, ragged != 0, queries, plan);
+  return TEMPO_OK;
+}
+
+size_t tempo_attn_block_workspace_bytes(const tempo_kv* kv, int32_t batch, int32_t num_q_heads,
+                                        int32_t queries, int32_t max_t) {
+  if (check_layout(kv) != TEMPO_OK || max_t < 0 || max_t > INT32_MAX - 64) return 0;
+  if (check_heads(kv, batch, num_q_heads) != TEMPO_OK) return 0;
+  if (check_queries(kv, num_q_heads, queries) != TEMPO_OK) return 0;
+  // as tempo_attn_workspace_bytes, for the union range that ends at the last query's step
+  int64_t worst = splits_bound(last_step(max_t, queries), 0, 5);
+  if (worst > kMaxSplits) worst = kMaxSplits;
+  return plan_bytes(kv, (int64_t)batch * queries * num_q_heads, (int32_t)worst);
 }
 
 const char* tempo_strerror(int status) {
@@ -387,9 +453,27 @@ int tempo_kv_append(const tempo_kv* kv, const void* k_new, const void* v_new, in
   if (!k_new || !v_new) return TEMPO_ERR_NULL;
   if (batch < 1 || batch > 65535) return TEMPO_ERR_SHAPE;
   if ((rc = check_step(kv, t)) != TEMPO_OK) return rc;
+  if ((int64_t)batch * kv->num_kv_heads * kv->head_dim > INT32_MAX) return TEMPO_ERR_SHAPE;
   const StoreParams p = store_params(kv, batch, t, t_per_seq);
   const hipError_t e = launch_append(p, k_new, v_new, kv->head_dim, kv->dtype, static_cast<hipStream_t>(stream));
   return launch_status(e, "kv_append");
+}
+
+int tempo_kv_append_block(const tempo_kv* kv, const void* k_new, const void* v_new, int32_t batch,
+                          int32_t t, const int32_t* t_per_seq, int32_t count, void* stream) {
+  int rc = check_store(kv);
+  if (rc != TEMPO_OK) return rc;
+  if (!k_new || !v_new) return TEMPO_ERR_NULL;
+  if (batch < 1 || batch > 65535) return TEMPO_ERR_SHAPE;
+  if (count < 1 || count > 65536) return TEMPO_ERR_SHAPE;
+  if (t < 0 || t > INT32_MAX - count) return TEMPO_ERR_RANGE;
+  if ((rc = check_step(kv, t + count - 1)) != TEMPO_OK) return rc;
+  // a ring store must not wrap onto rows of the same call
+  if (kv->ring_blocks && (int64_t)count > (int64_t)kv->ring_blocks * kv->block_size) return TEMPO_ERR_RANGE;
+  if ((int64_t)batch * count * kv->num_kv_heads * kv->head_dim > INT32_MAX) return TEMPO_ERR_SHAPE;
+  const StoreParams p = store_params(kv, batch, t, t_per_seq, count);
+  const hipError_t e = launch_append(p, k_new, v_new, kv->head_dim, kv->dtype, static_cast<hipStream_t>(stream));
+  return launch_status(e, "kv_append_block");
 }
 
 int tempo_kv_gather(const tempo_kv* kv, void* k_out, void* v_out, int32_t batch, int32_t j0,
@@ -441,6 +525,22 @@ int tempo_decode_step_window(const tempo_kv* kv, const void* q, const void* k_ne
   if (window < 1) return TEMPO_ERR_RANGE;
   return decode(kv, q, k_new, v_new, out, batch, num_q_heads, t, t_per_seq, window, scale, workspace,
                 workspace_bytes, stream);
+}
+
+int tempo_attn_block_causal(const tempo_kv* kv, const void* q, void* out, int32_t batch,
+                            int32_t num_q_heads, int32_t queries, int32_t t, const int32_t* t_per_seq,
+                            float scale, void* workspace, size_t workspace_bytes, void* stream) {
+  return decode(kv, q, nullptr, nullptr, out, batch, num_q_heads, t, t_per_seq, 0, scale, workspace,
+                workspace_bytes, stream, queries);
+}
+
+int tempo_attn_block_window(const tempo_kv* kv, const void* q, void* out, int32_t batch,
+                            int32_t num_q_heads, int32_t queries, int32_t t, const int32_t* t_per_seq,
+                            int32_t window, float scale, void* workspace, size_t workspace_bytes,
+                            void* stream) {
+  if (window < 1 || window > INT32_MAX - 64) return TEMPO_ERR_RANGE;
+  return decode(kv, q, nullptr, nullptr, out, batch, num_q_heads, t, t_per_seq, window, scale, workspace,
+                workspace_bytes, stream, queries);
 }
 
 int tempo_attn_decode_partial(const tempo_kv* kv, const void* q, const void* k_new,

@@ -57,6 +57,7 @@ struct StoreParams {
   int32_t num_blocks;
   int32_t Hkv;
   int32_t batch;
+  int32_t count;             // append: consecutive steps per sequence, rows [B][count][Hkv][D]
 };
 
 struct AttnParams {
@@ -64,12 +65,12 @@ struct AttnParams {
   void* v_pool;
   const int32_t* block_table;
   const void* q;
-  const void* k_new;         // [B][Hkv][D]; non-null: append step t inside the attention kernel
+  const void* k_new;         // [B][Hkv][D]; non-null: append step t inside the attention kernel (queries == 1)
   const void* v_new;
   const int32_t* t_per_seq;  // may be null
-  float* ws_ml;              // [B][Hq][S][2]  (running max in log2 units, running sum)
-  float* ws_acc;             // [B][Hq][S][D]
-  void* out;                 // [B][Hq][D]
+  float* ws_ml;              // [B][C][Hq][S][2]  (running max in log2 units, running sum)
+  float* ws_acc;             // [B][C][Hq][S][D]
+  void* out;                 // [B][C][Hq][D]
   int32_t t;                 // uniform step / upper bound
   int32_t window;            // 0 = causal
   int32_t z_log2;
@@ -81,20 +82,23 @@ struct AttnParams {
   int32_t G;                 // Hq / Hkv
   int32_t tps_log2;          // log2(tokens per split)
   int32_t num_splits;        // S: stride of the split axis in the workspace
+  int32_t queries;           // C: consecutive query steps per sequence (q, out, workspace rows are [B][C][Hq])
   int32_t direct;            // 1: single split, write `out` and skip the combine
   float scale_log2e;         // s * log2(e)
 };
 
 // Visible range and split bookkeeping of one sequence, identical on host and device.
+// With a block of C queries (steps t_b .. t_b+C-1) the range is the union of the
+// queries' ranges: from the first query's lo to the last query's step.
 struct SeqRange {
   int lo, hi, chunk0, nchunks;
 };
-__host__ __device__ inline SeqRange seq_range(int t_b, int window, int tps_log2) {
+__host__ __device__ inline SeqRange seq_range(int t_b, int window, int tps_log2, int queries = 1) {
   SeqRange r;
-  r.hi = t_b;
+  r.hi = t_b + queries - 1;
   r.lo = (window > 0 && t_b - window + 1 > 0) ? t_b - window + 1 : 0;
   r.chunk0 = r.lo >> tps_log2;
-  r.nchunks = (t_b >> tps_log2) - r.chunk0 + 1;
+  r.nchunks = (r.hi >> tps_log2) - r.chunk0 + 1;
   return r;
 }
 

@@ -63,6 +63,10 @@ class BlockStore:
     def append(self, k_new, v_new, t, t_per_seq=None):
         T.tempo_kv_append(self.kv, k_new, v_new, self.batch, t, t_per_seq)
 
+    def append_block(self, k_new, v_new, t, count, t_per_seq=None):
+        """Write steps t .. t+count-1 (rows [batch][count][Hkv][D]) in one launch."""
+        T.tempo_kv_append_block(self.kv, k_new, v_new, self.batch, t, t_per_seq, count)
+
     def gather(self, j0, count):
         tdt = _TORCH_DTYPE[self.dtype]
         k = torch.empty((self.batch, count, self.Hkv, self.D), dtype=tdt, device=self.device)
@@ -98,6 +102,21 @@ class BlockStore:
                                    self.workspace_bytes)
         return out
 
+    def attend_block(self, q, out, t, queries, window=0, t_per_seq=None, scale=None):
+        """Steps t .. t+queries-1 in one call; q, out are [batch][queries][Hq][D]."""
+        ws_t = self.ring_blocks * self.Z + 32 if self.ring_blocks else self.max_t
+        nbytes = T.tempo_attn_block_workspace_bytes(self.kv, self.batch, self.Hq, queries, ws_t)
+        if getattr(self, "_block_ws", None) is None or self._block_ws.numel() < nbytes:
+            self._block_ws = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        s = self.scale if scale is None else scale
+        if window:
+            T.tempo_attn_block_window(self.kv, q, out, self.batch, self.Hq, queries, t, t_per_seq, window, s,
+                                      self._block_ws, nbytes)
+        else:
+            T.tempo_attn_block_causal(self.kv, q, out, self.batch, self.Hq, queries, t, t_per_seq, s,
+                                      self._block_ws, nbytes)
+        return out
+
     def attend_with_plan(self, q, out, t, plan, window=0, t_per_seq=None, scale=None):
         """Partial + combine with an explicit plan (its own workspace)."""
         nbytes = T.tempo_attn_plan_workspace_bytes(self.kv, self.batch, self.Hq, plan)
@@ -112,8 +131,12 @@ class BlockStore:
 
     def prefill(self, K, V, upto, lengths=None):
         """Write steps 0..upto of flat K, V ([batch][T][Hkv][D] device tensors)
-        into the pool, one tempo_kv_append per step.  With `lengths` (int32 device
-        tensor of per-sequence lengths) sequence b stops at its own last step."""
+        into the pool: one tempo_kv_append_block for a linear store, one
+        tempo_kv_append per step otherwise.  With `lengths` (int32 device tensor of
+        per-sequence lengths) sequence b stops at its own last step."""
+        if lengths is None and not self.ring_blocks:
+            self.append_block(K[:, :upto + 1].contiguous(), V[:, :upto + 1].contiguous(), 0, upto + 1)
+            return
         if lengths is None:
             for j in range(upto + 1):
                 self.append(K[:, j].contiguous(), V[:, j].contiguous(), j)

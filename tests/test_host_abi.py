@@ -118,6 +118,35 @@ def test_plan_covers_every_step_and_workspace_bound_holds():
                         assert T.tempo_attn_plan_workspace_bytes(kv, batch, Hq, plan) <= bound
 
 
+def test_block_plan_fits_its_workspace_bound_and_lds():
+    D = 128
+    for dtype, Hq, Hkv in ((T.TEMPO_BF16, 24, 8), (T.TEMPO_BF16, 16, 1), (T.TEMPO_BF16, 2, 2), (T.TEMPO_F32, 8, 2)):
+        G = Hq // Hkv
+        for queries in sorted({1, min(2, 16 // G), 16 // G}):
+            for batch in (1, 16, 64):
+                for max_t in (0, 40, 4095, 70000):
+                    kv = kv_desc(dtype, D=D, Hkv=Hkv, Z=64, max_blocks=(max_t + queries) // 64 + 1)
+                    bound = T.tempo_attn_block_workspace_bytes(kv, batch, Hq, queries, max_t)
+                    assert bound > 0 and bound % 256 == 0
+                    for t in sorted({0, max_t // 3, max(0, max_t - 1), max_t}):
+                        for w in (0, 1, 33, 512):
+                            for ragged in (False, True):
+                                plan = T.tempo_attn_block_plan(kv, batch, Hq, queries, t, w, ragged)
+                                tps = plan.tokens_per_split
+                                lo = 0 if w == 0 else max(0, t - w + 1)
+                                assert plan.num_splits >= (t + queries - 1) // tps - lo // tps + 1
+                                rows = batch * queries * Hq
+                                need = -(-rows * plan.num_splits * 8 // 256) * 256 + \
+                                    -(-rows * plan.num_splits * D * 4 // 256) * 256
+                                assert need <= bound
+                                if dtype == T.TEMPO_BF16:   # wave-merge area + staged rows within 64 KiB
+                                    assert plan.waves * (32 + queries * G * D) * 4 + 4 * D <= 65536
+    with pytest.raises(T.TempoError):
+        T.tempo_attn_block_plan(kv_desc(T.TEMPO_BF16, Hkv=2), 1, 8, 5, 10)      # 5 x 4 columns > 16
+    assert T.tempo_attn_block_workspace_bytes(kv_desc(T.TEMPO_BF16, Hkv=2), 1, 8, 5, 10) == 0
+    assert T.tempo_attn_block_workspace_bytes(kv_desc(T.TEMPO_BF16, Hkv=2), 1, 8, 0, 10) == 0
+
+
 def test_bad_arguments_are_refused_before_any_launch():
     lib = T.load()
     good = kv_desc(T.TEMPO_BF16)
@@ -173,6 +202,30 @@ def test_bad_arguments_are_refused_before_any_launch():
     assert ring_window(100, 5000) == T.TEMPO_ERR_WORKSPACE                    # window longer than history: 2 tiles
     assert ring_causal(255) == T.TEMPO_ERR_WORKSPACE
     assert ring_causal(256) == T.TEMPO_ERR_RANGE
+
+    def block(kv, queries, t=5, Hq=6, w=None):
+        if w is None:
+            return lib.tempo_attn_block_causal(ctypes.byref(kv), fake, fake, 2, Hq, queries, t, None, 0.1, None, 0, None)
+        return lib.tempo_attn_block_window(ctypes.byref(kv), fake, fake, 2, Hq, queries, t, None, w, 0.1, None, 0, None)
+
+    assert block(good, 0) == T.TEMPO_ERR_SHAPE
+    assert block(good, 6) == T.TEMPO_ERR_SHAPE                   # 6 steps x 3 heads > 16 columns
+    assert block(good, 5) == T.TEMPO_ERR_WORKSPACE               # everything else is fine
+    assert block(good, 5, t=4 * 64 - 5) == T.TEMPO_ERR_WORKSPACE  # last step is the store's last slot
+    assert block(good, 5, t=4 * 64 - 4) == T.TEMPO_ERR_RANGE     # last step needs a fifth block
+    assert block(good, 2, w=0) == T.TEMPO_ERR_RANGE
+    ringed = kv_desc(T.TEMPO_BF16, ring=4)
+    assert block(ringed, 1, t=100000, w=193) == T.TEMPO_ERR_WORKSPACE
+    assert block(ringed, 2, t=100000, w=193) == T.TEMPO_ERR_RANGE   # the union of two ranges may touch 5 tiles
+
+    def append_block(kv, count, t=0):
+        return lib.tempo_kv_append_block(ctypes.byref(kv), fake, fake, 2, t, None, count, None)
+
+    assert append_block(good, 0) == T.TEMPO_ERR_SHAPE
+    assert append_block(good, 4 * 64 + 1) == T.TEMPO_ERR_RANGE
+    assert append_block(good, 10, t=4 * 64 - 9) == T.TEMPO_ERR_RANGE
+    assert append_block(ringed, 4 * 64 + 1, t=7) == T.TEMPO_ERR_RANGE   # would wrap onto its own rows
+    assert lib.tempo_kv_append_block(ctypes.byref(good), None, fake, 2, 0, None, 3, None) == T.TEMPO_ERR_NULL
 
     bad_plan = T.tempo_plan(48, 1, 1)
     assert lib.tempo_attn_decode_partial(ctypes.byref(good), fake, None, None, 2, 6, 5, None, 0, 0.1,
