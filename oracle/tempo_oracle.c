@@ -27,7 +27,9 @@
  * Every function here is pinned by tests that do not call it to produce their
  * expected value (closed forms, a brute-force evaluator written differently,
  * the padded+masked formulation, the paper's tiled three-reduction form, the
- * paper's printed inverse-window example).  Nothing is "parity unpinned".
+ * paper's printed inverse-window example; for the rotary embedding: closed
+ * forms at chosen angles, norm preservation, the relative-position identity and
+ * composition of rotations).  Nothing is "parity unpinned".
  */
 #include <math.h>
 #include <stddef.h>
@@ -165,6 +167,53 @@ int tempo_oracle_attend(const double* q, const double* K, const double* V,
         for (int d = 0; d < D; ++d) ov[d] += p * vv[d];
       }
       for (int d = 0; d < D; ++d) ov[d] /= denom;
+    }
+  }
+  return 0;
+}
+
+/*
+ * Rotary position embedding of the producer step (the operation whose output the
+ * block store receives in place, Section 6 "in-place writes").  The paper names
+ * no position encoding; its decoding workload is a Llama-3.2 model, whose public
+ * definition rotates each head vector x of dimension D at position t by
+ *     angle_i = t * theta^(-2i/D),           i = 0 .. D/2-1
+ *     y[i]       = x[i] * cos(angle_i) - x[i + D/2] * sin(angle_i)
+ *     y[i + D/2] = x[i + D/2] * cos(angle_i) + x[i] * sin(angle_i)
+ * (dimension i is paired with i + D/2; no frequency rescaling).
+ *   x, y  [B][H][D] fp64;  t [B] positions;  theta > 0 the base.
+ * Returns 0, or -1 on a bad argument (odd D, negative position, ...).
+ */
+int tempo_oracle_rope(const double* x, int B, int H, int D, const int* t, double theta, double* y) {
+  if (!x || !t || !y || B < 1 || H < 1 || D < 2 || D % 2 != 0 || !(theta > 0.0)) return -1;
+  for (int b = 0; b < B; ++b)
+    if (t[b] < 0) return -1;
+  const int half = D / 2;
+  for (int b = 0; b < B; ++b) {
+    for (int h = 0; h < H; ++h) {
+      const double* xv = x + ((size_t)b * H + h) * D;
+      double* yv = y + ((size_t)b * H + h) * D;
+      for (int i = 0; i < half; ++i) {
+        const double angle = (double)t[b] * pow(theta, -2.0 * (double)i / (double)D);
+        const double c = cos(angle), sn = sin(angle);
+        yv[i] = xv[i] * c - xv[i + half] * sn;
+        yv[i + half] = xv[i + half] * c + xv[i] * sn;
+      }
+    }
+  }
+  return 0;
+}
+
+/* cos and sin of the same angles as a table [positions][D/2] (position t = row t),
+ * the form in which inference stacks keep them.  Returns 0 or -1. */
+int tempo_oracle_rope_table(int positions, int D, double theta, double* cos_out, double* sin_out) {
+  if (!cos_out || !sin_out || positions < 1 || D < 2 || D % 2 != 0 || !(theta > 0.0)) return -1;
+  const int half = D / 2;
+  for (int t = 0; t < positions; ++t) {
+    for (int i = 0; i < half; ++i) {
+      const double angle = (double)t * pow(theta, -2.0 * (double)i / (double)D);
+      cos_out[(size_t)t * half + i] = cos(angle);
+      sin_out[(size_t)t * half + i] = sin(angle);
     }
   }
   return 0;

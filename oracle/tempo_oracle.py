@@ -47,6 +47,10 @@ def _bind(path: str):
         lib.tempo_oracle_attend.argtypes = [dp, dp, dp] + [ctypes.c_int] * 5 + [ip, ctypes.c_int,
                                                                              ctypes.c_double, dp]
         lib.tempo_oracle_attend.restype = ctypes.c_int
+        lib.tempo_oracle_rope.argtypes = [dp, ctypes.c_int, ctypes.c_int, ctypes.c_int, ip, ctypes.c_double, dp]
+        lib.tempo_oracle_rope.restype = ctypes.c_int
+        lib.tempo_oracle_rope_table.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_double, dp, dp]
+        lib.tempo_oracle_rope_table.restype = ctypes.c_int
         lib.tempo_oracle_threads.argtypes = []
         lib.tempo_oracle_threads.restype = ctypes.c_int
     return lib
@@ -103,6 +107,33 @@ def attend(q, K, V, t, window: int, scale: float) -> np.ndarray:
     if rc != 0:
         raise ValueError("oracle: bad argument to attend")
     return out
+
+
+def rope(x, t, theta: float) -> np.ndarray:
+    """x [B][H][D], t int or [B] positions -> rotated copy (fp64)."""
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    B, H, D = x.shape
+    tt = np.ascontiguousarray(np.broadcast_to(np.asarray(t, dtype=np.int32), (B,)), dtype=np.int32)
+    y = np.empty_like(x)
+    dp = ctypes.POINTER(ctypes.c_double)
+    rc = _load().tempo_oracle_rope(x.ctypes.data_as(dp), B, H, D, tt.ctypes.data_as(ctypes.POINTER(ctypes.c_int)),
+                                   float(theta), y.ctypes.data_as(dp))
+    if rc != 0:
+        raise ValueError("oracle: bad argument to rope")
+    return y
+
+
+def rope_table(positions: int, D: int, theta: float):
+    """(cos, sin) tables [positions][D/2] (fp64)."""
+    if D < 2 or D % 2:
+        raise ValueError("oracle: bad argument to rope_table")
+    c = np.empty((positions, D // 2), dtype=np.float64)
+    s = np.empty_like(c)
+    dp = ctypes.POINTER(ctypes.c_double)
+    rc = _load().tempo_oracle_rope_table(positions, D, float(theta), c.ctypes.data_as(dp), s.ctypes.data_as(dp))
+    if rc != 0:
+        raise ValueError("oracle: bad argument to rope_table")
+    return c, s
 
 
 def threads() -> int:

@@ -26,6 +26,9 @@ PIN_TESTS = [
     pins.test_p10_integer_closed_forms,
     pins.test_p10_printed_inverse_window_example,
     pins.test_p10_static_tiling_fixture,
+    pins.test_p11_rope_closed_forms,
+    pins.test_p11_rope_is_a_rotation_with_relative_positions,
+    pins.test_p11_rope_table_matches_closed_forms_and_rope,
 ]
 
 # (name, text to find, replacement) -- each is a mistake someone could make.
@@ -49,6 +52,20 @@ MUTATIONS = [
     ("tile opens one key late", "if (++slot == Z) { slot = 0; ++tile; }\n  }\n  tile = 0; slot = 0;",
      "if (++slot > Z) { slot = 0; ++tile; }\n  }\n  tile = 0; slot = 0;"),
     ("tile count floor instead of ceil", "for (int j = 0; j <= t; j += Z) ++tiles;", "for (int j = Z; j <= t; j += Z) ++tiles;"),
+    ("rope turns clockwise", "yv[i] = xv[i] * c - xv[i + half] * sn;\n        yv[i + half] = xv[i + half] * c + xv[i] * sn;",
+     "yv[i] = xv[i] * c + xv[i + half] * sn;\n        yv[i + half] = xv[i + half] * c - xv[i] * sn;"),
+    ("rope pairs neighbours", "yv[i] = xv[i] * c - xv[i + half] * sn;\n        yv[i + half] = xv[i + half] * c + xv[i] * sn;",
+     "yv[2 * i] = xv[2 * i] * c - xv[2 * i + 1] * sn;\n        yv[2 * i + 1] = xv[2 * i + 1] * c + xv[2 * i] * sn;"),
+    ("rope exponent over D/2", "const double angle = (double)t[b] * pow(theta, -2.0 * (double)i / (double)D);",
+     "const double angle = (double)t[b] * pow(theta, -2.0 * (double)i / (double)half);"),
+    ("rope exponent sign", "const double angle = (double)t[b] * pow(theta, -2.0 * (double)i / (double)D);",
+     "const double angle = (double)t[b] * pow(theta, 2.0 * (double)i / (double)D);"),
+    ("rope position of sequence 0", "const double angle = (double)t[b] * pow(", "const double angle = (double)t[0] * pow("),
+    ("rope second half not rotated", "yv[i + half] = xv[i + half] * c + xv[i] * sn;", "yv[i + half] = xv[i + half];"),
+    ("rope table sin and cos swapped", "cos_out[(size_t)t * half + i] = cos(angle);\n      sin_out[(size_t)t * half + i] = sin(angle);",
+     "cos_out[(size_t)t * half + i] = sin(angle);\n      sin_out[(size_t)t * half + i] = cos(angle);"),
+    ("rope table exponent", "const double angle = (double)t * pow(theta, -2.0 * (double)i / (double)D);",
+     "const double angle = (double)t * pow(theta, -(double)i / (double)D);"),
     ("append slot one late", "for (int j = 0; j < t; ++j) {\n    if (++s == Z)", "for (int j = 0; j <= t; ++j) {\n    if (++s == Z)"),
 ]
 

@@ -5,7 +5,9 @@ the paper prints.  None of these tests needs a GPU.
 
 Citations are to the paper: Section 2 (Eq. 1 and the causal / window attention
 patterns), Section 3 (symbolic automatic differentiation: printed inverse
-dependence examples), Section 4.3 (static tiling).
+dependence examples), Section 4.3 (static tiling), Section 6 (in-place writes of
+the producer's output; the producer pinned here is the rotary position embedding
+of the Llama-3.2 workload of Section 7.2, which the paper itself does not define).
 """
 import math
 import os
@@ -366,6 +368,75 @@ def test_p10_static_tiling_fixture():
 # ----------------------------------------------------------------------------
 # The input generator is shared by both sides, so pin what it promises.
 # ----------------------------------------------------------------------------
+# ----------------------------------------------------------------------------
+# P11 rotary position embedding (the producer of k_t and q_t): closed forms at
+#     chosen angles, a rotation per pair, the relative-position identity.
+# ----------------------------------------------------------------------------
+def test_p11_rope_closed_forms():
+    # D = 2: one pair, frequency theta^0 = 1, so position t rotates by t radians
+    y = oracle.rope(np.array([[[1.0, 0.0]]]), 1, 12345.0)
+    assert np.allclose(y[0, 0], [math.cos(1.0), math.sin(1.0)], rtol=0, atol=1e-15)
+    y = oracle.rope(np.array([[[0.0, 1.0]]]), 2, 7.0)
+    assert np.allclose(y[0, 0], [-math.sin(2.0), math.cos(2.0)], rtol=0, atol=1e-15)
+    # D = 4, theta = 10000: pairs are (0,2) and (1,3); pair 1 turns at 10000^(-2/4) = 0.01 rad per
+    # position, so position 100 turns it by exactly 1 rad while pair 0 turns by 100 rad
+    y = oracle.rope(np.array([[[0.0, 1.0, 0.0, 0.0]]]), 100, 10000.0)
+    assert np.allclose(y[0, 0], [0.0, math.cos(1.0), 0.0, math.sin(1.0)], rtol=0, atol=1e-13)
+    y = oracle.rope(np.array([[[0.0, 0.0, 1.0, 0.0]]]), 100, 10000.0)
+    assert np.allclose(y[0, 0], [-math.sin(100.0), 0.0, math.cos(100.0), 0.0], rtol=0, atol=1e-13)
+    # D = 8, theta = 16: frequencies 16^(-i/4) = 1, 1/2, 1/4, 1/8
+    x = np.zeros((1, 1, 8)); x[0, 0, :4] = 1.0
+    y = oracle.rope(x, 8, 16.0)
+    for i, f in enumerate((1.0, 0.5, 0.25, 0.125)):
+        assert abs(y[0, 0, i] - math.cos(8 * f)) < 1e-14 and abs(y[0, 0, i + 4] - math.sin(8 * f)) < 1e-14
+    # position 0 is the identity, bit for bit; each sequence uses its own position
+    x = synth.normal(31, 1, (3, 2, 16))
+    assert np.array_equal(oracle.rope(x, 0, 500000.0), x)
+    y = oracle.rope(x, [0, 5, 9], 500000.0)
+    assert np.array_equal(y[0], x[0])
+    assert np.array_equal(y[1], oracle.rope(x[1:2], 5, 500000.0)[0])
+    assert np.array_equal(y[2], oracle.rope(x[2:3], 9, 500000.0)[0])
+    with pytest.raises(ValueError):
+        oracle.rope(np.zeros((1, 1, 3)), 1, 10.0)
+    with pytest.raises(ValueError):
+        oracle.rope(np.zeros((1, 1, 4)), -1, 10.0)
+
+
+def test_p11_rope_is_a_rotation_with_relative_positions():
+    D, theta = 32, 500000.0
+    q = synth.normal(32, 1, (2, 3, D))
+    k = synth.normal(32, 2, (2, 3, D))
+    # norms of every (i, i + D/2) pair are kept
+    y = oracle.rope(q, 77, theta)
+    assert np.allclose(y[..., :D // 2] ** 2 + y[..., D // 2:] ** 2, q[..., :D // 2] ** 2 + q[..., D // 2:] ** 2,
+                       rtol=1e-13)
+    # <rope(q, m), rope(k, n)> depends on m - n only, and equals <rope(q, m - n), k>
+    for m, n in ((9, 4), (1000, 995), (12, 12), (4000, 3995)):
+        lhs = np.einsum("bhd,bhd->bh", oracle.rope(q, m, theta), oracle.rope(k, n, theta))
+        rhs = np.einsum("bhd,bhd->bh", oracle.rope(q, m - n, theta), k)
+        assert np.allclose(lhs, rhs, rtol=0, atol=1e-9)
+    # rotations compose: position a then position b is position a + b
+    assert np.allclose(oracle.rope(oracle.rope(q, 13, theta), 29, theta), oracle.rope(q, 42, theta), rtol=0, atol=1e-12)
+    # counter-clockwise: a small positive position moves x[i] = 1 towards +x[i + D/2]
+    e = np.zeros((1, 1, D)); e[0, 0, 3] = 1.0
+    assert oracle.rope(e, 1, theta)[0, 0, 3 + D // 2] > 0.0
+
+
+def test_p11_rope_table_matches_closed_forms_and_rope():
+    D, theta, P = 8, 16.0, 40
+    c, s = oracle.rope_table(P, D, theta)
+    assert c.shape == (P, D // 2)
+    for t in (0, 1, 7, 39):
+        for i, f in enumerate((1.0, 0.5, 0.25, 0.125)):
+            assert abs(c[t, i] - math.cos(t * f)) < 1e-14 and abs(s[t, i] - math.sin(t * f)) < 1e-14
+    # applying the table by hand gives what rope gives
+    x = synth.normal(33, 1, (1, 2, D))
+    for t in (3, 39):
+        lo, hi = x[..., :D // 2], x[..., D // 2:]
+        by_table = np.concatenate([lo * c[t] - hi * s[t], hi * c[t] + lo * s[t]], axis=-1)
+        assert np.allclose(by_table, oracle.rope(x, t, theta), rtol=0, atol=1e-15)
+
+
 def test_synth_generator_properties():
     x = synth.normal(5, 1, (200000,))
     assert abs(x.mean()) < 0.01 and abs(x.std() - 1.0) < 0.01
