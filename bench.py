@@ -94,6 +94,32 @@ def other_workloads(torch, T, BlockStore, synth, dev, kv_bytes_per_token):
     del sts
     torch.cuda.empty_cache()
 
+    # producer fused in: unrotated q and k in, rotary embedding + block-store write + attention
+    # in the launches of the plain step, against the same work as separate launches
+    sts = layers(8, 16, 4095)
+    ang = torch.arange(4096, device=dev, dtype=torch.float64)[:, None] * \
+        (500000.0 ** (-torch.arange(0, D, 2, device=dev, dtype=torch.float64) / D))[None, :]
+    cos_t, sin_t = torch.cos(ang).float().contiguous(), torch.sin(ang).float().contiguous()
+    for st in sts:
+        st.set_rope(cos_t, sin_t)
+    o = sts[0].new_out()
+    qr = torch.empty_like(q16)
+    dt = _timed(torch, lambda i: sts[i % 8].rope_step(q16, k16, v16, o, 4095), 200, 20)
+
+    def rope_separate(i):
+        st = sts[i % 8]
+        st.rope_rotate(q16, qr, 4095)
+        st.rope_append(k16, v16, 4095)
+        st.attend_causal(qr, o, 4095)
+
+    dt3 = _timed(torch, rope_separate, 200, 20)
+    out["rope_step_b16_t4095"] = {"us_per_step": round(dt * 1e6, 2),
+                                  "kv_gbs": round(16 * 4096 * kv_bytes_per_token / dt / 1e9, 1),
+                                  "separate_launches_us": round(dt3 * 1e6, 2),
+                                  "note": "fused: rotate q,k + append + attend in 2 launches; separate: 4 launches"}
+    del sts
+    torch.cuda.empty_cache()
+
     # sliding window 512, batch 16, steady state (t >= 511), unaligned window position
     sts = layers(8, 16, 16383)
     o = sts[0].new_out()

@@ -228,6 +228,60 @@ int tempo_decode_step_window(const tempo_kv* kv, const void* q, const void* k_ne
                              void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Rotary position embedding of the producer step, fused with the block-store
+ * write (Section 6, kernel wrappers / "in-place writes": the kernel that produces
+ * a value writes it straight to index t of the pre-allocated buffer; here the
+ * producer is the position encoding of the Llama decoding workload of Section 7.2,
+ * which the paper leaves to the model).  A head vector x at position t becomes
+ *     y[i]       = x[i] * cos[t][i] - x[i + D/2] * sin[t][i]
+ *     y[i + D/2] = x[i + D/2] * cos[t][i] + x[i] * sin[t][i],     i = 0 .. D/2-1,
+ * with the caller's tables (normally cos / sin of t * theta^(-2i/D)).  Arithmetic
+ * is fp32; bf16 results are rounded to nearest even once.
+ *   cos, sin   device, [positions][head_dim/2] float, 16-byte aligned; read only;
+ *              owned by the caller and unchanged
+ *   head_dim   must equal the store's head_dim where a store is involved
+ * Errors: TEMPO_ERR_NULL (rope or a table is NULL), TEMPO_ERR_SHAPE (head_dim
+ * mismatch, misaligned table), TEMPO_ERR_RANGE (a step >= positions).
+ */
+typedef struct tempo_rope {
+  const float* cos;
+  const float* sin;
+  int32_t positions;
+  int32_t head_dim;
+} tempo_rope;
+
+/* y = x rotated to position t (t_per_seq[b] if given, t their upper bound).
+ * x, y: device, [batch][heads][rope->head_dim] of `dtype`; y may be x. */
+int tempo_rope_rotate(const tempo_rope* rope, const void* x, void* y, int32_t dtype, int32_t batch,
+                      int32_t heads, int32_t t, const int32_t* t_per_seq, void* stream);
+
+/* tempo_kv_append of (rotate(k_raw, t), v_new): the rotated key is written to its
+ * slot directly and never exists as a tensor.  Arguments as tempo_kv_append. */
+int tempo_rope_kv_append(const tempo_kv* kv, const tempo_rope* rope, const void* k_raw,
+                         const void* v_new, int32_t batch, int32_t t, const int32_t* t_per_seq,
+                         void* stream);
+
+/*
+ * The whole producer + consumer step in the launches of tempo_decode_step_*:
+ * q_raw and k_raw (both unrotated) are turned to position t inside the attention
+ * kernel, the rotated key and v_new are written to step t's slot, and the rotated
+ * query attends over the visible range.  Same result as tempo_rope_rotate(q),
+ * tempo_rope_kv_append, tempo_attn_decode_*, bit for bit in the store.
+ * Arguments otherwise as tempo_decode_step_causal / _window.
+ */
+int tempo_rope_decode_step_causal(const tempo_kv* kv, const tempo_rope* rope, const void* q_raw,
+                                  const void* k_raw, const void* v_new, void* out, int32_t batch,
+                                  int32_t num_q_heads, int32_t t, const int32_t* t_per_seq,
+                                  float scale, void* workspace, size_t workspace_bytes,
+                                  void* stream);
+
+int tempo_rope_decode_step_window(const tempo_kv* kv, const tempo_rope* rope, const void* q_raw,
+                                  const void* k_raw, const void* v_new, void* out, int32_t batch,
+                                  int32_t num_q_heads, int32_t t, const int32_t* t_per_seq,
+                                  int32_t window, float scale, void* workspace,
+                                  size_t workspace_bytes, void* stream);
+
+/*
  * Block of queries (Section 2: the block access pattern and prompt processing;
  * Section 4.3: a tile of timesteps evaluated together).  `queries` = C consecutive
  * steps t .. t+C-1 of every sequence are answered by one call: query c attends

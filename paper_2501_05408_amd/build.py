@@ -20,7 +20,7 @@ LIB = os.path.join(LIBDIR, "libtempo.so")
 OBJDIR = os.path.join(HERE, "_build")
 
 SOURCES = ["tempo_api.hip", "kv_store.hip", "attn_partial_bf16.hip", "attn_partial_f32.hip",
-           "attn_combine.hip", "stream_read.hip"]
+           "attn_combine.hip", "stream_read.hip", "rope.hip"]
 HEADERS = [os.path.join(CSRC, "tempo_internal.h"), os.path.join(ROOT, "include", "tempo.h")]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",

@@ -28,6 +28,13 @@
 // from its own window start), which is one more per-lane bound in the index mask.
 // The keys and values are still read once, now for C steps.
 //
+// Rotary embedding (kRope instantiations).  q, and the k_new of a fused append,
+// arrive unrotated; the kernel turns them to their step's position with fp32
+// arithmetic and rounds to bf16 once, so the producer's output never exists as a
+// tensor of its own (Section 6, "in-place writes", applied to the whole step).
+// Dimension i pairs with i + D/2: for q both live in the same lane (operand
+// registers s and s + D/64), for the fetched key row in lanes l and l ^ (D/16).
+//
 // Pipeline.  A wavefront owns ONE register image of a group (keys: 2*D/32 units,
 // values: D/16 units) and refills each half as soon as the MFMAs that read it
 // have been issued: the next group's keys are requested right after Q.K^T, its
@@ -165,6 +172,72 @@ __device__ __forceinline__ void append_values(const AttnParams& p, int64_t base,
   }
 }
 
+// ---- rotary embedding of q and of the fetched key row ------------------------------
+__device__ inline void unpack8(u32x4 v, float* f) {
+  const bf16x8 b = as_bf16x8(v);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) f[e] = (float)b[e];
+}
+__device__ inline u32x4 pack8(const float* f) {
+  bf16x8 b;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) b[e] = (__bf16)f[e];  // round to nearest even
+  return __builtin_bit_cast(u32x4, b);
+}
+// 8 consecutive table entries starting at entry i0 of row `pos`.
+__device__ inline void load_angles(const float* table, int64_t pos, int half, int i0, float* f) {
+  const float4* src = reinterpret_cast<const float4*>(table + pos * half + i0);
+  const float4 a = src[0], b = src[1];
+  f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w;
+  f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
+}
+
+// Query operand registers: qreg[s] holds dims 32s + 8c .. +7, its partner qreg[s + KS/2].
+template <int D>
+__device__ inline void rotate_query(const AttnParams& p, int pos, int lane, u32x4* qreg) {
+  constexpr int KS = D / 32;
+  const int c = lane >> 4;
+#pragma unroll
+  for (int s = 0; s < KS / 2; ++s) {
+    float cs[8], sn[8], lo[8], hi[8];
+    load_angles(p.rope_cos, pos, D / 2, 32 * s + 8 * c, cs);
+    load_angles(p.rope_sin, pos, D / 2, 32 * s + 8 * c, sn);
+    unpack8(qreg[s], lo);
+    unpack8(qreg[s + KS / 2], hi);
+    float ylo[8], yhi[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      ylo[e] = rope_lo(lo[e], hi[e], cs[e], sn[e]);
+      yhi[e] = rope_hi(lo[e], hi[e], cs[e], sn[e]);
+    }
+    qreg[s] = pack8(ylo);
+    qreg[s + KS / 2] = pack8(yhi);
+  }
+}
+
+// The row pair fetch_new_row returned: lanes 0..D/8-1 hold the key row (lane l:
+// dims 8l .. 8l+7), whose partner dims sit in lane l ^ (D/16).  All lanes call this.
+template <int D>
+__device__ inline u32x4 rotate_fetched_key(const AttnParams& p, int pos, int lane, u32x4 fetched) {
+  constexpr int UNITS = D / 8;
+  u32x4 other;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) other[w] = __shfl_xor(fetched[w], UNITS / 2);
+  if (lane < UNITS) {
+    float cs[8], sn[8], x[8], o[8], y[8];
+    load_angles(p.rope_cos, pos, D / 2, 8 * (lane % (UNITS / 2)), cs);
+    load_angles(p.rope_sin, pos, D / 2, 8 * (lane % (UNITS / 2)), sn);
+    unpack8(fetched, x);
+    unpack8(other, o);
+    const bool first = lane < UNITS / 2;  // dims below D/2: y = x cos - partner sin
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      y[e] = first ? rope_lo(x[e], o[e], cs[e], sn[e]) : rope_hi(o[e], x[e], cs[e], sn[e]);
+    fetched = pack8(y);
+  }
+  return fetched;
+}
+
 // ---- the phases of a group ---------------------------------------------------------
 
 // Q.K^T for the group's two row tiles; logits in base-2 units.
@@ -241,7 +314,7 @@ __device__ inline bf16x8 softmax_update(const float* x, int lane, WaveState<D>& 
   return pa;
 }
 
-template <int D>
+template <int D, bool kRope>
 __global__ __launch_bounds__(512) void attn_partial_bf16(AttnParams p) {
   constexpr int KS = D / 32;
   constexpr int DT = D / 16;
@@ -284,6 +357,7 @@ __global__ __launch_bounds__(512) void attn_partial_bf16(AttnParams p) {
   if (p.k_new && split == rg.nchunks - 1 && ((t_b >> 5) - grp) % nwaves == 0 && (t_b >> 5) >= grp) {
     grp_new = t_b >> 5;
     fetched = fetch_new_row<D>(p, b, hkv, lane);
+    if (kRope) fetched = rotate_fetched_key<D>(p, t_b, lane, fetched);
   }
 
   // Columns: j = cq*G + gq for query step cq and head gq of the group; ncols = C*G <= 16.
@@ -314,6 +388,7 @@ __global__ __launch_bounds__(512) void attn_partial_bf16(AttnParams p) {
       qreg[s] = col < ncols ? v : zero;
     }
   }
+  if (kRope) rotate_query<D>(p, t_b + cq, lane, qreg);
 
   WaveState<D> st;
   st.m = -INFINITY;
@@ -413,8 +488,12 @@ hipError_t launch_partial_bf16(const AttnParams& p, int batch, int D, int grid_s
   // wave-merge area, then room for one staged key row and one value row (bf16)
   const size_t lds = (size_t)waves * (32 + (size_t)p.queries * p.G * D) * sizeof(float) +
                      2 * (size_t)D * sizeof(uint16_t);
-  if (D == 128) return launch(attn_partial_bf16<128>, grid, block, lds, stream, p);
-  else return launch(attn_partial_bf16<64>, grid, block, lds, stream, p);
+  if (p.rope_cos) {
+    if (D == 128) return launch((attn_partial_bf16<128, true>), grid, block, lds, stream, p);
+    else return launch((attn_partial_bf16<64, true>), grid, block, lds, stream, p);
+  }
+  if (D == 128) return launch((attn_partial_bf16<128, false>), grid, block, lds, stream, p);
+  else return launch((attn_partial_bf16<64, false>), grid, block, lds, stream, p);
 }
 
 }  // namespace tempo

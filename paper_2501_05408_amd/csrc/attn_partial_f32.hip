@@ -56,6 +56,17 @@ __global__ __launch_bounds__(512) void attn_partial_f32(AttnParams p) {
 #pragma unroll
     for (int e = 0; e < E; ++e) qv[e] = qp[e];
   }
+  // Rotary embedding: dims col*E .. +E-1 pair with those of lane col ^ 8 of the same
+  // 16-lane row; table entry (position, i) with i = (col & 7) * E + e.
+  if (p.rope_cos) {
+    const float* cs = p.rope_cos + (int64_t)t_q * (D / 2) + (col & 7) * E;
+    const float* sn = p.rope_sin + (int64_t)t_q * (D / 2) + (col & 7) * E;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      const float other = __shfl_xor(qv[e], 8);
+      qv[e] = col < 8 ? rope_lo(qv[e], other, cs[e], sn[e]) : rope_hi(other, qv[e], cs[e], sn[e]);
+    }
+  }
   float m = -INFINITY, l = 0.f, acc[E];
 #pragma unroll
   for (int e = 0; e < E; ++e) acc[e] = 0.f;
@@ -74,12 +85,26 @@ __global__ __launch_bounds__(512) void attn_partial_f32(AttnParams p) {
     for (int e = 0; e < E; e += 4) {
       const float4 k4 = *reinterpret_cast<const float4*>(ksrc + e);
       const float4 v4 = *reinterpret_cast<const float4*>(vsrc + e);
-      if (fresh && hq == hkv * p.G) {
-        *reinterpret_cast<float4*>(kpool + off + e) = k4;
-        *reinterpret_cast<float4*>(vpool + off + e) = v4;
-      }
       kx[e] = k4.x; kx[e + 1] = k4.y; kx[e + 2] = k4.z; kx[e + 3] = k4.w;
       vx[e] = v4.x; vx[e + 1] = v4.y; vx[e + 2] = v4.z; vx[e + 3] = v4.w;
+    }
+    if (fresh) {  // all 16 lanes of the row take this branch together
+      if (p.rope_cos) {  // the new key arrives unrotated: turn it to position t_b
+        const float* cs = p.rope_cos + (int64_t)t_b * (D / 2) + (col & 7) * E;
+        const float* sn = p.rope_sin + (int64_t)t_b * (D / 2) + (col & 7) * E;
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+          const float other = __shfl_xor(kx[e], 8);
+          kx[e] = col < 8 ? rope_lo(kx[e], other, cs[e], sn[e]) : rope_hi(other, kx[e], cs[e], sn[e]);
+        }
+      }
+      if (hq == hkv * p.G) {
+#pragma unroll
+        for (int e = 0; e < E; e += 4) {
+          *reinterpret_cast<float4*>(kpool + off + e) = float4{kx[e], kx[e + 1], kx[e + 2], kx[e + 3]};
+          *reinterpret_cast<float4*>(vpool + off + e) = float4{vx[e], vx[e + 1], vx[e + 2], vx[e + 3]};
+        }
+      }
     }
     float dot = 0.f;
 #pragma unroll

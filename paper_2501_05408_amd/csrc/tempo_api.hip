@@ -82,6 +82,16 @@ int check_ring_covers(const tempo_kv* kv, int32_t t, int32_t window) {
   return tiles <= kv->ring_blocks ? TEMPO_OK : TEMPO_ERR_RANGE;
 }
 
+// Rotary tables: both present, made for this head_dim, and long enough for step t.
+int check_rope(const tempo_rope* rope, int32_t head_dim, int32_t t_last) {
+  if (!rope || !rope->cos || !rope->sin) return TEMPO_ERR_NULL;
+  if (rope->head_dim != head_dim) return TEMPO_ERR_SHAPE;
+  if ((reinterpret_cast<uintptr_t>(rope->cos) & 15u) != 0 || (reinterpret_cast<uintptr_t>(rope->sin) & 15u) != 0)
+    return TEMPO_ERR_SHAPE;
+  if (t_last < 0 || rope->positions < 1 || t_last >= rope->positions) return TEMPO_ERR_RANGE;
+  return TEMPO_OK;
+}
+
 int32_t tile_mask_of(const tempo_kv* kv) { return kv->ring_blocks ? kv->ring_blocks - 1 : INT32_MAX; }
 
 // Upper bound of the number of splits any step t' <= t can need with this tps.
@@ -214,6 +224,8 @@ AttnParams attn_params(const tempo_kv* kv, const void* q, void* out, int32_t Hq,
   p.k_new = nullptr;
   p.v_new = nullptr;
   p.t_per_seq = t_per_seq;
+  p.rope_cos = nullptr;
+  p.rope_sin = nullptr;
   char* ws = static_cast<char*>(workspace);
   p.ws_ml = reinterpret_cast<float*>(ws);
   p.ws_acc = reinterpret_cast<float*>(ws + ml_bytes((int64_t)batch * queries * Hq, plan->num_splits));
@@ -286,11 +298,15 @@ int check_attn(const tempo_kv* kv, int32_t batch, int32_t Hq, int32_t t, int32_t
 int do_partial(const tempo_kv* kv, const void* q, const void* k_new, const void* v_new, void* out,
                int32_t batch, int32_t Hq, int32_t t, const int32_t* t_per_seq, int32_t window,
                float scale, const tempo_plan* plan, void* workspace, hipStream_t stream,
-               int32_t queries = 1) {
+               int32_t queries = 1, const tempo_rope* rope = nullptr) {
   AttnParams p = attn_params(kv, q, out, Hq, t, t_per_seq, window, scale, plan, workspace, batch, queries);
   p.direct = (out != nullptr && plan->num_splits == 1) ? 1 : 0;
   p.k_new = k_new;
   p.v_new = v_new;
+  if (rope) {
+    p.rope_cos = rope->cos;
+    p.rope_sin = rope->sin;
+  }
   const int32_t gs = grid_splits(plan, t, t_per_seq, window, queries);
   const hipError_t e = kv->dtype == TEMPO_BF16
                            ? launch_partial_bf16(p, batch, kv->head_dim, gs, plan->waves, stream)
@@ -319,18 +335,21 @@ void make_block_plan(const tempo_kv* kv, int32_t batch, int32_t Hq, int32_t t, i
 
 int decode(const tempo_kv* kv, const void* q, const void* k_new, const void* v_new, void* out,
            int32_t batch, int32_t Hq, int32_t t, const int32_t* t_per_seq, int32_t window, float scale,
-           void* workspace, size_t workspace_bytes, void* stream, int32_t queries = 1) {
+           void* workspace, size_t workspace_bytes, void* stream, int32_t queries = 1,
+           const tempo_rope* rope = nullptr) {
   int rc = check_layout(kv);
   if (rc != TEMPO_OK) return rc;
   if (!q || !out) return TEMPO_ERR_NULL;
   if ((rc = check_heads(kv, batch, Hq)) != TEMPO_OK) return rc;
   if ((rc = check_queries(kv, Hq, queries)) != TEMPO_OK) return rc;
   if (t < 0 || window < 0 || t > INT32_MAX - 64) return TEMPO_ERR_RANGE;
+  if (rope && (rc = check_rope(rope, kv->head_dim, last_step(t, queries))) != TEMPO_OK) return rc;
   tempo_plan plan;
   make_block_plan(kv, batch, Hq, t, window, t_per_seq != nullptr, queries, &plan);
   if ((rc = check_attn(kv, batch, Hq, t, window, t_per_seq != nullptr, &plan, workspace, workspace_bytes, queries)) != TEMPO_OK) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  rc = do_partial(kv, q, k_new, v_new, out, batch, Hq, t, t_per_seq, window, scale, &plan, workspace, s, queries);
+  rc = do_partial(kv, q, k_new, v_new, out, batch, Hq, t, t_per_seq, window, scale, &plan, workspace, s, queries,
+                  rope);
   if (rc != TEMPO_OK || plan.num_splits == 1) return rc;  // a single split wrote `out` itself
   return do_combine(kv, out, batch, Hq, t, t_per_seq, window, &plan, workspace, s, queries);
 }
@@ -525,6 +544,54 @@ int tempo_decode_step_window(const tempo_kv* kv, const void* q, const void* k_ne
   if (window < 1) return TEMPO_ERR_RANGE;
   return decode(kv, q, k_new, v_new, out, batch, num_q_heads, t, t_per_seq, window, scale, workspace,
                 workspace_bytes, stream);
+}
+
+int tempo_rope_rotate(const tempo_rope* rope, const void* x, void* y, int32_t dtype, int32_t batch,
+                      int32_t heads, int32_t t, const int32_t* t_per_seq, void* stream) {
+  if (!rope || !x || !y) return TEMPO_ERR_NULL;
+  if (dtype != TEMPO_BF16 && dtype != TEMPO_F32) return TEMPO_ERR_DTYPE;
+  if (rope->head_dim < 2 || rope->head_dim % 2 != 0 || rope->head_dim > 65536) return TEMPO_ERR_SHAPE;
+  if (batch < 1 || heads < 1 || (int64_t)batch * heads * rope->head_dim > INT32_MAX) return TEMPO_ERR_SHAPE;
+  const int rc = check_rope(rope, rope->head_dim, t);
+  if (rc != TEMPO_OK) return rc;
+  const hipError_t e = launch_rope_rotate(rope->cos, rope->sin, x, y, dtype, batch, heads, rope->head_dim, t,
+                                          t_per_seq, static_cast<hipStream_t>(stream));
+  return launch_status(e, "rope_rotate");
+}
+
+int tempo_rope_kv_append(const tempo_kv* kv, const tempo_rope* rope, const void* k_raw, const void* v_new,
+                         int32_t batch, int32_t t, const int32_t* t_per_seq, void* stream) {
+  int rc = check_store(kv);
+  if (rc != TEMPO_OK) return rc;
+  if (!k_raw || !v_new) return TEMPO_ERR_NULL;
+  if (batch < 1 || batch > 65535) return TEMPO_ERR_SHAPE;
+  if ((rc = check_step(kv, t)) != TEMPO_OK) return rc;
+  if ((rc = check_rope(rope, kv->head_dim, t)) != TEMPO_OK) return rc;
+  if ((int64_t)batch * kv->num_kv_heads * kv->head_dim > INT32_MAX) return TEMPO_ERR_SHAPE;
+  const StoreParams p = store_params(kv, batch, t, t_per_seq);
+  const hipError_t e = launch_rope_append(p, rope->cos, rope->sin, k_raw, v_new, kv->head_dim, kv->dtype,
+                                          static_cast<hipStream_t>(stream));
+  return launch_status(e, "kv_rope_append");
+}
+
+int tempo_rope_decode_step_causal(const tempo_kv* kv, const tempo_rope* rope, const void* q_raw,
+                                  const void* k_raw, const void* v_new, void* out, int32_t batch,
+                                  int32_t num_q_heads, int32_t t, const int32_t* t_per_seq, float scale,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
+  if (!rope || !k_raw || !v_new) return TEMPO_ERR_NULL;
+  return decode(kv, q_raw, k_raw, v_new, out, batch, num_q_heads, t, t_per_seq, 0, scale, workspace,
+                workspace_bytes, stream, 1, rope);
+}
+
+int tempo_rope_decode_step_window(const tempo_kv* kv, const tempo_rope* rope, const void* q_raw,
+                                  const void* k_raw, const void* v_new, void* out, int32_t batch,
+                                  int32_t num_q_heads, int32_t t, const int32_t* t_per_seq,
+                                  int32_t window, float scale, void* workspace, size_t workspace_bytes,
+                                  void* stream) {
+  if (!rope || !k_raw || !v_new) return TEMPO_ERR_NULL;
+  if (window < 1) return TEMPO_ERR_RANGE;
+  return decode(kv, q_raw, k_raw, v_new, out, batch, num_q_heads, t, t_per_seq, window, scale, workspace,
+                workspace_bytes, stream, 1, rope);
 }
 
 int tempo_attn_block_causal(const tempo_kv* kv, const void* q, void* out, int32_t batch,

@@ -44,6 +44,12 @@ __host__ __device__ inline int clamp_block(int phys, int num_blocks) {
   return phys < 0 ? 0 : (phys >= num_blocks ? num_blocks - 1 : phys);
 }
 
+// ---- rotary embedding of one (i, i + D/2) pair ---------------------------------
+// Every kernel that rotates uses these two expressions, so the fused and the
+// separate launches store the same bits: one product, then one fused multiply-add.
+__device__ inline float rope_lo(float lo, float hi, float c, float s) { return fmaf(-hi, s, lo * c); }
+__device__ inline float rope_hi(float lo, float hi, float c, float s) { return fmaf(lo, s, hi * c); }
+
 // ---- kernel parameter blocks -------------------------------------------------
 struct StoreParams {
   void* k_pool;
@@ -68,6 +74,8 @@ struct AttnParams {
   const void* k_new;         // [B][Hkv][D]; non-null: append step t inside the attention kernel (queries == 1)
   const void* v_new;
   const int32_t* t_per_seq;  // may be null
+  const float* rope_cos;     // [positions][D/2]; non-null: q (and k_new) arrive unrotated and are
+  const float* rope_sin;     //   rotated to their step's position inside the kernel
   float* ws_ml;              // [B][C][Hq][S][2]  (running max in log2 units, running sum)
   float* ws_acc;             // [B][C][Hq][S][D]
   void* out;                 // [B][C][Hq][D]
@@ -128,6 +136,11 @@ hipError_t launch_partial_bf16(const AttnParams& p, int batch, int D, int grid_s
 hipError_t launch_partial_f32(const AttnParams& p, int batch, int D, int grid_splits, int waves,
                               hipStream_t stream);
 
+hipError_t launch_rope_rotate(const float* rope_cos, const float* rope_sin, const void* x, void* y,
+                              int dtype, int batch, int heads, int D, int t, const int32_t* t_per_seq,
+                              hipStream_t stream);
+hipError_t launch_rope_append(const StoreParams& p, const float* rope_cos, const float* rope_sin,
+                              const void* k_raw, const void* v_new, int D, int dtype, hipStream_t stream);
 hipError_t launch_combine(const AttnParams& p, int batch, int D, int dtype, hipStream_t stream);
 hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, int workgroups,
                               hipStream_t stream);

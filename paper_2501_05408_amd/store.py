@@ -102,6 +102,30 @@ class BlockStore:
                                    self.workspace_bytes)
         return out
 
+    # -- rotary producer ------------------------------------------------------------
+    def set_rope(self, cos_table, sin_table):
+        """Tables [positions][D/2], fp32, on the store's device (kept alive here)."""
+        self._rope_tables = (cos_table.contiguous(), sin_table.contiguous())
+        self.rope = T.make_rope(self._rope_tables[0], self._rope_tables[1], self.D)
+
+    def rope_rotate(self, x, y, t, t_per_seq=None):
+        T.tempo_rope_rotate(self.rope, x, y, self.dtype, x.shape[0], x.shape[1], t, t_per_seq)
+        return y
+
+    def rope_append(self, k_raw, v_new, t, t_per_seq=None):
+        T.tempo_rope_kv_append(self.kv, self.rope, k_raw, v_new, self.batch, t, t_per_seq)
+
+    def rope_step(self, q_raw, k_raw, v_new, out, t, window=0, t_per_seq=None, scale=None):
+        """Rotate q and k, append step t, attend: the launches of step_causal / step_window."""
+        s = self.scale if scale is None else scale
+        if window:
+            T.tempo_rope_decode_step_window(self.kv, self.rope, q_raw, k_raw, v_new, out, self.batch, self.Hq, t,
+                                            t_per_seq, window, s, self.workspace, self.workspace_bytes)
+        else:
+            T.tempo_rope_decode_step_causal(self.kv, self.rope, q_raw, k_raw, v_new, out, self.batch, self.Hq, t,
+                                            t_per_seq, s, self.workspace, self.workspace_bytes)
+        return out
+
     def attend_block(self, q, out, t, queries, window=0, t_per_seq=None, scale=None):
         """Steps t .. t+queries-1 in one call; q, out are [batch][queries][Hq][D]."""
         ws_t = self.ring_blocks * self.Z + 32 if self.ring_blocks else self.max_t

@@ -55,6 +55,15 @@ class tempo_plan(ctypes.Structure):
                 f"num_splits={self.num_splits}, waves={self.waves})")
 
 
+class tempo_rope(ctypes.Structure):
+    _fields_ = [
+        ("cos", ctypes.c_void_p),
+        ("sin", ctypes.c_void_p),
+        ("positions", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32),
+    ]
+
+
 class TempoError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -67,6 +76,7 @@ _i32 = ctypes.c_int32
 _vp = ctypes.c_void_p
 _kvp = ctypes.POINTER(tempo_kv)
 _planp = ctypes.POINTER(tempo_plan)
+_ropep = ctypes.POINTER(tempo_rope)
 _i32p = ctypes.POINTER(ctypes.c_int32)
 
 # name -> (restype, argtypes); kept in the order of include/tempo.h
@@ -88,6 +98,12 @@ SIGNATURES = {
                                                 ctypes.c_float, _vp, ctypes.c_size_t, _vp]),
     "tempo_decode_step_window": (ctypes.c_int, [_kvp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _i32,
                                                 ctypes.c_float, _vp, ctypes.c_size_t, _vp]),
+    "tempo_rope_rotate": (ctypes.c_int, [_ropep, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp]),
+    "tempo_rope_kv_append": (ctypes.c_int, [_kvp, _ropep, _vp, _vp, _i32, _i32, _vp, _vp]),
+    "tempo_rope_decode_step_causal": (ctypes.c_int, [_kvp, _ropep, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp,
+                                                     ctypes.c_float, _vp, ctypes.c_size_t, _vp]),
+    "tempo_rope_decode_step_window": (ctypes.c_int, [_kvp, _ropep, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp,
+                                                     _i32, ctypes.c_float, _vp, ctypes.c_size_t, _vp]),
     "tempo_attn_block_causal": (ctypes.c_int, [_kvp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, ctypes.c_float,
                                                _vp, ctypes.c_size_t, _vp]),
     "tempo_attn_block_window": (ctypes.c_int, [_kvp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _i32,
@@ -188,6 +204,11 @@ def make_kv(k_pool, v_pool, block_table, num_blocks, max_blocks_per_seq, block_s
                     block_size, num_kv_heads, head_dim, dtype, ring_blocks)
 
 
+def make_rope(cos_table, sin_table, head_dim) -> tempo_rope:
+    """Fill a tempo_rope descriptor from two [positions][head_dim/2] fp32 device tensors."""
+    return tempo_rope(_ptr(cos_table), _ptr(sin_table), int(cos_table.shape[0]), head_dim)
+
+
 # ---- pure host functions -------------------------------------------------------
 def tempo_visible_range(t: int, window: int, Z: int) -> dict:
     vals = [ctypes.c_int32(0) for _ in range(6)]
@@ -270,6 +291,32 @@ def tempo_decode_step_window(kv, q, k_new, v_new, out, batch, num_q_heads, t, t_
                                            batch, num_q_heads, t, _ptr(t_per_seq), window, scale,
                                            _ptr(workspace), workspace_bytes, _stream(stream)),
            "tempo_decode_step_window")
+
+
+def tempo_rope_rotate(rope, x, y, dtype, batch, heads, t, t_per_seq=None, stream=None):
+    _check(load().tempo_rope_rotate(ctypes.byref(rope), _ptr(x), _ptr(y), dtype, batch, heads, t,
+                                    _ptr(t_per_seq), _stream(stream)), "tempo_rope_rotate")
+
+
+def tempo_rope_kv_append(kv, rope, k_raw, v_new, batch, t, t_per_seq=None, stream=None):
+    _check(load().tempo_rope_kv_append(ctypes.byref(kv), ctypes.byref(rope), _ptr(k_raw), _ptr(v_new), batch, t,
+                                       _ptr(t_per_seq), _stream(stream)), "tempo_rope_kv_append")
+
+
+def tempo_rope_decode_step_causal(kv, rope, q_raw, k_raw, v_new, out, batch, num_q_heads, t, t_per_seq, scale,
+                                  workspace, workspace_bytes, stream=None):
+    _check(load().tempo_rope_decode_step_causal(ctypes.byref(kv), ctypes.byref(rope), _ptr(q_raw), _ptr(k_raw),
+                                                _ptr(v_new), _ptr(out), batch, num_q_heads, t, _ptr(t_per_seq),
+                                                scale, _ptr(workspace), workspace_bytes, _stream(stream)),
+           "tempo_rope_decode_step_causal")
+
+
+def tempo_rope_decode_step_window(kv, rope, q_raw, k_raw, v_new, out, batch, num_q_heads, t, t_per_seq, window,
+                                  scale, workspace, workspace_bytes, stream=None):
+    _check(load().tempo_rope_decode_step_window(ctypes.byref(kv), ctypes.byref(rope), _ptr(q_raw), _ptr(k_raw),
+                                                _ptr(v_new), _ptr(out), batch, num_q_heads, t, _ptr(t_per_seq),
+                                                window, scale, _ptr(workspace), workspace_bytes,
+                                                _stream(stream)), "tempo_rope_decode_step_window")
 
 
 def tempo_attn_block_causal(kv, q, out, batch, num_q_heads, queries, t, t_per_seq, scale, workspace,

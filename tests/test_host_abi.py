@@ -227,6 +227,39 @@ def test_bad_arguments_are_refused_before_any_launch():
     assert append_block(ringed, 4 * 64 + 1, t=7) == T.TEMPO_ERR_RANGE   # would wrap onto its own rows
     assert lib.tempo_kv_append_block(ctypes.byref(good), None, fake, 2, 0, None, 3, None) == T.TEMPO_ERR_NULL
 
+    # rotary tables: both present, 16-byte aligned, made for the store's head_dim, long enough
+    def rope_desc(cos=fake, sin=fake, positions=100, head_dim=128):
+        return T.tempo_rope(cos, sin, positions, head_dim)
+
+    def rope_append(rope, t=5):
+        return lib.tempo_rope_kv_append(ctypes.byref(good), ctypes.byref(rope), fake, fake, 2, t, None, None)
+
+    assert rope_append(rope_desc(cos=None)) == T.TEMPO_ERR_NULL
+    assert rope_append(rope_desc(sin=None)) == T.TEMPO_ERR_NULL
+    assert rope_append(rope_desc(head_dim=64)) == T.TEMPO_ERR_SHAPE
+    assert rope_append(rope_desc(cos=fake + 4)) == T.TEMPO_ERR_SHAPE
+    assert rope_append(rope_desc(positions=5)) == T.TEMPO_ERR_RANGE        # step 5 needs 6 rows
+    assert lib.tempo_rope_kv_append(ctypes.byref(good), None, fake, fake, 2, 5, None, None) == T.TEMPO_ERR_NULL
+
+    def rope_step(rope, t=5, w=None):
+        r = ctypes.byref(rope) if rope is not None else None
+        if w is None:
+            return lib.tempo_rope_decode_step_causal(ctypes.byref(good), r, fake, fake, fake, fake, 2, 6, t, None,
+                                                     0.1, None, 0, None)
+        return lib.tempo_rope_decode_step_window(ctypes.byref(good), r, fake, fake, fake, fake, 2, 6, t, None, w,
+                                                 0.1, None, 0, None)
+
+    assert rope_step(None) == T.TEMPO_ERR_NULL
+    assert rope_step(rope_desc(positions=5)) == T.TEMPO_ERR_RANGE
+    assert rope_step(rope_desc(head_dim=64)) == T.TEMPO_ERR_SHAPE
+    assert rope_step(rope_desc()) == T.TEMPO_ERR_WORKSPACE                  # everything else is fine
+    assert rope_step(rope_desc(), w=0) == T.TEMPO_ERR_RANGE
+    assert rope_step(rope_desc(), w=7) == T.TEMPO_ERR_WORKSPACE
+    assert lib.tempo_rope_rotate(ctypes.byref(rope_desc()), fake, fake, 9, 2, 6, 5, None, None) == T.TEMPO_ERR_DTYPE
+    assert lib.tempo_rope_rotate(ctypes.byref(rope_desc()), None, fake, T.TEMPO_F32, 2, 6, 5, None, None) == T.TEMPO_ERR_NULL
+    assert lib.tempo_rope_rotate(ctypes.byref(rope_desc(head_dim=7)), fake, fake, T.TEMPO_F32, 2, 6, 5, None, None) == T.TEMPO_ERR_SHAPE
+    assert lib.tempo_rope_rotate(ctypes.byref(rope_desc()), fake, fake, T.TEMPO_F32, 2, 6, 100, None, None) == T.TEMPO_ERR_RANGE
+
     bad_plan = T.tempo_plan(48, 1, 1)
     assert lib.tempo_attn_decode_partial(ctypes.byref(good), fake, None, None, 2, 6, 5, None, 0, 0.1,
                                          ctypes.byref(bad_plan), fake << 4, 1 << 30, None) == T.TEMPO_ERR_SHAPE
