@@ -202,6 +202,45 @@ def other_workloads(torch, T, BlockStore, synth, dev, kv_bytes_per_token):
     return out
 
 
+def tile_sweep(torch, T, BlockStore, synth, dev):
+    """Tile-size sweep and padded baseline at T = 16384 (the shape of the paper's block-size
+    figure, Section 7.2): for batch 4 and 16 and tile sizes Z = 32 .. 8192, the mean time of a
+    decode step over steps spread evenly over 0..T-1, (a) over the dynamic range (fused append +
+    attention), (b) with every step padded to T and masked.  Pools are filled directly with
+    N(0,1); 4 layer pools are rotated."""
+    Hq, Hkv, D, T_len = 24, 8, 128, 16384
+    kv_bytes_per_token = 2 * Hkv * D * 2
+    steps = [T_len * (2 * i + 1) // 64 for i in range(32)]          # 32 evenly spread steps, mean = T/2
+    out = {"T": T_len, "sampled_steps": len(steps), "unit": "us per decode step (mean over sampled steps)"}
+    for batch in (4, 16):
+        q = synth.device_normal((batch, Hq, D), 81, torch.bfloat16, dev)
+        k = synth.device_normal((batch, Hkv, D), 82, torch.bfloat16, dev)
+        v = synth.device_normal((batch, Hkv, D), 83, torch.bfloat16, dev)
+        rows = {}
+        for Z in (32, 64, 256, 1024, 2048, 8192):
+            sts = []
+            for layer in range(4):
+                st = BlockStore(batch, Hq, Hkv, D, Z, T_len - 1, T.TEMPO_BF16, device=dev)
+                st.k_pool.normal_()
+                st.v_pool.normal_()
+                sts.append(st)
+            o = sts[0].new_out()
+            dyn, pad = [], []
+            for t in steps:
+                dyn.append(_timed(torch, lambda i: sts[i % 4].step_causal(q, k, v, o, t), 40, 8))
+                pad.append(_timed(torch, lambda i: sts[i % 4].attend_padded(q, o, t, T_len - 1), 40, 8))
+            mean_dyn, mean_pad = sum(dyn) / len(dyn), sum(pad) / len(pad)
+            mean_bytes = batch * (sum(steps) / len(steps) + 1) * kv_bytes_per_token
+            rows[str(Z)] = {"dynamic_us": round(mean_dyn * 1e6, 2), "padded_us": round(mean_pad * 1e6, 2),
+                            "padded_over_dynamic": round(mean_pad / mean_dyn, 2),
+                            "dynamic_kv_gbs": round(mean_bytes / mean_dyn / 1e9, 1),
+                            "last_step_dynamic_us": round(dyn[-1] * 1e6, 2)}
+            del sts
+            torch.cuda.empty_cache()
+        out[f"batch{batch}"] = rows
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -214,6 +253,9 @@ def main() -> int:
                     help="short run to put under rocprofv3 --pmc: pools filled directly with N(0,1), "
                          "W+K decode steps, then 4 copy launches of 256 MiB (the known-size kernel the "
                          "traffic counters are scaled by); no timing, no oracle")
+    ap.add_argument("--tile-sweep", action="store_true",
+                    help="instead of the headline run: tile-size sweep and padded baseline at T=16384, "
+                         "printed as one JSON line")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -233,6 +275,9 @@ def main() -> int:
     T.load()
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.tile_sweep:
+        print(json.dumps({"tile_size_sweep": tile_sweep(torch, T, BlockStore, synth, dev)}))
+        return 0
 
     B, Hq, Hkv, D, Z, t = 16, 24, 8, 128, 256, 4095
     R = args.layers

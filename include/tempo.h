@@ -228,6 +228,21 @@ int tempo_decode_step_window(const tempo_kv* kv, const void* q, const void* k_ne
                              void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Padded + masked baseline (Section 2.1, workaround (c): pad the dynamic dimension
+ * to a static bound and mask; Section 7.2 measures the dynamic formulation against
+ * it).  Same result as tempo_attn_decode_causal at step t, but the kernel reads and
+ * multiplies keys/values 0 .. t_pad of every sequence and masks those beyond the
+ * step by index (their contents never matter).  For measurement: its time is that
+ * of step t_pad whatever t is.  bf16 stores only (TEMPO_ERR_DTYPE otherwise);
+ * t <= t_pad, and step t_pad must fit the store (TEMPO_ERR_RANGE).  workspace as
+ * for step t_pad.
+ */
+int tempo_attn_decode_padded_causal(const tempo_kv* kv, const void* q, void* out, int32_t batch,
+                                    int32_t num_q_heads, int32_t t, const int32_t* t_per_seq,
+                                    int32_t t_pad, float scale, void* workspace,
+                                    size_t workspace_bytes, void* stream);
+
+/*
  * Rotary position embedding of the producer step, fused with the block-store
  * write (Section 6, kernel wrappers / "in-place writes": the kernel that produces
  * a value writes it straight to index t of the pre-allocated buffer; here the

@@ -18,7 +18,7 @@ __global__ __launch_bounds__(256) void attn_combine(AttnParams p) {
   const int b = blockIdx.y;  // blockIdx.x runs over the sequence's (query step, query head) rows
   int t_b = p.t_per_seq ? p.t_per_seq[b] : p.t;
   t_b = t_b > p.t ? p.t : (t_b < 0 ? 0 : t_b);
-  const SeqRange rg = seq_range(t_b, p.window, p.tps_log2, p.queries);
+  const SeqRange rg = seq_range(t_b, p.window, p.tps_log2, p.queries, p.pad_t);
   const int n = rg.nchunks < p.num_splits ? rg.nchunks : p.num_splits;
   const int64_t row = (int64_t)b * gridDim.x + blockIdx.x;
   const int esz = kBf16 ? 2 : 4;
@@ -36,7 +36,7 @@ __global__ __launch_bounds__(256) void attn_combine_few(AttnParams p, int rows) 
   const int b = row / (p.Hq * p.queries);
   int t_b = p.t_per_seq ? p.t_per_seq[b] : p.t;
   t_b = t_b > p.t ? p.t : (t_b < 0 ? 0 : t_b);
-  const SeqRange rg = seq_range(t_b, p.window, p.tps_log2, p.queries);
+  const SeqRange rg = seq_range(t_b, p.window, p.tps_log2, p.queries, p.pad_t);
   const int n = rg.nchunks < p.num_splits ? rg.nchunks : p.num_splits;  // 1..8
   const float* ml = p.ws_ml + (int64_t)row * p.num_splits * 2;
   const float* acc = p.ws_acc + (int64_t)row * p.num_splits * D + 4 * c4;

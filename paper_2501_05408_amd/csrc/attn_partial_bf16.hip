@@ -23,6 +23,11 @@
 // Only G of the 16 head columns carry data (G = 3 for the Llama shape): the MFMA
 // is mostly padding, which is free here -- the kernel is bound by HBM reads.
 //
+// Padded baseline.  With pad_t set the kernel reads keys and values up to pad_t
+// whatever the step is and masks what lies beyond the step: the static-shape
+// formulation (Section 2.1, workaround (c)) that the dynamic range is measured
+// against.
+//
 // Block of queries.  The 16 columns can also hold C consecutive query steps of
 // the G heads (column = c*G + g, C*G <= 16): step t+c sees keys up to t+c (and
 // from its own window start), which is one more per-lane bound in the index mask.
@@ -325,7 +330,7 @@ __global__ __launch_bounds__(512) void attn_partial_bf16(AttnParams p) {
   const int hkv = blockIdx.x, b = blockIdx.y;
   int t_b = p.t_per_seq ? ((const_i32_ptr)p.t_per_seq)[b] : p.t;
   t_b = t_b > p.t ? p.t : (t_b < 0 ? 0 : t_b);
-  const SeqRange rg = seq_range(t_b, p.window, p.tps_log2, p.queries);
+  const SeqRange rg = seq_range(t_b, p.window, p.tps_log2, p.queries, p.pad_t);
   if ((int)blockIdx.z >= rg.nchunks) return;  // uniform over the workgroup
   // Dispatch order: the split index is the slowest grid dimension and runs from
   // the newest split to the oldest.  The newest split of every (sequence, head)
@@ -374,6 +379,9 @@ __global__ __launch_bounds__(512) void attn_partial_bf16(AttnParams p) {
   int lo_last = (p.window > 0 && rg.hi - p.window + 1 > 0) ? rg.hi - p.window + 1 : 0;
   const int all_lo = lo_last > start ? lo_last : start;
   const int all_hi = t_b < end ? t_b : end;
+  // last key any column sees (below `end` only for the padded baseline, whose extra
+  // keys are read, masked out of the logits and zeroed in the value operand)
+  const int seen_hi = (t_b + p.queries - 1) < end ? (t_b + p.queries - 1) : end;
 
   // Query operand: lane (j + 16c) holds dims 32s + 8c .. +7 of column j (0 for unused columns).
   u32x4 qreg[KS];
@@ -408,7 +416,7 @@ __global__ __launch_bounds__(512) void attn_partial_bf16(AttnParams p) {
 
     uint32_t keep[4];
     const bool cut = (grp << 5) < all_lo || (grp << 5) + 31 > all_hi;  // wave-uniform
-    if (cut) edge_masks(grp, lo_col, hi_col, start, end, lane, x, keep);
+    if (cut) edge_masks(grp, lo_col, hi_col, start, seen_hi, lane, x, keep);
     const bf16x8 pa = softmax_update<D>(x, lane, st);
 
     if (grp == grp_new) append_values<D>(p, base, t_b, lane, stage, g);

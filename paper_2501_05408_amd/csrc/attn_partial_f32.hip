@@ -29,7 +29,7 @@ __global__ __launch_bounds__(512) void attn_partial_f32(AttnParams p) {
   const int hkv = hq / p.G;
   int t_b = p.t_per_seq ? p.t_per_seq[b] : p.t;
   t_b = t_b > p.t ? p.t : (t_b < 0 ? 0 : t_b);
-  const SeqRange rg = seq_range(t_b, p.window, p.tps_log2, p.queries);
+  const SeqRange rg = seq_range(t_b, p.window, p.tps_log2, p.queries, p.pad_t);
   if ((int)blockIdx.z >= rg.nchunks) return;
   const int split = rg.nchunks - 1 - (int)blockIdx.z;  // newest split first, as in the bf16 kernel
   const int chunk = rg.chunk0 + split;

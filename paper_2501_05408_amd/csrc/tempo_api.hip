@@ -177,14 +177,16 @@ void make_plan(const tempo_kv* kv, int32_t batch, int32_t Hq, int32_t t_max, int
 }
 
 // A uniform step needs its own split count; ragged steps (any t' <= t) need the bound.
-int check_plan(const tempo_plan* plan, int32_t t, int32_t window, bool ragged, int32_t queries) {
+int check_plan(const tempo_plan* plan, int32_t t, int32_t window, bool ragged, int32_t queries,
+               int32_t pad_t = 0) {
   if (!plan) return TEMPO_ERR_NULL;
   const int k = ilog2_exact(plan->tokens_per_split);
   if (k < 5) return TEMPO_ERR_SHAPE;
   if (plan->waves != 1 && plan->waves != 2 && plan->waves != 4 && plan->waves != 8) return TEMPO_ERR_SHAPE;
   if (plan->num_splits < 1 || plan->num_splits > 65535) return TEMPO_ERR_SHAPE;
-  const int32_t need = ragged ? splits_bound(last_step(t, queries), union_window(window, queries), k)
-                              : seq_range(t, window, k, queries).nchunks;
+  const int32_t cover = last_step(t, queries) > pad_t ? last_step(t, queries) : pad_t;
+  const int32_t need = ragged ? splits_bound(cover, union_window(window, queries), k)
+                              : seq_range(t, window, k, queries, pad_t).nchunks;
   if (plan->num_splits < need) return TEMPO_ERR_RANGE;
   return TEMPO_OK;
 }
@@ -215,7 +217,8 @@ constexpr size_t kMaxLds = 64 * 1024;
 
 AttnParams attn_params(const tempo_kv* kv, const void* q, void* out, int32_t Hq, int32_t t,
                        const int32_t* t_per_seq, int32_t window, float scale,
-                       const tempo_plan* plan, void* workspace, int32_t batch, int32_t queries) {
+                       const tempo_plan* plan, void* workspace, int32_t batch, int32_t queries,
+                       int32_t pad_t = 0) {
   AttnParams p;
   p.k_pool = kv->k_pool;
   p.v_pool = kv->v_pool;
@@ -242,6 +245,7 @@ AttnParams attn_params(const tempo_kv* kv, const void* q, void* out, int32_t Hq,
   p.tps_log2 = ilog2_exact(plan->tokens_per_split);
   p.num_splits = plan->num_splits;
   p.queries = queries;
+  p.pad_t = pad_t;
   p.direct = 0;
   p.scale_log2e = scale * 1.44269504088896340736f;
   return p;
@@ -267,23 +271,26 @@ StoreParams store_params(const tempo_kv* kv, int32_t batch, int32_t t, const int
 
 // Splits to launch along grid.x: exact for a uniform step, the bound for ragged steps.
 int32_t grid_splits(const tempo_plan* plan, int32_t t, const int32_t* t_per_seq, int32_t window,
-                    int32_t queries) {
+                    int32_t queries, int32_t pad_t) {
   if (t_per_seq) return plan->num_splits;
-  const int32_t exact = seq_range(t, window, ilog2_exact(plan->tokens_per_split), queries).nchunks;
+  const int32_t exact = seq_range(t, window, ilog2_exact(plan->tokens_per_split), queries, pad_t).nchunks;
   return exact < plan->num_splits ? exact : plan->num_splits;
 }
 
 int check_attn(const tempo_kv* kv, int32_t batch, int32_t Hq, int32_t t, int32_t window, bool ragged,
                const tempo_plan* plan, const void* workspace, size_t workspace_bytes,
-               int32_t queries = 1) {
+               int32_t queries = 1, int32_t pad_t = 0) {
   int rc = check_store(kv);
   if (rc != TEMPO_OK) return rc;
   if ((rc = check_heads(kv, batch, Hq)) != TEMPO_OK) return rc;
   if ((rc = check_queries(kv, Hq, queries)) != TEMPO_OK) return rc;
   if (window < 0 || t < 0 || t > INT32_MAX - 64) return TEMPO_ERR_RANGE;
-  if ((rc = check_step(kv, last_step(t, queries))) != TEMPO_OK) return rc;
-  if ((rc = check_ring_covers(kv, last_step(t, queries), union_window(window, queries))) != TEMPO_OK) return rc;
-  if ((rc = check_plan(plan, t, window, ragged, queries)) != TEMPO_OK) return rc;
+  // the padded baseline is causal only: with a window the range's length would depend on the step
+  if (pad_t < 0 || (pad_t > 0 && window != 0)) return TEMPO_ERR_RANGE;
+  const int32_t cover = last_step(t, queries) > pad_t ? last_step(t, queries) : pad_t;
+  if ((rc = check_step(kv, cover)) != TEMPO_OK) return rc;
+  if ((rc = check_ring_covers(kv, cover, union_window(window, queries))) != TEMPO_OK) return rc;
+  if ((rc = check_plan(plan, t, window, ragged, queries, pad_t)) != TEMPO_OK) return rc;
   if (kv->dtype == TEMPO_BF16 &&
       partial_bf16_lds(plan->waves, queries * (Hq / kv->num_kv_heads), kv->head_dim) > kMaxLds)
     return TEMPO_ERR_SHAPE;
@@ -298,8 +305,8 @@ int check_attn(const tempo_kv* kv, int32_t batch, int32_t Hq, int32_t t, int32_t
 int do_partial(const tempo_kv* kv, const void* q, const void* k_new, const void* v_new, void* out,
                int32_t batch, int32_t Hq, int32_t t, const int32_t* t_per_seq, int32_t window,
                float scale, const tempo_plan* plan, void* workspace, hipStream_t stream,
-               int32_t queries = 1, const tempo_rope* rope = nullptr) {
-  AttnParams p = attn_params(kv, q, out, Hq, t, t_per_seq, window, scale, plan, workspace, batch, queries);
+               int32_t queries = 1, const tempo_rope* rope = nullptr, int32_t pad_t = 0) {
+  AttnParams p = attn_params(kv, q, out, Hq, t, t_per_seq, window, scale, plan, workspace, batch, queries, pad_t);
   p.direct = (out != nullptr && plan->num_splits == 1) ? 1 : 0;
   p.k_new = k_new;
   p.v_new = v_new;
@@ -307,7 +314,7 @@ int do_partial(const tempo_kv* kv, const void* q, const void* k_new, const void*
     p.rope_cos = rope->cos;
     p.rope_sin = rope->sin;
   }
-  const int32_t gs = grid_splits(plan, t, t_per_seq, window, queries);
+  const int32_t gs = grid_splits(plan, t, t_per_seq, window, queries, pad_t);
   const hipError_t e = kv->dtype == TEMPO_BF16
                            ? launch_partial_bf16(p, batch, kv->head_dim, gs, plan->waves, stream)
                            : launch_partial_f32(p, batch, kv->head_dim, gs, plan->waves, stream);
@@ -316,8 +323,9 @@ int do_partial(const tempo_kv* kv, const void* q, const void* k_new, const void*
 
 int do_combine(const tempo_kv* kv, void* out, int32_t batch, int32_t Hq, int32_t t,
                const int32_t* t_per_seq, int32_t window, const tempo_plan* plan, void* workspace,
-               hipStream_t stream, int32_t queries = 1) {
-  AttnParams p = attn_params(kv, nullptr, out, Hq, t, t_per_seq, window, 1.0f, plan, workspace, batch, queries);
+               hipStream_t stream, int32_t queries = 1, int32_t pad_t = 0) {
+  AttnParams p = attn_params(kv, nullptr, out, Hq, t, t_per_seq, window, 1.0f, plan, workspace, batch, queries,
+                             pad_t);
   const hipError_t e = launch_combine(p, batch, kv->head_dim, kv->dtype, stream);
   return launch_status(e, "attn_decode_combine");
 }
@@ -336,7 +344,7 @@ void make_block_plan(const tempo_kv* kv, int32_t batch, int32_t Hq, int32_t t, i
 int decode(const tempo_kv* kv, const void* q, const void* k_new, const void* v_new, void* out,
            int32_t batch, int32_t Hq, int32_t t, const int32_t* t_per_seq, int32_t window, float scale,
            void* workspace, size_t workspace_bytes, void* stream, int32_t queries = 1,
-           const tempo_rope* rope = nullptr) {
+           const tempo_rope* rope = nullptr, int32_t pad_t = 0) {
   int rc = check_layout(kv);
   if (rc != TEMPO_OK) return rc;
   if (!q || !out) return TEMPO_ERR_NULL;
@@ -344,14 +352,18 @@ int decode(const tempo_kv* kv, const void* q, const void* k_new, const void* v_n
   if ((rc = check_queries(kv, Hq, queries)) != TEMPO_OK) return rc;
   if (t < 0 || window < 0 || t > INT32_MAX - 64) return TEMPO_ERR_RANGE;
   if (rope && (rc = check_rope(rope, kv->head_dim, last_step(t, queries))) != TEMPO_OK) return rc;
+  if (pad_t < 0 || pad_t > INT32_MAX - 64) return TEMPO_ERR_RANGE;
   tempo_plan plan;
-  make_block_plan(kv, batch, Hq, t, window, t_per_seq != nullptr, queries, &plan);
-  if ((rc = check_attn(kv, batch, Hq, t, window, t_per_seq != nullptr, &plan, workspace, workspace_bytes, queries)) != TEMPO_OK) return rc;
+  // the padded baseline is planned as the step it pretends every step to be
+  make_block_plan(kv, batch, Hq, pad_t > t ? pad_t : t, window, t_per_seq != nullptr, queries, &plan);
+  if ((rc = check_attn(kv, batch, Hq, t, window, t_per_seq != nullptr, &plan, workspace, workspace_bytes, queries,
+                       pad_t)) != TEMPO_OK)
+    return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   rc = do_partial(kv, q, k_new, v_new, out, batch, Hq, t, t_per_seq, window, scale, &plan, workspace, s, queries,
-                  rope);
+                  rope, pad_t);
   if (rc != TEMPO_OK || plan.num_splits == 1) return rc;  // a single split wrote `out` itself
-  return do_combine(kv, out, batch, Hq, t, t_per_seq, window, &plan, workspace, s, queries);
+  return do_combine(kv, out, batch, Hq, t, t_per_seq, window, &plan, workspace, s, queries, pad_t);
 }
 
 }  // namespace
@@ -544,6 +556,16 @@ int tempo_decode_step_window(const tempo_kv* kv, const void* q, const void* k_ne
   if (window < 1) return TEMPO_ERR_RANGE;
   return decode(kv, q, k_new, v_new, out, batch, num_q_heads, t, t_per_seq, window, scale, workspace,
                 workspace_bytes, stream);
+}
+
+int tempo_attn_decode_padded_causal(const tempo_kv* kv, const void* q, void* out, int32_t batch,
+                                    int32_t num_q_heads, int32_t t, const int32_t* t_per_seq,
+                                    int32_t t_pad, float scale, void* workspace, size_t workspace_bytes,
+                                    void* stream) {
+  if (kv && kv->dtype == TEMPO_F32) return TEMPO_ERR_DTYPE;  // the baseline exists for the bf16 kernel only
+  if (t_pad < t) return TEMPO_ERR_RANGE;
+  return decode(kv, q, nullptr, nullptr, out, batch, num_q_heads, t, t_per_seq, 0, scale, workspace,
+                workspace_bytes, stream, 1, nullptr, t_pad);
 }
 
 int tempo_rope_rotate(const tempo_rope* rope, const void* x, void* y, int32_t dtype, int32_t batch,

@@ -91,19 +91,23 @@ struct AttnParams {
   int32_t tps_log2;          // log2(tokens per split)
   int32_t num_splits;        // S: stride of the split axis in the workspace
   int32_t queries;           // C: consecutive query steps per sequence (q, out, workspace rows are [B][C][Hq])
+  int32_t pad_t;             // padded baseline: keys up to pad_t are read and masked; 0 = none
   int32_t direct;            // 1: single split, write `out` and skip the combine
   float scale_log2e;         // s * log2(e)
 };
 
 // Visible range and split bookkeeping of one sequence, identical on host and device.
 // With a block of C queries (steps t_b .. t_b+C-1) the range is the union of the
-// queries' ranges: from the first query's lo to the last query's step.
+// queries' ranges: from the first query's lo to the last query's step.  The padded
+// baseline reads on to key pad_t (masked beyond each query's own step).
 struct SeqRange {
   int lo, hi, chunk0, nchunks;
 };
-__host__ __device__ inline SeqRange seq_range(int t_b, int window, int tps_log2, int queries = 1) {
+__host__ __device__ inline SeqRange seq_range(int t_b, int window, int tps_log2, int queries = 1,
+                                              int pad_t = 0) {
   SeqRange r;
   r.hi = t_b + queries - 1;
+  r.hi = r.hi > pad_t ? r.hi : pad_t;
   r.lo = (window > 0 && t_b - window + 1 > 0) ? t_b - window + 1 : 0;
   r.chunk0 = r.lo >> tps_log2;
   r.nchunks = (r.hi >> tps_log2) - r.chunk0 + 1;

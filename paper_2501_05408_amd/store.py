@@ -89,6 +89,13 @@ class BlockStore:
                                    self.workspace_bytes)
         return out
 
+    def attend_padded(self, q, out, t, t_pad, t_per_seq=None, scale=None):
+        """The padded + masked baseline: reads keys 0..t_pad, masks those beyond t."""
+        T.tempo_attn_decode_padded_causal(self.kv, q, out, self.batch, self.Hq, t, t_per_seq, t_pad,
+                                          self.scale if scale is None else scale, self.workspace,
+                                          self.workspace_bytes)
+        return out
+
     def step_causal(self, q, k_new, v_new, out, t, t_per_seq=None, scale=None):
         """Append step t and attend over 0..t in one launch."""
         T.tempo_decode_step_causal(self.kv, q, k_new, v_new, out, self.batch, self.Hq, t, t_per_seq,

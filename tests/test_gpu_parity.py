@@ -228,6 +228,41 @@ def test_ragged_steps_random_block_table(dtype, window):
 
 
 # ----------------------------------------------------------------------------
+# The padded + masked baseline gives the same result as the dynamic range at every
+# step, while the pool beyond the step holds NaN (masking is by index).
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("B,t_pad", [(2, 229), (1, 699)])
+def test_padded_baseline_matches_oracle_every_step(B, t_pad):
+    Hq, Hkv, D, Z = 6, 2, 128, 64
+    steps = t_pad + 1
+    dtype = T.TEMPO_BF16
+    q, K, V = host_inputs(6, B, steps, Hq, Hkv, D, dtype)
+    st = BlockStore(B, Hq, Hkv, D, Z, steps - 1, dtype, fill="nan")
+    qd, Kd, Vd = dev(q, dtype), dev(K, dtype), dev(V, dtype)
+    todo = list(range(steps)) if B == 2 else list(range(0, steps, 7)) + [steps - 1]
+    outs = torch.empty((steps, B, Hq, D), dtype=torch.bfloat16, device=DEV)
+    for t in range(steps):
+        st.append(Kd[:, t].contiguous(), Vd[:, t].contiguous(), t)
+        if t in todo:
+            st.attend_padded(qd[t], outs[t], t, t_pad)
+    torch.cuda.synchronize()
+    got = np64(outs)
+    K64, V64 = K.astype(np.float64), V.astype(np.float64)
+    for t in todo:
+        ref = oracle.attend(q[t].astype(np.float64), K64, V64, t, 0, 1.0 / np.sqrt(D))
+        assert_close(got[t], ref, dtype, f"padded baseline t={t} of {t_pad}")
+    # per-sequence steps under one padding bound
+    tps = torch.tensor([t_pad // 3, 5][:B], dtype=torch.int32, device=DEV)
+    out = st.attend_padded(qd[0], st.new_out(), t_pad, t_pad, t_per_seq=tps)
+    ref = oracle.attend(q[0].astype(np.float64), K64, V64, tps.cpu().numpy(), 0, 1.0 / np.sqrt(D))
+    assert_close(out, ref, dtype, "padded baseline, per-sequence steps")
+    with pytest.raises(T.TempoError):
+        st.attend_padded(qd[0], st.new_out(), 10, 9)             # padding bound below the step
+    with pytest.raises(T.TempoError):
+        st.attend_padded(qd[0], st.new_out(), 10, st.max_t + 1)  # beyond the store
+
+
+# ----------------------------------------------------------------------------
 # Any valid split plan gives the same result within tolerance; same plan, same bits.
 # ----------------------------------------------------------------------------
 @pytest.mark.parametrize("dtype", [T.TEMPO_BF16, T.TEMPO_F32])
