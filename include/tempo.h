@@ -306,8 +306,10 @@ int tempo_rope_decode_step_window(const tempo_kv* kv, const tempo_rope* rope, co
  *   q, out   device, [batch][queries][num_q_heads][head_dim], kv->dtype
  *   t        first step of the block (uniform), or with t_per_seq the upper bound of
  *            the per-sequence first steps t_per_seq[b]
- * Limits: queries >= 1 and queries * (num_q_heads / num_kv_heads) <= 16
- * (TEMPO_ERR_SHAPE otherwise).  workspace: device, 256-byte aligned, at least
+ * Limits: queries >= 1 and queries * (num_q_heads / num_kv_heads) <= 64
+ * (TEMPO_ERR_SHAPE otherwise): up to 16 such (step, head) columns ride in the
+ * padding of the single-step kernel's tiles, 17..64 use kernels with two or four
+ * column tiles per wavefront.  workspace: device, 256-byte aligned, at least
  * tempo_attn_block_workspace_bytes(kv, batch, num_q_heads, queries, t) bytes.
  * Other arguments, launches and errors as tempo_attn_decode_causal / _window.
  */

@@ -48,11 +48,13 @@ int check_heads(const tempo_kv* kv, int32_t batch, int32_t Hq) {
   return TEMPO_OK;
 }
 
-// A block of C consecutive query steps shares the 16 columns of the bf16 kernel's
-// tiles with the query group: C * (Hq / Hkv) <= 16 (the same limit for fp32).
+// A block of C consecutive query steps shares the columns of the bf16 kernel's
+// tiles with the query group: C * (Hq / Hkv) <= 64, up to four tiles of 16 columns
+// per wavefront (the same limit for fp32).
+constexpr int kMaxColumns = 64;
 int check_queries(const tempo_kv* kv, int32_t Hq, int32_t queries) {
-  if (queries < 1 || queries > 16) return TEMPO_ERR_SHAPE;
-  if ((int64_t)queries * (Hq / kv->num_kv_heads) > 16) return TEMPO_ERR_SHAPE;
+  if (queries < 1 || queries > kMaxColumns) return TEMPO_ERR_SHAPE;
+  if ((int64_t)queries * (Hq / kv->num_kv_heads) > kMaxColumns) return TEMPO_ERR_SHAPE;
   if ((int64_t)queries * Hq > 65535) return TEMPO_ERR_SHAPE;
   return TEMPO_OK;
 }
@@ -208,11 +210,6 @@ size_t plan_bytes(const tempo_kv* kv, int64_t rows, int32_t S) {
   return ml_bytes(rows, S) + align_up((size_t)rows * S * kv->head_dim * sizeof(float), 256);
 }
 
-// LDS of the bf16 partial kernel: per wavefront 32 floats of (m, l) and one
-// accumulator row per column, plus the two staged rows of a fused append.
-size_t partial_bf16_lds(int waves, int columns, int D) {
-  return (size_t)waves * (32 + (size_t)columns * D) * sizeof(float) + 2 * (size_t)D * sizeof(uint16_t);
-}
 constexpr size_t kMaxLds = 64 * 1024;
 
 AttnParams attn_params(const tempo_kv* kv, const void* q, void* out, int32_t Hq, int32_t t,
@@ -291,9 +288,11 @@ int check_attn(const tempo_kv* kv, int32_t batch, int32_t Hq, int32_t t, int32_t
   if ((rc = check_step(kv, cover)) != TEMPO_OK) return rc;
   if ((rc = check_ring_covers(kv, cover, union_window(window, queries))) != TEMPO_OK) return rc;
   if ((rc = check_plan(plan, t, window, ragged, queries, pad_t)) != TEMPO_OK) return rc;
-  if (kv->dtype == TEMPO_BF16 &&
-      partial_bf16_lds(plan->waves, queries * (Hq / kv->num_kv_heads), kv->head_dim) > kMaxLds)
-    return TEMPO_ERR_SHAPE;
+  if (kv->dtype == TEMPO_BF16) {
+    const int columns = queries * (Hq / kv->num_kv_heads);
+    if (partial_bf16_lds_bytes(plan->waves, columns, kv->head_dim) > kMaxLds) return TEMPO_ERR_SHAPE;
+    if (partial_bf16_column_tiles(columns) > 2 && plan->waves > 4) return TEMPO_ERR_SHAPE;
+  }
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return TEMPO_ERR_WORKSPACE;
   if (workspace_bytes < plan_bytes(kv, (int64_t)batch * queries * Hq, plan->num_splits)) return TEMPO_ERR_WORKSPACE;
   return TEMPO_OK;
@@ -338,7 +337,10 @@ void make_block_plan(const tempo_kv* kv, int32_t batch, int32_t Hq, int32_t t, i
   make_plan(kv, batch, Hq, last_step(t, queries), union_window(window, queries), ragged, plan);
   if (kv->dtype != TEMPO_BF16) return;
   const int columns = queries * (Hq / kv->num_kv_heads);
-  while (plan->waves > 1 && partial_bf16_lds(plan->waves, columns, kv->head_dim) > kMaxLds) plan->waves /= 2;
+  // the kernel for four column tiles keeps four tiles of accumulators in registers
+  // and is built for workgroups of at most four wavefronts
+  if (partial_bf16_column_tiles(columns) > 2 && plan->waves > 4) plan->waves = 4;
+  while (plan->waves > 1 && partial_bf16_lds_bytes(plan->waves, columns, kv->head_dim) > kMaxLds) plan->waves /= 2;
 }
 
 int decode(const tempo_kv* kv, const void* q, const void* k_new, const void* v_new, void* out,

@@ -137,6 +137,8 @@ hipError_t launch_gather(const StoreParams& p, void* k_out, void* v_out, int D, 
                          int count, hipStream_t stream);
 hipError_t launch_partial_bf16(const AttnParams& p, int batch, int D, int grid_splits, int waves,
                                hipStream_t stream);
+int partial_bf16_column_tiles(int columns);                        // 1, 2 or 4 tiles of 16 columns
+size_t partial_bf16_lds_bytes(int waves, int columns, int D);      // dynamic LDS of that launch
 hipError_t launch_partial_f32(const AttnParams& p, int batch, int D, int grid_splits, int waves,
                               hipStream_t stream);
 

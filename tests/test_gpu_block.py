@@ -106,7 +106,10 @@ def test_block_fp32_every_start(window, C):
 # one sequence so the planner cuts the range into many short splits (queries whose
 # range misses a split; both combine kernels), pool poisoned beyond the last step.
 # ----------------------------------------------------------------------------
-@pytest.mark.parametrize("G,C,D", [(3, 5, 128), (1, 16, 128), (4, 4, 64), (2, 3, 128), (16, 1, 64), (5, 3, 128)])
+@pytest.mark.parametrize("G,C,D", [(3, 5, 128), (1, 16, 128), (4, 4, 64), (2, 3, 128), (16, 1, 64), (5, 3, 128),
+                                   # more than 16 columns: two and four column tiles per wavefront
+                                   (3, 10, 128), (3, 21, 128), (1, 64, 64), (4, 16, 128), (2, 9, 64), (16, 4, 128),
+                                   (1, 17, 128), (5, 7, 64)])
 @pytest.mark.parametrize("window", [0, 1, 2, 33, 64, 65, 200])
 def test_block_bf16_every_start(G, C, D, window):
     B, Hkv, Z, steps = 1, 2, 64, 700
@@ -191,11 +194,13 @@ def test_block_on_ring_store_bf16():
 
 
 # ----------------------------------------------------------------------------
-# Full-size Llama shape: blocks of 5 steps (5 x 3 heads = 15 of the 16 columns),
-# including blocks that straddle the planner's split boundary at key 2048.
+# Full-size Llama shape: blocks of 5 steps (5 x 3 heads = 15 of the 16 columns)
+# and of 21 steps (63 columns, four column tiles), including blocks that straddle
+# the planner's split boundary at key 2048.
 # ----------------------------------------------------------------------------
-def test_llama_shape_block_bf16_full_size():
-    B, Hq, Hkv, D, Z, T_len, C = 16, 24, 8, 128, 256, 4096, 5
+@pytest.mark.parametrize("C", [5, 21])
+def test_llama_shape_block_bf16_full_size(C):
+    B, Hq, Hkv, D, Z, T_len = 16, 24, 8, 128, 256, 4096
     dtype = T.TEMPO_BF16
     K, V = flat_kv(46, B, T_len, Hkv, D)
     table, nb = random_table(46, B, T_len // Z, extra=0)
@@ -203,7 +208,7 @@ def test_llama_shape_block_bf16_full_size():
     st.prefill(K, V, T_len - 1)
     K64, V64 = np64(K), np64(V)
     for window in (0, 512):
-        for t0 in (0, 29, 2043, 2044, 2046, 2048, 4091):
+        for t0 in (0, 29, 2043 - (C - 5), 2044, 2046, 2048, 4096 - C):
             q = synth.device_normal((B, C, Hq, D), 4600 + t0, torch.bfloat16, DEV)
             out = torch.empty((B, C, Hq, D), dtype=torch.bfloat16, device=DEV)
             st.attend_block(q, out, t0, C, window)
