@@ -91,6 +91,37 @@ def other_workloads(torch, T, BlockStore, synth, dev, kv_bytes_per_token):
                                "kv_gbs": round(16 * 4096 * kv_bytes_per_token / dt / 1e9, 1),
                                "splits": plan.num_splits, "tokens_per_split": plan.tokens_per_split,
                                "waves": plan.waves}
+    # wider blocks: 10 steps (30 columns, two column tiles) and 21 steps (63 columns, four tiles)
+    for C in (10, 21):
+        qc = synth.device_normal((16, C, Hq, D), 177, torch.bfloat16, dev)
+        kc = synth.device_normal((16, C, Hkv, D), 178, torch.bfloat16, dev)
+        vc = synth.device_normal((16, C, Hkv, D), 179, torch.bfloat16, dev)
+        oc = torch.empty_like(qc)
+
+        def wide_step(i):
+            sts[i % 8].append_block(kc, vc, 4096 - C, C)
+            sts[i % 8].attend_block(qc, oc, 4096 - C, C)
+
+        dt = _timed(torch, wide_step, 200, 20)
+        plan = T.tempo_attn_block_plan(sts[0].kv, 16, Hq, C, 4096 - C, 0)
+        out[f"block{C}_b16_t{4096 - C}"] = {"us_per_call": round(dt * 1e6, 2),
+                                            "us_per_query_step": round(dt * 1e6 / C, 2),
+                                            "kv_gbs": round(16 * 4096 * kv_bytes_per_token / dt / 1e9, 1),
+                                            "splits": plan.num_splits, "tokens_per_split": plan.tokens_per_split,
+                                            "waves": plan.waves}
+    # prompt processing: 4096 steps of 16 sequences in one tempo_prefill_causal call
+    # (195 blocks of 21 steps + one of 1; per block: append, partial attention, combine)
+    P = 4096
+    qp = synth.device_normal((16, P, Hq, D), 277, torch.bfloat16, dev)
+    kp = synth.device_normal((16, P, Hkv, D), 278, torch.bfloat16, dev)
+    vp = synth.device_normal((16, P, Hkv, D), 279, torch.bfloat16, dev)
+    op = torch.empty_like(qp)
+    dt = _timed(torch, lambda i: sts[i % 8].prefill_attend(qp, kp, vp, op, 0, P), 5, 1)
+    pairs = P * (P + 1) // 2                                             # (query, key) pairs per sequence
+    out["prompt_b16_t4096"] = {"ms": round(dt * 1e3, 3), "tokens_per_s": round(16 * P / dt, 1),
+                               "tflops": round(16 * pairs * 4 * D * Hq / dt / 1e12, 1),
+                               "note": "one call; flops = 4*D*Hq per (query, key) pair"}
+    del qp, kp, vp, op
     del sts
     torch.cuda.empty_cache()
 

@@ -323,6 +323,46 @@ int tempo_attn_block_window(const tempo_kv* kv, const void* q, void* out, int32_
                             const int32_t* t_per_seq, int32_t window, float scale, void* workspace,
                             size_t workspace_bytes, void* stream);
 
+/*
+ * Prompt processing (Section 2: prompt tokens are processed before decoding
+ * starts; Section 4.3: the temporal dimension evaluated in tiles): steps
+ * t .. t+count-1 of every sequence in ONE call.  The keys/values of those steps are
+ * written to the store and every step's query attends over its own range (keys
+ * 0 .. t+c, or its window), exactly as `count` single decode steps would.  Work is
+ * issued in blocks of 64 / (num_q_heads / num_kv_heads) steps: per block one
+ * tempo_kv_append_block and one tempo_attn_block_* (all launches asynchronous on
+ * `stream`, nothing allocated).
+ *   q, out        device, [batch][count][num_q_heads][head_dim]
+ *   k_new, v_new  device, [batch][count][num_kv_heads][head_dim]
+ *   workspace     device, 256-byte aligned, >= tempo_prefill_workspace_bytes(kv, batch,
+ *                 num_q_heads, t + count - 1) bytes
+ * All arguments are validated for every block before the first launch.
+ */
+int tempo_prefill_causal(const tempo_kv* kv, const void* q, const void* k_new, const void* v_new,
+                         void* out, int32_t batch, int32_t num_q_heads, int32_t t, int32_t count,
+                         float scale, void* workspace, size_t workspace_bytes, void* stream);
+
+int tempo_prefill_window(const tempo_kv* kv, const void* q, const void* k_new, const void* v_new,
+                         void* out, int32_t batch, int32_t num_q_heads, int32_t t, int32_t count,
+                         int32_t window, float scale, void* workspace, size_t workspace_bytes,
+                         void* stream);
+
+/* Workspace bound for tempo_prefill_* calls whose last step is at most max_t (host only). */
+size_t tempo_prefill_workspace_bytes(const tempo_kv* kv, int32_t batch, int32_t num_q_heads,
+                                     int32_t max_t);
+
+/* tempo_attn_block_causal (window = 0) or _window with the caller's plan instead of
+ * the library's (for sweeping plans).  The plan must cover the union of the block's
+ * ranges and satisfy the limits of tempo_attn_block_plan's results (at most 4
+ * wavefronts above 32 columns, wave-merge area within 64 KiB of LDS); workspace at
+ * least batch * queries * num_q_heads rows of plan->num_splits partials
+ * (tempo_attn_plan_workspace_bytes with batch * queries as the batch). */
+int tempo_attn_block_with_plan(const tempo_kv* kv, const void* q, void* out, int32_t batch,
+                               int32_t num_q_heads, int32_t queries, int32_t t,
+                               const int32_t* t_per_seq, int32_t window, float scale,
+                               const tempo_plan* plan, void* workspace, size_t workspace_bytes,
+                               void* stream);
+
 /* The plan tempo_attn_block_* use for a block whose first step is t_max (host
  * only): tempo_attn_plan for the union of the queries' ranges, with fewer
  * wavefronts where the per-column accumulators would not fit the workgroup's LDS.

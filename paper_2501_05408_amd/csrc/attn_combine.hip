@@ -21,9 +21,10 @@ __global__ __launch_bounds__(256) void attn_combine(AttnParams p) {
   const SeqRange rg = seq_range(t_b, p.window, p.tps_log2, p.queries, p.pad_t);
   const int n = rg.nchunks < p.num_splits ? rg.nchunks : p.num_splits;
   const int64_t row = (int64_t)b * gridDim.x + blockIdx.x;
+  const int64_t orow = (int64_t)b * p.io_steps * p.Hq + blockIdx.x;  // rows of `out` may be strided per sequence
   const int esz = kBf16 ? 2 : 4;
   combine_heads<D, kBf16>(p.ws_ml + row * p.num_splits * 2, p.ws_acc + row * p.num_splits * D,
-                                 p.num_splits, n, 1, static_cast<char*>(p.out) + row * D * esz, smem);
+                                 p.num_splits, n, 1, static_cast<char*>(p.out) + orow * D * esz, smem);
 }
 
 template <int D, bool kBf16>
@@ -34,6 +35,7 @@ __global__ __launch_bounds__(256) void attn_combine_few(AttnParams p, int rows) 
   const int row = idx / C4, c4 = idx - row * C4;
   if (row >= rows) return;
   const int b = row / (p.Hq * p.queries);
+  const int64_t orow = (int64_t)b * p.io_steps * p.Hq + (row - b * (p.Hq * p.queries));
   int t_b = p.t_per_seq ? p.t_per_seq[b] : p.t;
   t_b = t_b > p.t ? p.t : (t_b < 0 ? 0 : t_b);
   const SeqRange rg = seq_range(t_b, p.window, p.tps_log2, p.queries, p.pad_t);
@@ -70,10 +72,10 @@ __global__ __launch_bounds__(256) void attn_combine_few(AttnParams p, int rows) 
     bf16x4 o;
     o[0] = (__bf16)(A.x * inv); o[1] = (__bf16)(A.y * inv);
     o[2] = (__bf16)(A.z * inv); o[3] = (__bf16)(A.w * inv);
-    *reinterpret_cast<bf16x4*>(static_cast<__bf16*>(p.out) + (int64_t)row * D + 4 * c4) = o;
+    *reinterpret_cast<bf16x4*>(static_cast<__bf16*>(p.out) + orow * D + 4 * c4) = o;
   } else {
     const float4 o = {A.x * inv, A.y * inv, A.z * inv, A.w * inv};
-    *reinterpret_cast<float4*>(static_cast<float*>(p.out) + (int64_t)row * D + 4 * c4) = o;
+    *reinterpret_cast<float4*>(static_cast<float*>(p.out) + orow * D + 4 * c4) = o;
   }
 }
 

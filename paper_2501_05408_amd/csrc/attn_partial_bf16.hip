@@ -404,7 +404,7 @@ __global__ __launch_bounds__(NT <= 2 ? 512 : 256) void attn_partial_bf16(AttnPar
     lo_col[jt] = lo_q > start ? lo_q : start;
     const int c = lane >> 4;
     const uint16_t* qp = static_cast<const uint16_t*>(p.q) +
-                         (((int64_t)b * p.queries + cq) * p.Hq + (int64_t)hkv * p.G + gq) * D + 8 * c;
+                         (((int64_t)b * p.io_steps + cq) * p.Hq + (int64_t)hkv * p.G + gq) * D + 8 * c;
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
       const u32x4 zero = {0u, 0u, 0u, 0u};
@@ -530,7 +530,8 @@ __global__ __launch_bounds__(NT <= 2 ? 512 : 256) void attn_partial_bf16(AttnPar
       const int jc = col / p.G, jg = col - jc * p.G;
       const int64_t row = ((int64_t)b * p.queries + jc) * p.Hq + (int64_t)hkv * p.G + jg;
       if (p.direct) {
-        static_cast<__bf16*>(p.out)[row * D + d] = (__bf16)(num / den);
+        const int64_t orow = ((int64_t)b * p.io_steps + jc) * p.Hq + (int64_t)hkv * p.G + jg;
+        static_cast<__bf16*>(p.out)[orow * D + d] = (__bf16)(num / den);
       } else {
         const int64_t part = row * p.num_splits + split;
         p.ws_acc[part * D + d] = num;

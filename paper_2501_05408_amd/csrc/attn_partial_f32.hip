@@ -52,7 +52,7 @@ __global__ __launch_bounds__(512) void attn_partial_f32(AttnParams p) {
 
   float qv[E];
   {
-    const float* qp = static_cast<const float*>(p.q) + (((int64_t)b * p.queries + cq) * p.Hq + hq) * D + col * E;
+    const float* qp = static_cast<const float*>(p.q) + (((int64_t)b * p.io_steps + cq) * p.Hq + hq) * D + col * E;
 #pragma unroll
     for (int e = 0; e < E; ++e) qv[e] = qp[e];
   }
@@ -148,7 +148,8 @@ __global__ __launch_bounds__(512) void attn_partial_f32(AttnParams p) {
     }
     const int64_t qrow = ((int64_t)b * p.queries + cq) * p.Hq + hq;
     if (p.direct) {
-      static_cast<float*>(p.out)[qrow * D + d] = num / den;
+      const int64_t orow = ((int64_t)b * p.io_steps + cq) * p.Hq + hq;
+      static_cast<float*>(p.out)[orow * D + d] = num / den;
     } else {
       const int64_t part = qrow * p.num_splits + split;
       p.ws_acc[part * D + d] = num;

@@ -37,10 +37,11 @@ __global__ __launch_bounds__(256) void kv_append_bf16(StoreParams p, const uint1
   const int phys = clamp_block(p.block_table[(int64_t)b * p.max_blocks_per_seq + (tile & p.tile_mask)], p.num_blocks);
   const int64_t base = ((int64_t)phys * p.Hkv + head) * Z * D;
   uint16_t* vp = static_cast<uint16_t*>(p.v_pool);
-  vp[base + tile_off_v_bf16(D, slot, d)] = v_new[idx];
+  const int64_t src = (((int64_t)b * p.src_steps + c) * p.Hkv + head) * D + d;
+  vp[base + tile_off_v_bf16(D, slot, d)] = v_new[src];
   if ((d & 7) == 0) {
     uint16_t* kp = static_cast<uint16_t*>(p.k_pool);
-    const uint4 unit = *reinterpret_cast<const uint4*>(k_new + idx);
+    const uint4 unit = *reinterpret_cast<const uint4*>(k_new + src);
     *reinterpret_cast<uint4*>(kp + base + tile_off_k_bf16(D, slot, d)) = unit;
   }
 }
@@ -61,7 +62,7 @@ __global__ __launch_bounds__(256) void kv_append_f32(StoreParams p, const float*
   const int tile = t >> p.z_log2, slot = t & (Z - 1);
   const int phys = clamp_block(p.block_table[(int64_t)b * p.max_blocks_per_seq + (tile & p.tile_mask)], p.num_blocks);
   const int64_t off = ((int64_t)phys * p.Hkv + head) * Z * D + tile_off_f32(D, slot, d);
-  const int64_t src = (((int64_t)b * p.count + c) * p.Hkv + head) * D + d;
+  const int64_t src = (((int64_t)b * p.src_steps + c) * p.Hkv + head) * D + d;
   *reinterpret_cast<float4*>(static_cast<float*>(p.k_pool) + off) =
       *reinterpret_cast<const float4*>(k_new + src);
   *reinterpret_cast<float4*>(static_cast<float*>(p.v_pool) + off) =

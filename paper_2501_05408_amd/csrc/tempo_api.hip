@@ -242,6 +242,7 @@ AttnParams attn_params(const tempo_kv* kv, const void* q, void* out, int32_t Hq,
   p.tps_log2 = ilog2_exact(plan->tokens_per_split);
   p.num_splits = plan->num_splits;
   p.queries = queries;
+  p.io_steps = queries;
   p.pad_t = pad_t;
   p.direct = 0;
   p.scale_log2e = scale * 1.44269504088896340736f;
@@ -263,6 +264,7 @@ StoreParams store_params(const tempo_kv* kv, int32_t batch, int32_t t, const int
   p.Hkv = kv->num_kv_heads;
   p.batch = batch;
   p.count = count;
+  p.src_steps = count;
   return p;
 }
 
@@ -304,8 +306,9 @@ int check_attn(const tempo_kv* kv, int32_t batch, int32_t Hq, int32_t t, int32_t
 int do_partial(const tempo_kv* kv, const void* q, const void* k_new, const void* v_new, void* out,
                int32_t batch, int32_t Hq, int32_t t, const int32_t* t_per_seq, int32_t window,
                float scale, const tempo_plan* plan, void* workspace, hipStream_t stream,
-               int32_t queries = 1, const tempo_rope* rope = nullptr, int32_t pad_t = 0) {
+               int32_t queries = 1, const tempo_rope* rope = nullptr, int32_t pad_t = 0, int32_t io_steps = 0) {
   AttnParams p = attn_params(kv, q, out, Hq, t, t_per_seq, window, scale, plan, workspace, batch, queries, pad_t);
+  if (io_steps > 0) p.io_steps = io_steps;
   p.direct = (out != nullptr && plan->num_splits == 1) ? 1 : 0;
   p.k_new = k_new;
   p.v_new = v_new;
@@ -322,9 +325,10 @@ int do_partial(const tempo_kv* kv, const void* q, const void* k_new, const void*
 
 int do_combine(const tempo_kv* kv, void* out, int32_t batch, int32_t Hq, int32_t t,
                const int32_t* t_per_seq, int32_t window, const tempo_plan* plan, void* workspace,
-               hipStream_t stream, int32_t queries = 1, int32_t pad_t = 0) {
+               hipStream_t stream, int32_t queries = 1, int32_t pad_t = 0, int32_t io_steps = 0) {
   AttnParams p = attn_params(kv, nullptr, out, Hq, t, t_per_seq, window, 1.0f, plan, workspace, batch, queries,
                              pad_t);
+  if (io_steps > 0) p.io_steps = io_steps;
   const hipError_t e = launch_combine(p, batch, kv->head_dim, kv->dtype, stream);
   return launch_status(e, "attn_decode_combine");
 }
@@ -616,6 +620,95 @@ int tempo_rope_decode_step_window(const tempo_kv* kv, const tempo_rope* rope, co
   if (window < 1) return TEMPO_ERR_RANGE;
   return decode(kv, q_raw, k_raw, v_new, out, batch, num_q_heads, t, t_per_seq, window, scale, workspace,
                 workspace_bytes, stream, 1, rope);
+}
+
+// Prompt processing: `count` steps per sequence, written and answered in blocks of
+// as many steps as the column tiles hold.
+static int prefill(const tempo_kv* kv, const void* q, const void* k_new, const void* v_new, void* out, int32_t batch,
+            int32_t Hq, int32_t t, int32_t count, int32_t window, float scale, void* workspace,
+            size_t workspace_bytes, void* stream) {
+  int rc = check_store(kv);
+  if (rc != TEMPO_OK) return rc;
+  if (!q || !k_new || !v_new || !out) return TEMPO_ERR_NULL;
+  if ((rc = check_heads(kv, batch, Hq)) != TEMPO_OK) return rc;
+  if (count < 1 || count > (1 << 24)) return TEMPO_ERR_SHAPE;
+  if (t < 0 || window < 0 || t > INT32_MAX - 64 - count) return TEMPO_ERR_RANGE;
+  if ((rc = check_step(kv, t + count - 1)) != TEMPO_OK) return rc;
+  const int G = Hq / kv->num_kv_heads;
+  const int32_t block = kMaxColumns / G;  // steps per block: all four column tiles
+  if ((int64_t)batch * block * Hq * kv->head_dim > INT32_MAX) return TEMPO_ERR_SHAPE;
+  const size_t esz = kv->dtype == TEMPO_BF16 ? 2 : 4;
+  const bool ragged = false;  // every sequence starts at step t
+  const int32_t* t_per_seq = nullptr;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  // validate every block before the first launch, so that an error leaves the store untouched
+  for (int pass = 0; pass < 2; ++pass) {
+    for (int32_t c0 = 0; c0 < count; c0 += block) {
+      const int32_t C = count - c0 < block ? count - c0 : block;
+      tempo_plan plan;
+      make_block_plan(kv, batch, Hq, t + c0, window, ragged, C, &plan);
+      if (pass == 0) {
+        if ((rc = check_attn(kv, batch, Hq, t + c0, window, ragged, &plan, workspace, workspace_bytes, C)) != TEMPO_OK)
+          return rc;
+        if (kv->ring_blocks && (int64_t)C > (int64_t)kv->ring_blocks * kv->block_size) return TEMPO_ERR_RANGE;
+        continue;
+      }
+      const char* kc = static_cast<const char*>(k_new) + (size_t)c0 * kv->num_kv_heads * kv->head_dim * esz;
+      const char* vc = static_cast<const char*>(v_new) + (size_t)c0 * kv->num_kv_heads * kv->head_dim * esz;
+      const char* qc = static_cast<const char*>(q) + (size_t)c0 * Hq * kv->head_dim * esz;
+      char* oc = static_cast<char*>(out) + (size_t)c0 * Hq * kv->head_dim * esz;
+      StoreParams sp = store_params(kv, batch, t + c0, t_per_seq, C);
+      sp.src_steps = count;
+      hipError_t e = launch_append(sp, kc, vc, kv->head_dim, kv->dtype, s);
+      if ((rc = launch_status(e, "kv_append_block")) != TEMPO_OK) return rc;
+      rc = do_partial(kv, qc, nullptr, nullptr, oc, batch, Hq, t + c0, t_per_seq, window, scale, &plan, workspace, s,
+                      C, nullptr, 0, count);
+      if (rc != TEMPO_OK) return rc;
+      if (plan.num_splits > 1) {
+        rc = do_combine(kv, oc, batch, Hq, t + c0, t_per_seq, window, &plan, workspace, s, C, 0, count);
+        if (rc != TEMPO_OK) return rc;
+      }
+    }
+  }
+  return TEMPO_OK;
+}
+
+int tempo_prefill_causal(const tempo_kv* kv, const void* q, const void* k_new, const void* v_new, void* out,
+                         int32_t batch, int32_t num_q_heads, int32_t t, int32_t count, float scale,
+                         void* workspace, size_t workspace_bytes, void* stream) {
+  return prefill(kv, q, k_new, v_new, out, batch, num_q_heads, t, count, 0, scale, workspace, workspace_bytes,
+                 stream);
+}
+
+int tempo_prefill_window(const tempo_kv* kv, const void* q, const void* k_new, const void* v_new, void* out,
+                         int32_t batch, int32_t num_q_heads, int32_t t, int32_t count, int32_t window,
+                         float scale, void* workspace, size_t workspace_bytes, void* stream) {
+  if (window < 1 || window > INT32_MAX - 128) return TEMPO_ERR_RANGE;
+  return prefill(kv, q, k_new, v_new, out, batch, num_q_heads, t, count, window, scale, workspace,
+                 workspace_bytes, stream);
+}
+
+size_t tempo_prefill_workspace_bytes(const tempo_kv* kv, int32_t batch, int32_t num_q_heads, int32_t max_t) {
+  if (check_layout(kv) != TEMPO_OK || check_heads(kv, batch, num_q_heads) != TEMPO_OK) return 0;
+  const int32_t block = kMaxColumns / (num_q_heads / kv->num_kv_heads);
+  return tempo_attn_block_workspace_bytes(kv, batch, num_q_heads, block, max_t);
+}
+
+int tempo_attn_block_with_plan(const tempo_kv* kv, const void* q, void* out, int32_t batch,
+                               int32_t num_q_heads, int32_t queries, int32_t t, const int32_t* t_per_seq,
+                               int32_t window, float scale, const tempo_plan* plan, void* workspace,
+                               size_t workspace_bytes, void* stream) {
+  int rc = check_layout(kv);
+  if (rc != TEMPO_OK) return rc;
+  if (!q || !out || !plan) return TEMPO_ERR_NULL;
+  if ((rc = check_attn(kv, batch, num_q_heads, t, window, t_per_seq != nullptr, plan, workspace, workspace_bytes,
+                       queries)) != TEMPO_OK)
+    return rc;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  rc = do_partial(kv, q, nullptr, nullptr, out, batch, num_q_heads, t, t_per_seq, window, scale, plan, workspace, s,
+                  queries);
+  if (rc != TEMPO_OK || plan->num_splits == 1) return rc;
+  return do_combine(kv, out, batch, num_q_heads, t, t_per_seq, window, plan, workspace, s, queries);
 }
 
 int tempo_attn_block_causal(const tempo_kv* kv, const void* q, void* out, int32_t batch,

@@ -64,6 +64,7 @@ struct StoreParams {
   int32_t Hkv;
   int32_t batch;
   int32_t count;             // append: consecutive steps per sequence, rows [B][count][Hkv][D]
+  int32_t src_steps;         // steps per sequence in the caller's k_new / v_new (>= count; == count normally)
 };
 
 struct AttnParams {
@@ -91,6 +92,8 @@ struct AttnParams {
   int32_t tps_log2;          // log2(tokens per split)
   int32_t num_splits;        // S: stride of the split axis in the workspace
   int32_t queries;           // C: consecutive query steps per sequence (q, out, workspace rows are [B][C][Hq])
+  int32_t io_steps;          // steps per sequence in the caller's q / out ([B][io_steps][Hq][D]); the block is
+                             //   `queries` consecutive ones of them (pointers pre-offset); == queries normally
   int32_t pad_t;             // padded baseline: keys up to pad_t are read and masked; 0 = none
   int32_t direct;            // 1: single split, write `out` and skip the combine
   float scale_log2e;         // s * log2(e)

@@ -148,6 +148,22 @@ class BlockStore:
                                       self._block_ws, nbytes)
         return out
 
+    def prefill_attend(self, q, k_new, v_new, out, t, count, window=0, scale=None):
+        """Write steps t .. t+count-1 and answer all of them in one call
+        (q, out [batch][count][Hq][D]; k_new, v_new [batch][count][Hkv][D])."""
+        ws_t = self.ring_blocks * self.Z + 128 if self.ring_blocks else self.max_t
+        nbytes = T.tempo_prefill_workspace_bytes(self.kv, self.batch, self.Hq, ws_t)
+        if getattr(self, "_prefill_ws", None) is None or self._prefill_ws.numel() < nbytes:
+            self._prefill_ws = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        s = self.scale if scale is None else scale
+        if window:
+            T.tempo_prefill_window(self.kv, q, k_new, v_new, out, self.batch, self.Hq, t, count, window, s,
+                                   self._prefill_ws, nbytes)
+        else:
+            T.tempo_prefill_causal(self.kv, q, k_new, v_new, out, self.batch, self.Hq, t, count, s,
+                                   self._prefill_ws, nbytes)
+        return out
+
     def attend_with_plan(self, q, out, t, plan, window=0, t_per_seq=None, scale=None):
         """Partial + combine with an explicit plan (its own workspace)."""
         nbytes = T.tempo_attn_plan_workspace_bytes(self.kv, self.batch, self.Hq, plan)

@@ -110,6 +110,13 @@ SIGNATURES = {
                                                _vp, ctypes.c_size_t, _vp]),
     "tempo_attn_block_window": (ctypes.c_int, [_kvp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _i32,
                                                ctypes.c_float, _vp, ctypes.c_size_t, _vp]),
+    "tempo_prefill_causal": (ctypes.c_int, [_kvp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, ctypes.c_float, _vp,
+                                            ctypes.c_size_t, _vp]),
+    "tempo_prefill_window": (ctypes.c_int, [_kvp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, ctypes.c_float,
+                                            _vp, ctypes.c_size_t, _vp]),
+    "tempo_prefill_workspace_bytes": (ctypes.c_size_t, [_kvp, _i32, _i32, _i32]),
+    "tempo_attn_block_with_plan": (ctypes.c_int, [_kvp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _i32, ctypes.c_float,
+                                                  _planp, _vp, ctypes.c_size_t, _vp]),
     "tempo_attn_block_plan": (ctypes.c_int, [_kvp, _i32, _i32, _i32, _i32, _i32, _i32, _planp]),
     "tempo_attn_block_workspace_bytes": (ctypes.c_size_t, [_kvp, _i32, _i32, _i32, _i32]),
     "tempo_kv_append_block": (ctypes.c_int, [_kvp, _vp, _vp, _i32, _i32, _vp, _i32, _vp]),
@@ -341,6 +348,32 @@ def tempo_attn_block_window(kv, q, out, batch, num_q_heads, queries, t, t_per_se
     _check(load().tempo_attn_block_window(ctypes.byref(kv), _ptr(q), _ptr(out), batch, num_q_heads, queries,
                                           t, _ptr(t_per_seq), window, scale, _ptr(workspace),
                                           workspace_bytes, _stream(stream)), "tempo_attn_block_window")
+
+
+def tempo_prefill_causal(kv, q, k_new, v_new, out, batch, num_q_heads, t, count, scale, workspace,
+                         workspace_bytes, stream=None):
+    _check(load().tempo_prefill_causal(ctypes.byref(kv), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), batch,
+                                       num_q_heads, t, count, scale, _ptr(workspace), workspace_bytes,
+                                       _stream(stream)), "tempo_prefill_causal")
+
+
+def tempo_prefill_window(kv, q, k_new, v_new, out, batch, num_q_heads, t, count, window, scale, workspace,
+                         workspace_bytes, stream=None):
+    _check(load().tempo_prefill_window(ctypes.byref(kv), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), batch,
+                                       num_q_heads, t, count, window, scale, _ptr(workspace), workspace_bytes,
+                                       _stream(stream)), "tempo_prefill_window")
+
+
+def tempo_prefill_workspace_bytes(kv: tempo_kv, batch: int, num_q_heads: int, max_t: int) -> int:
+    return load().tempo_prefill_workspace_bytes(ctypes.byref(kv), batch, num_q_heads, max_t)
+
+
+def tempo_attn_block_with_plan(kv, q, out, batch, num_q_heads, queries, t, t_per_seq, window, scale, plan,
+                               workspace, workspace_bytes, stream=None):
+    _check(load().tempo_attn_block_with_plan(ctypes.byref(kv), _ptr(q), _ptr(out), batch, num_q_heads, queries,
+                                             t, _ptr(t_per_seq), window, scale, ctypes.byref(plan),
+                                             _ptr(workspace), workspace_bytes, _stream(stream)),
+           "tempo_attn_block_with_plan")
 
 
 def tempo_attn_block_plan(kv: tempo_kv, batch: int, num_q_heads: int, queries: int, t_max: int,

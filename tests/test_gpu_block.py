@@ -216,3 +216,56 @@ def test_llama_shape_block_bf16_full_size(C):
             ref = np.stack([oracle.attend(q64[:, c], K64[:, :t0 + c + 1], V64[:, :t0 + c + 1], t0 + c, window,
                                           1.0 / np.sqrt(D)) for c in range(C)], axis=1)
             assert_close(out, ref, dtype, f"llama block w={window} t0={t0}")
+
+
+# ----------------------------------------------------------------------------
+# Prompt processing in one call: `count` steps written and answered, each step
+# exactly the single-step result; the store ends up as single appends leave it.
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,G,D", [(T.TEMPO_BF16, 3, 128), (T.TEMPO_BF16, 1, 64), (T.TEMPO_BF16, 16, 128),
+                                       (T.TEMPO_F32, 2, 64)])
+@pytest.mark.parametrize("window", [0, 50])
+def test_prefill_every_step(dtype, G, D, window):
+    B, Hkv, Z, steps, first = 2, 2, 32, 300, 37
+    Hq = Hkv * G
+    q, K, V = host_inputs(47, B, steps, Hq, Hkv, D, dtype)
+    table, nb = random_table(47, B, steps // Z + 1)
+    st = BlockStore(B, Hq, Hkv, D, Z, steps - 1, dtype, num_blocks=nb, block_table=table, fill="nan")
+    ref_store = BlockStore(B, Hq, Hkv, D, Z, steps - 1, dtype, num_blocks=nb, block_table=table, fill="nan")
+    Kd, Vd = dev(K, dtype), dev(V, dtype)
+    qd = dev(np.ascontiguousarray(np.transpose(q, (1, 0, 2, 3))), dtype)       # [B][T][Hq][D]
+    # a first call from step 0, a second one that continues the history
+    o1 = torch.empty((B, first, Hq, D), dtype=TDT[dtype], device=DEV)
+    st.prefill_attend(qd[:, :first].contiguous(), Kd[:, :first].contiguous(), Vd[:, :first].contiguous(), o1, 0,
+                      first, window)
+    o2 = torch.empty((B, steps - first, Hq, D), dtype=TDT[dtype], device=DEV)
+    st.prefill_attend(qd[:, first:].contiguous(), Kd[:, first:].contiguous(), Vd[:, first:].contiguous(), o2, first,
+                      steps - first, window)
+    got = np.concatenate([np64(o1), np64(o2)], axis=1)
+    for t in range(steps):
+        ref_store.append(Kd[:, t].contiguous(), Vd[:, t].contiguous(), t)
+    assert torch.equal(st.k_pool.view(torch.uint8), ref_store.k_pool.view(torch.uint8))
+    assert torch.equal(st.v_pool.view(torch.uint8), ref_store.v_pool.view(torch.uint8))
+    K64, V64 = K.astype(np.float64), V.astype(np.float64)
+    for t in range(steps):
+        ref = oracle.attend(q[t].astype(np.float64), K64, V64, t, window, 1.0 / np.sqrt(D))
+        assert_close(got[:, t], ref, dtype, f"prefill step {t} w={window}")
+
+
+def test_llama_shape_prefill_bf16_full_size():
+    B, Hq, Hkv, D, Z, T_len = 16, 24, 8, 128, 256, 4096
+    dtype = T.TEMPO_BF16
+    K, V = flat_kv(48, B, T_len, Hkv, D)
+    table, nb = random_table(48, B, T_len // Z, extra=0)
+    st = BlockStore(B, Hq, Hkv, D, Z, T_len - 1, dtype, num_blocks=nb, block_table=table, fill="nan")
+    q = synth.device_normal((B, T_len, Hq, D), 4800, torch.bfloat16, DEV)
+    out = torch.empty_like(q)
+    st.prefill_attend(q, K, V, out, 0, T_len)
+    kg, vg = st.gather(0, T_len)
+    assert torch.equal(kg, K) and torch.equal(vg, V)
+    K64, V64 = np64(K), np64(V)
+    sample = [0, 1, 20, 21, 22, 41, 42, 63, 1000, 2047, 2048, 2049, 2058, 3000, 4073, 4074, 4094, 4095]
+    sample += [int(x) for x in synth.integers(48, 9, 24, 0, T_len - 1)]
+    for t in sample:
+        ref = oracle.attend(np64(q[:, t]), K64[:, :t + 1], V64[:, :t + 1], t, 0, 1.0 / np.sqrt(D))
+        assert_close(out[:, t], ref, dtype, f"llama prefill step {t}")

@@ -262,6 +262,19 @@ def test_bad_arguments_are_refused_before_any_launch():
     assert lib.tempo_rope_rotate(ctypes.byref(rope_desc(head_dim=7)), fake, fake, T.TEMPO_F32, 2, 6, 5, None, None) == T.TEMPO_ERR_SHAPE
     assert lib.tempo_rope_rotate(ctypes.byref(rope_desc()), fake, fake, T.TEMPO_F32, 2, 6, 100, None, None) == T.TEMPO_ERR_RANGE
 
+    def prefill(kv, t=0, count=10, w=None, k=fake):
+        if w is None:
+            return lib.tempo_prefill_causal(ctypes.byref(kv), fake, k, fake, fake, 2, 6, t, count, 0.1, None, 0, None)
+        return lib.tempo_prefill_window(ctypes.byref(kv), fake, k, fake, fake, 2, 6, t, count, w, 0.1, None, 0, None)
+
+    assert prefill(good) == T.TEMPO_ERR_WORKSPACE                 # everything else is fine
+    assert prefill(good, count=0) == T.TEMPO_ERR_SHAPE
+    assert prefill(good, k=None) == T.TEMPO_ERR_NULL
+    assert prefill(good, t=250, count=7) == T.TEMPO_ERR_RANGE     # last step 256 needs a fifth block
+    assert prefill(good, t=250, count=6) == T.TEMPO_ERR_WORKSPACE
+    assert prefill(good, w=0) == T.TEMPO_ERR_RANGE
+    assert T.tempo_prefill_workspace_bytes(good, 2, 6, 255) >= T.tempo_attn_block_workspace_bytes(good, 2, 6, 21, 255)
+
     bad_plan = T.tempo_plan(48, 1, 1)
     assert lib.tempo_attn_decode_partial(ctypes.byref(good), fake, None, None, 2, 6, 5, None, 0, 0.1,
                                          ctypes.byref(bad_plan), fake << 4, 1 << 30, None) == T.TEMPO_ERR_SHAPE
