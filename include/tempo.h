@@ -347,6 +347,13 @@ int tempo_prefill_window(const tempo_kv* kv, const void* q, const void* k_new, c
                          int32_t window, float scale, void* workspace, size_t workspace_bytes,
                          void* stream);
 
+/* How many launches a tempo_prefill_* call of `count` steps issues at most (host
+ * only; 0 on unsupported arguments): 2 when the prompt's query blocks fill the part
+ * (bf16, linear store: one block-store write, then one launch of the prompt kernel,
+ * in which every workgroup walks the whole key range of its 128 (step, head)
+ * columns through LDS and writes `out` directly), else 3 per block of steps. */
+int tempo_prefill_launches(const tempo_kv* kv, int32_t batch, int32_t num_q_heads, int32_t count);
+
 /* Workspace bound for tempo_prefill_* calls whose last step is at most max_t (host only). */
 size_t tempo_prefill_workspace_bytes(const tempo_kv* kv, int32_t batch, int32_t num_q_heads,
                                      int32_t max_t);

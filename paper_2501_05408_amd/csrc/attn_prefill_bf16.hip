@@ -1,0 +1,173 @@
+// Prompt processing: attention of many consecutive query steps over the tiled
+// keys/values, bf16, MFMA on gfx950.
+//
+// What is computed (Section 2, Eq. 1 for every step t .. t+count-1 of a sequence,
+// with the causal or window pattern; Section 4.3 index masks): exactly what the
+// decode kernel computes for each of those steps, one after the other.  With many
+// steps per key the products dominate the reads: this kernel is bound by the
+// matrix cores and the softmax arithmetic, not by HBM.
+//
+// Mapping.  One workgroup = one (sequence, kv head, block of QB query steps); its
+// columns are the block's (step, head) pairs, 16 per wavefront (column = c*G + g).
+// Every wavefront walks ALL 32-slot groups of the block's key range, so each
+// column's softmax is finished inside one wavefront: no partials, no combine, the
+// output is written directly.  The key/value image of a group (16 KiB at D = 128)
+// is the same for all wavefronts: the workgroup copies it once from the pool into
+// LDS (it is already in MFMA operand order there, 1 KiB units) and every wavefront
+// reads its operands from LDS.  Two LDS buffers: the copy of group n+1 (global
+// loads into registers at the top of the iteration, LDS stores at its end)
+// overlaps the arithmetic on group n; one barrier per group.
+//
+// Workgroups of one (sequence, head) are adjacent in the grid and run together, so
+// the pool is streamed from HBM about once per (sequence, head) and the blocks that
+// follow find it in the caches; the longest blocks are dispatched first.
+#include "attn_bf16_common.h"
+
+namespace tempo {
+namespace {
+
+// Steps per workgroup for a query group of G heads: all `waves` x 16 columns.
+__host__ __device__ inline int prefill_block_steps(int G, int waves) { return (16 * waves) / G; }
+
+template <int D, int NW>
+__global__ __launch_bounds__(64 * NW) void attn_prefill_bf16(AttnParams p) {
+  constexpr int KS = D / 32;
+  constexpr int DT = D / 16;
+  constexpr int UNITS = 2 * KS + DT;          // 1 KiB units of one group: keys then values
+  constexpr int PER_THREAD = UNITS / NW;      // units each wavefront copies per group
+  static_assert(UNITS % NW == 0, "units must divide among the wavefronts");
+  extern __shared__ u32x4 lds[];              // [2][UNITS][64] x 16 bytes
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int QB = prefill_block_steps(p.G, NW);
+  const int nblocks = (p.queries + QB - 1) / QB;
+  const int qb = nblocks - 1 - (int)blockIdx.x;  // longest range first
+  const int hkv = blockIdx.y, b = blockIdx.z;
+  const int c0 = qb * QB;                                           // first step of the block within the call
+  const int C = p.queries - c0 < QB ? p.queries - c0 : QB;         // steps in this block
+  const int ncols = C * p.G;
+  const int t_first = p.t + c0, t_last = t_first + C - 1;
+  const int lo = (p.window > 0 && t_first - p.window + 1 > 0) ? t_first - p.window + 1 : 0;
+  const int g_first = lo >> 5, g_last = t_last >> 5;
+
+  // This wavefront's 16 columns.  Unused columns behave like the block's last step with q = 0.
+  const int col = 16 * wave + (lane & 15);
+  const int cq = col < ncols ? col / p.G : C - 1;
+  const int gq = col < ncols ? col - cq * p.G : 0;
+  const int hi_col = t_first + cq;
+  const int lo_col = (p.window > 0 && hi_col - p.window + 1 > 0) ? hi_col - p.window + 1 : 0;
+  // wavefront-uniform bounds: the groups this wavefront has any work in, and those no column cuts
+  const int first_col = 16 * wave, last_col = (16 * wave + 15) < ncols - 1 ? (16 * wave + 15) : ncols - 1;
+  const bool idle = first_col >= ncols;                             // a wavefront beyond the block's columns
+  const int w_hi = t_first + (idle ? 0 : last_col / p.G);           // newest key any of its columns sees
+  const int w_hi_min = t_first + (idle ? 0 : first_col / p.G);      // newest key ALL of its columns see
+  const int w_lo_first = (p.window > 0 && w_hi_min - p.window + 1 > 0) ? w_hi_min - p.window + 1 : 0;
+  const int w_lo_last = (p.window > 0 && w_hi - p.window + 1 > 0) ? w_hi - p.window + 1 : 0;
+
+  u32x4 qreg[KS];
+  {
+    const int c = lane >> 4;
+    const uint16_t* qp = static_cast<const uint16_t*>(p.q) +
+                         (((int64_t)b * p.io_steps + c0 + cq) * p.Hq + (int64_t)hkv * p.G + gq) * D + 8 * c;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      const u32x4 zero = {0u, 0u, 0u, 0u};
+      const u32x4 v = *reinterpret_cast<const u32x4*>(qp + 32 * s);
+      qreg[s] = col < ncols ? v : zero;
+    }
+  }
+
+  WaveState<D> st;
+  st.m = -INFINITY;
+  st.l = 0.f;
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) st.acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // Copy of one group: wavefront w moves units w, w + NW, ... (keys are units
+  // 0 .. 2KS-1 of the key pool's group, values units 2KS .. of the value pool's).
+  u32x4 stage[PER_THREAD];
+  auto fetch = [&](int grp) {
+    const int64_t base = group_base<D>(p, b, hkv, grp);
+    const u32x4* kp = reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(p.k_pool) + base) + lane;
+    const u32x4* vp = reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(p.v_pool) + base) + lane;
+#pragma unroll
+    for (int i = 0; i < PER_THREAD; ++i) {
+      const int u = wave + NW * i;  // wave-uniform
+      stage[i] = u < 2 * KS ? kp[u * 64] : vp[(u - 2 * KS) * 64];
+    }
+  };
+  auto stash = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < PER_THREAD; ++i) lds[(buf * UNITS + wave + NW * i) * 64 + lane] = stage[i];
+  };
+
+  fetch(g_first);
+  stash(0);
+  __syncthreads();
+
+  for (int grp = g_first; grp <= g_last; ++grp) {
+    const int buf = (grp - g_first) & 1;
+    const bool more = grp < g_last;  // uniform over the workgroup
+    if (more) fetch(grp + 1);
+
+    // Has this wavefront anything to do in this group?  (Uniform over the wavefront.)
+    const int j0 = grp << 5;
+    if (!idle && j0 <= w_hi && j0 + 31 >= (p.window > 0 ? w_lo_first : 0)) {
+      Group<D> g;
+      const u32x4* src = lds + buf * UNITS * 64 + lane;
+#pragma unroll
+      for (int i = 0; i < 2 * KS; ++i) g.k[i] = src[i * 64];
+      float x[8];
+      logits_of_group<D>(p, qreg, g, x);
+      const bool cut = j0 < w_lo_last || j0 + 31 > w_hi_min;
+      if (cut) mask_logits(grp, lo_col, hi_col, lane, x);
+      const bf16x8 pa = softmax_update<D>(x, lane, st);
+      uint32_t keep[4] = {~0u, ~0u, ~0u, ~0u};
+      if (cut) value_masks(grp, lo, t_last, lane, keep);  // slots beyond the block's last step may be unwritten
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) {
+        u32x4 vv = src[(2 * KS + dt) * 64];
+        vv.x &= keep[0]; vv.y &= keep[1]; vv.z &= keep[2]; vv.w &= keep[3];
+        st.acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, as_bf16x8(vv), st.acc[dt], 0, 0, 0);
+      }
+    }
+
+    if (more) stash(buf ^ 1);  // nobody reads that buffer in this iteration
+    __syncthreads();           // group n+1 is in LDS; group n's buffer may be overwritten next time
+  }
+
+  // Every column saw its own key, so l > 0.  Columns (4c + r) of acc, value dims 16dt + n.
+  float l_tot = st.l + __shfl_xor(st.l, 16);
+  l_tot += __shfl_xor(l_tot, 32);
+  const int n = lane & 15, c = lane >> 4;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int j = 16 * wave + 4 * c + r;
+    const float l_j = __shfl(l_tot, 4 * c + r);
+    if (j < ncols) {
+      const int jc = j / p.G, jg = j - jc * p.G;
+      __bf16* orow = static_cast<__bf16*>(p.out) +
+                     (((int64_t)b * p.io_steps + c0 + jc) * p.Hq + (int64_t)hkv * p.G + jg) * D;
+      const float inv = 1.0f / l_j;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) orow[16 * dt + n] = (__bf16)(st.acc[dt][r] * inv);
+    }
+  }
+}
+
+}  // namespace
+
+int prefill_bf16_block_steps(int G) { return prefill_block_steps(G, 8); }
+
+hipError_t launch_prefill_bf16(const AttnParams& p, int batch, int D, hipStream_t stream) {
+  constexpr int NW = 8;
+  const int QB = prefill_block_steps(p.G, NW);
+  const int nblocks = (p.queries + QB - 1) / QB;
+  const dim3 grid(nblocks, p.Hkv, batch);
+  const dim3 block(64 * NW);
+  const size_t lds = 2 * (size_t)(2 * (D / 32) + D / 16) * 1024;
+  if (D == 128) return launch((attn_prefill_bf16<128, NW>), grid, block, lds, stream, p);
+  return launch((attn_prefill_bf16<64, NW>), grid, block, lds, stream, p);
+}
+
+}  // namespace tempo

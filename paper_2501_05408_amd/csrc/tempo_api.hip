@@ -622,6 +622,16 @@ int tempo_rope_decode_step_window(const tempo_kv* kv, const tempo_rope* rope, co
                 workspace_bytes, stream, 1, rope);
 }
 
+// Does a prompt of `count` steps go through the prompt kernel (one launch after the
+// block-store write) rather than block by block?  It does when its query blocks fill
+// the part; a ring store and fp32 always go block by block.
+bool prefill_in_one_launch(const tempo_kv* kv, int32_t batch, int32_t Hq, int32_t count) {
+  if (kv->dtype != TEMPO_BF16 || kv->ring_blocks != 0) return false;
+  if ((int64_t)batch * count * kv->num_kv_heads * kv->head_dim > INT32_MAX) return false;
+  const int32_t qb = prefill_bf16_block_steps(Hq / kv->num_kv_heads);
+  return (int64_t)((count + qb - 1) / qb) * kv->num_kv_heads * batch >= kComputeUnits;
+}
+
 // Prompt processing: `count` steps per sequence, written and answered in blocks of
 // as many steps as the column tiles hold.
 static int prefill(const tempo_kv* kv, const void* q, const void* k_new, const void* v_new, void* out, int32_t batch,
@@ -642,32 +652,46 @@ static int prefill(const tempo_kv* kv, const void* q, const void* k_new, const v
   const int32_t* t_per_seq = nullptr;
   hipStream_t s = static_cast<hipStream_t>(stream);
   // validate every block before the first launch, so that an error leaves the store untouched
-  for (int pass = 0; pass < 2; ++pass) {
-    for (int32_t c0 = 0; c0 < count; c0 += block) {
-      const int32_t C = count - c0 < block ? count - c0 : block;
-      tempo_plan plan;
-      make_block_plan(kv, batch, Hq, t + c0, window, ragged, C, &plan);
-      if (pass == 0) {
-        if ((rc = check_attn(kv, batch, Hq, t + c0, window, ragged, &plan, workspace, workspace_bytes, C)) != TEMPO_OK)
-          return rc;
-        if (kv->ring_blocks && (int64_t)C > (int64_t)kv->ring_blocks * kv->block_size) return TEMPO_ERR_RANGE;
-        continue;
-      }
-      const char* kc = static_cast<const char*>(k_new) + (size_t)c0 * kv->num_kv_heads * kv->head_dim * esz;
-      const char* vc = static_cast<const char*>(v_new) + (size_t)c0 * kv->num_kv_heads * kv->head_dim * esz;
-      const char* qc = static_cast<const char*>(q) + (size_t)c0 * Hq * kv->head_dim * esz;
-      char* oc = static_cast<char*>(out) + (size_t)c0 * Hq * kv->head_dim * esz;
-      StoreParams sp = store_params(kv, batch, t + c0, t_per_seq, C);
-      sp.src_steps = count;
-      hipError_t e = launch_append(sp, kc, vc, kv->head_dim, kv->dtype, s);
-      if ((rc = launch_status(e, "kv_append_block")) != TEMPO_OK) return rc;
-      rc = do_partial(kv, qc, nullptr, nullptr, oc, batch, Hq, t + c0, t_per_seq, window, scale, &plan, workspace, s,
-                      C, nullptr, 0, count);
+  for (int32_t c0 = 0; c0 < count; c0 += block) {
+    const int32_t C = count - c0 < block ? count - c0 : block;
+    tempo_plan plan;
+    make_block_plan(kv, batch, Hq, t + c0, window, ragged, C, &plan);
+    if ((rc = check_attn(kv, batch, Hq, t + c0, window, ragged, &plan, workspace, workspace_bytes, C)) != TEMPO_OK)
+      return rc;
+    if (kv->ring_blocks && (int64_t)C > (int64_t)kv->ring_blocks * kv->block_size) return TEMPO_ERR_RANGE;
+  }
+
+  // Enough query blocks to fill the part: write the whole prompt, then one launch of
+  // the prompt kernel (each workgroup walks its block's whole key range; no partials).
+  if (prefill_in_one_launch(kv, batch, Hq, count)) {
+    const StoreParams sp = store_params(kv, batch, t, nullptr, count);
+    if ((rc = launch_status(launch_append(sp, k_new, v_new, kv->head_dim, kv->dtype, s), "kv_append_block")) != TEMPO_OK)
+      return rc;
+    const tempo_plan unused = {32, 1, 1};
+    AttnParams p = attn_params(kv, q, out, Hq, t, nullptr, window, scale, &unused, workspace, batch, count);
+    return launch_status(launch_prefill_bf16(p, batch, kv->head_dim, s), "attn_prefill");
+  }
+
+  // Otherwise block by block: split-KV partial attention keeps the part busy when the
+  // blocks are few and the history is long.
+  for (int32_t c0 = 0; c0 < count; c0 += block) {
+    const int32_t C = count - c0 < block ? count - c0 : block;
+    tempo_plan plan;
+    make_block_plan(kv, batch, Hq, t + c0, window, ragged, C, &plan);
+    const char* kc = static_cast<const char*>(k_new) + (size_t)c0 * kv->num_kv_heads * kv->head_dim * esz;
+    const char* vc = static_cast<const char*>(v_new) + (size_t)c0 * kv->num_kv_heads * kv->head_dim * esz;
+    const char* qc = static_cast<const char*>(q) + (size_t)c0 * Hq * kv->head_dim * esz;
+    char* oc = static_cast<char*>(out) + (size_t)c0 * Hq * kv->head_dim * esz;
+    StoreParams sp = store_params(kv, batch, t + c0, t_per_seq, C);
+    sp.src_steps = count;
+    hipError_t e = launch_append(sp, kc, vc, kv->head_dim, kv->dtype, s);
+    if ((rc = launch_status(e, "kv_append_block")) != TEMPO_OK) return rc;
+    rc = do_partial(kv, qc, nullptr, nullptr, oc, batch, Hq, t + c0, t_per_seq, window, scale, &plan, workspace, s,
+                    C, nullptr, 0, count);
+    if (rc != TEMPO_OK) return rc;
+    if (plan.num_splits > 1) {
+      rc = do_combine(kv, oc, batch, Hq, t + c0, t_per_seq, window, &plan, workspace, s, C, 0, count);
       if (rc != TEMPO_OK) return rc;
-      if (plan.num_splits > 1) {
-        rc = do_combine(kv, oc, batch, Hq, t + c0, t_per_seq, window, &plan, workspace, s, C, 0, count);
-        if (rc != TEMPO_OK) return rc;
-      }
     }
   }
   return TEMPO_OK;
@@ -686,6 +710,13 @@ int tempo_prefill_window(const tempo_kv* kv, const void* q, const void* k_new, c
   if (window < 1 || window > INT32_MAX - 128) return TEMPO_ERR_RANGE;
   return prefill(kv, q, k_new, v_new, out, batch, num_q_heads, t, count, window, scale, workspace,
                  workspace_bytes, stream);
+}
+
+int tempo_prefill_launches(const tempo_kv* kv, int32_t batch, int32_t num_q_heads, int32_t count) {
+  if (check_layout(kv) != TEMPO_OK || check_heads(kv, batch, num_q_heads) != TEMPO_OK || count < 1) return 0;
+  if (prefill_in_one_launch(kv, batch, num_q_heads, count)) return 2;
+  const int32_t block = kMaxColumns / (num_q_heads / kv->num_kv_heads);
+  return 3 * ((count + block - 1) / block);
 }
 
 size_t tempo_prefill_workspace_bytes(const tempo_kv* kv, int32_t batch, int32_t num_q_heads, int32_t max_t) {

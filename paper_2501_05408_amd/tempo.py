@@ -114,6 +114,7 @@ SIGNATURES = {
                                             ctypes.c_size_t, _vp]),
     "tempo_prefill_window": (ctypes.c_int, [_kvp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, ctypes.c_float,
                                             _vp, ctypes.c_size_t, _vp]),
+    "tempo_prefill_launches": (ctypes.c_int, [_kvp, _i32, _i32, _i32]),
     "tempo_prefill_workspace_bytes": (ctypes.c_size_t, [_kvp, _i32, _i32, _i32]),
     "tempo_attn_block_with_plan": (ctypes.c_int, [_kvp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _i32, ctypes.c_float,
                                                   _planp, _vp, ctypes.c_size_t, _vp]),
@@ -362,6 +363,10 @@ def tempo_prefill_window(kv, q, k_new, v_new, out, batch, num_q_heads, t, count,
     _check(load().tempo_prefill_window(ctypes.byref(kv), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), batch,
                                        num_q_heads, t, count, window, scale, _ptr(workspace), workspace_bytes,
                                        _stream(stream)), "tempo_prefill_window")
+
+
+def tempo_prefill_launches(kv: tempo_kv, batch: int, num_q_heads: int, count: int) -> int:
+    return load().tempo_prefill_launches(ctypes.byref(kv), batch, num_q_heads, count)
 
 
 def tempo_prefill_workspace_bytes(kv: tempo_kv, batch: int, num_q_heads: int, max_t: int) -> int:

@@ -252,6 +252,39 @@ def test_prefill_every_step(dtype, G, D, window):
         assert_close(got[:, t], ref, dtype, f"prefill step {t} w={window}")
 
 
+# ----------------------------------------------------------------------------
+# The prompt kernel (enough query blocks to fill the part: one launch after the
+# block-store write), every step against the oracle: group sizes, head dims,
+# windows, a call that continues a history, NaN beyond the prompt.
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("G,D,Hkv", [(3, 128, 4), (1, 64, 8), (16, 128, 2), (5, 64, 4)])
+@pytest.mark.parametrize("window", [0, 1, 45, 200])
+def test_prompt_kernel_every_step(G, D, Hkv, window):
+    B, Z, steps, first = 16, 32, 330, 29
+    Hq = Hkv * G
+    dtype = T.TEMPO_BF16
+    q, K, V = host_inputs(49, B, steps, Hq, Hkv, D, dtype)
+    table, nb = random_table(49, B, steps // Z + 2)
+    st = BlockStore(B, Hq, Hkv, D, Z, steps + Z - 1, dtype, num_blocks=nb, block_table=table, fill="nan")
+    Kd, Vd = dev(K, dtype), dev(V, dtype)
+    qd = dev(np.ascontiguousarray(np.transpose(q, (1, 0, 2, 3))), dtype)
+    assert T.tempo_prefill_launches(st.kv, B, Hq, first) > 2          # a short first call goes block by block
+    assert T.tempo_prefill_launches(st.kv, B, Hq, steps - first) == 2  # the rest is one launch of the prompt kernel
+    o1 = torch.empty((B, first, Hq, D), dtype=torch.bfloat16, device=DEV)
+    st.prefill_attend(qd[:, :first].contiguous(), Kd[:, :first].contiguous(), Vd[:, :first].contiguous(), o1, 0,
+                      first, window)
+    o2 = torch.empty((B, steps - first, Hq, D), dtype=torch.bfloat16, device=DEV)
+    st.prefill_attend(qd[:, first:].contiguous(), Kd[:, first:].contiguous(), Vd[:, first:].contiguous(), o2, first,
+                      steps - first, window)
+    got = np.concatenate([np64(o1), np64(o2)], axis=1)
+    kg, vg = st.gather(0, steps)
+    assert torch.equal(kg, Kd) and torch.equal(vg, Vd)
+    K64, V64 = K.astype(np.float64), V.astype(np.float64)
+    for t in range(steps):
+        ref = oracle.attend(q[t].astype(np.float64), K64, V64, t, window, 1.0 / np.sqrt(D))
+        assert_close(got[:, t], ref, dtype, f"prompt kernel step {t} G={G} w={window}")
+
+
 def test_llama_shape_prefill_bf16_full_size():
     B, Hq, Hkv, D, Z, T_len = 16, 24, 8, 128, 256, 4096
     dtype = T.TEMPO_BF16
@@ -260,6 +293,7 @@ def test_llama_shape_prefill_bf16_full_size():
     st = BlockStore(B, Hq, Hkv, D, Z, T_len - 1, dtype, num_blocks=nb, block_table=table, fill="nan")
     q = synth.device_normal((B, T_len, Hq, D), 4800, torch.bfloat16, DEV)
     out = torch.empty_like(q)
+    assert T.tempo_prefill_launches(st.kv, B, Hq, T_len) == 2
     st.prefill_attend(q, K, V, out, 0, T_len)
     kg, vg = st.gather(0, T_len)
     assert torch.equal(kg, K) and torch.equal(vg, V)
