@@ -26,6 +26,39 @@
 namespace tempo {
 namespace {
 
+// Online-softmax step of one group for this kernel: new running max, bf16 weights,
+// and the rescale of the accumulators.  The running sum is not kept here: it is
+// one more accumulator tile (weights times a column of ones), so the matrix cores
+// add up the rounded weights and the rescale below covers it.
+template <int D>
+__device__ inline bf16x8 prompt_softmax(const float* x, int lane, float& m, f32x4* acc, f32x4& acc_l) {
+  constexpr int DT = D / 16;
+  const int c = lane >> 4;
+  float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+  mx = fmaxf(mx, __shfl_xor(mx, 16));
+  mx = fmaxf(mx, __shfl_xor(mx, 32));
+  const float m_new = fmaxf(m, mx);
+  const float m_ref = m_new == -INFINITY ? 0.f : m_new;  // a column that has seen no key yet
+  const float alpha = fast_exp2(m - m_ref);
+  bf16x8 pa;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) pa[i] = (__bf16)fast_exp2(x[i] - m_ref);
+  m = m_new;
+  if (__any(alpha != 1.0f)) {
+    float a[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) a[r] = __shfl(alpha, 4 * c + r);
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) acc[dt][r] *= a[r];
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) acc_l[r] *= a[r];
+  }
+  return pa;
+}
+
 // Steps per workgroup for a query group of G heads: all `waves` x 16 columns.
 __host__ __device__ inline int prefill_block_steps(int G, int waves) { return (16 * waves) / G; }
 
@@ -77,11 +110,12 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_bf16(AttnParams p) {
     }
   }
 
-  WaveState<D> st;
-  st.m = -INFINITY;
-  st.l = 0.f;
+  float m_run = -INFINITY;                     // running max of column lane&15 (log2 units)
+  f32x4 acc[DT];                               // lane (n + 16c): dims 16dt + n of columns 4c .. 4c+3
+  f32x4 acc_l = {0.f, 0.f, 0.f, 0.f};          // running sums of columns 4c .. 4c+3 (the same in every n)
 #pragma unroll
-  for (int dt = 0; dt < DT; ++dt) st.acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int dt = 0; dt < DT; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const u32x4 ones = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};  // bf16 1.0 x 8
 
   // Copy of one group: wavefront w moves units w, w + NW, ... (keys are units
   // 0 .. 2KS-1 of the key pool's group, values units 2KS .. of the value pool's).
@@ -121,14 +155,15 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_bf16(AttnParams p) {
       logits_of_group<D>(p, qreg, g, x);
       const bool cut = j0 < w_lo_last || j0 + 31 > w_hi_min;
       if (cut) mask_logits(grp, lo_col, hi_col, lane, x);
-      const bf16x8 pa = softmax_update<D>(x, lane, st);
+      const bf16x8 pa = prompt_softmax<D>(x, lane, m_run, acc, acc_l);
+      acc_l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, as_bf16x8(ones), acc_l, 0, 0, 0);
       uint32_t keep[4] = {~0u, ~0u, ~0u, ~0u};
       if (cut) value_masks(grp, lo, t_last, lane, keep);  // slots beyond the block's last step may be unwritten
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) {
         u32x4 vv = src[(2 * KS + dt) * 64];
         vv.x &= keep[0]; vv.y &= keep[1]; vv.z &= keep[2]; vv.w &= keep[3];
-        st.acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, as_bf16x8(vv), st.acc[dt], 0, 0, 0);
+        acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, as_bf16x8(vv), acc[dt], 0, 0, 0);
       }
     }
 
@@ -136,21 +171,19 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_bf16(AttnParams p) {
     __syncthreads();           // group n+1 is in LDS; group n's buffer may be overwritten next time
   }
 
-  // Every column saw its own key, so l > 0.  Columns (4c + r) of acc, value dims 16dt + n.
-  float l_tot = st.l + __shfl_xor(st.l, 16);
-  l_tot += __shfl_xor(l_tot, 32);
+  // Every column saw its own key, so its sum is > 0.  Columns (4c + r) of acc, value dims 16dt + n.
   const int n = lane & 15, c = lane >> 4;
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
     const int j = 16 * wave + 4 * c + r;
-    const float l_j = __shfl(l_tot, 4 * c + r);
+    const float l_j = acc_l[r];
     if (j < ncols) {
       const int jc = j / p.G, jg = j - jc * p.G;
       __bf16* orow = static_cast<__bf16*>(p.out) +
                      (((int64_t)b * p.io_steps + c0 + jc) * p.Hq + (int64_t)hkv * p.G + jg) * D;
       const float inv = 1.0f / l_j;
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt) orow[16 * dt + n] = (__bf16)(st.acc[dt][r] * inv);
+      for (int dt = 0; dt < DT; ++dt) orow[16 * dt + n] = (__bf16)(acc[dt][r] * inv);
     }
   }
 }
