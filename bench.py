@@ -118,9 +118,14 @@ def other_workloads(torch, T, BlockStore, synth, dev, kv_bytes_per_token):
     op = torch.empty_like(qp)
     dt = _timed(torch, lambda i: sts[i % 8].prefill_attend(qp, kp, vp, op, 0, P), 5, 1)
     pairs = P * (P + 1) // 2                                             # (query, key) pairs per sequence
+    tflops = 16 * pairs * 4 * D * Hq / dt / 1e12
     out["prompt_b16_t4096"] = {"ms": round(dt * 1e3, 3), "tokens_per_s": round(16 * P / dt, 1),
-                               "tflops": round(16 * pairs * 4 * D * Hq / dt / 1e12, 1),
-                               "note": "one call; flops = 4*D*Hq per (query, key) pair"}
+                               "tflops": round(tflops, 1),
+                               "roofline": {"kernel": "attn_prefill_bf16<128, 8>", "bound": "mfma",
+                                            "achieved": round(tflops, 1), "peak": 2500.0, "unit": "TFLOP/s",
+                                            "frac": round(tflops / 2500.0, 4)},
+                               "note": "one tempo_prefill_causal call (block-store write + prompt kernel); "
+                                       "algorithmic flops = 4*D*Hq per visible (query, key) pair, whole call timed"}
     del qp, kp, vp, op
     del sts
     torch.cuda.empty_cache()
@@ -233,6 +238,23 @@ def other_workloads(torch, T, BlockStore, synth, dev, kv_bytes_per_token):
     return out
 
 
+def prompt_only(torch, T, BlockStore, synth, dev, repeats):
+    """The prompt-processing workload alone (for profiling its kernel): 4096 steps x 16
+    sequences of the headline shape through one tempo_prefill_causal call, `repeats` times."""
+    B, Hq, Hkv, D, Z, P = 16, 24, 8, 128, 256, 4096
+    st = BlockStore(B, Hq, Hkv, D, Z, P - 1, T.TEMPO_BF16, device=dev)
+    q = synth.device_normal((B, P, Hq, D), 277, torch.bfloat16, dev)
+    k = synth.device_normal((B, P, Hkv, D), 278, torch.bfloat16, dev)
+    v = synth.device_normal((B, P, Hkv, D), 279, torch.bfloat16, dev)
+    o = torch.empty_like(q)
+    dt = _timed(torch, lambda i: st.prefill_attend(q, k, v, o, 0, P), repeats, 2)
+    flops = B * (P * (P + 1) // 2) * 4 * D * Hq
+    return {"workload": "prompt of 4096 steps x 16 sequences, llama-3.2-3b attention shape, one tempo_prefill_causal call",
+            "ms": round(dt * 1e3, 3), "tokens_per_s": round(B * P / dt, 1), "algorithmic_flops_per_call": flops,
+            "roofline": {"kernel": "attn_prefill_bf16<128, 8>", "bound": "mfma", "achieved": round(flops / dt / 1e12, 1),
+                         "peak": 2500.0, "unit": "TFLOP/s", "frac": round(flops / dt / 1e12 / 2500.0, 4)}}
+
+
 def tile_sweep(torch, T, BlockStore, synth, dev):
     """Tile-size sweep and padded baseline at T = 16384 (the shape of the paper's block-size
     figure, Section 7.2): for batch 4 and 16 and tile sizes Z = 32 .. 8192, the mean time of a
@@ -284,6 +306,9 @@ def main() -> int:
                     help="short run to put under rocprofv3 --pmc: pools filled directly with N(0,1), "
                          "W+K decode steps, then 4 copy launches of 256 MiB (the known-size kernel the "
                          "traffic counters are scaled by); no timing, no oracle")
+    ap.add_argument("--prompt-only", action="store_true",
+                    help="instead of the headline run: the prompt-processing workload alone, --steps times "
+                         "(use a small --steps), printed as one JSON line")
     ap.add_argument("--tile-sweep", action="store_true",
                     help="instead of the headline run: tile-size sweep and padded baseline at T=16384, "
                          "printed as one JSON line")
@@ -306,6 +331,9 @@ def main() -> int:
     T.load()
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.prompt_only:
+        print(json.dumps({"prompt_processing": prompt_only(torch, T, BlockStore, synth, dev, min(args.steps, 50))}))
+        return 0
     if args.tile_sweep:
         print(json.dumps({"tile_size_sweep": tile_sweep(torch, T, BlockStore, synth, dev)}))
         return 0
@@ -453,7 +481,7 @@ def main() -> int:
                            "launches": "tempo_kv_append + tempo_attn_decode_causal"},
         "steps_per_s": round(args.steps / elapsed, 1),
         "roofline": {
-            "kernel": "attn_partial_bf16<128>",
+            "kernel": "attn_partial_bf16<128, false, 1>",
             "bound": "hbm",
             "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBS,

@@ -26,25 +26,41 @@
 namespace tempo {
 namespace {
 
-// Online-softmax step of one group for this kernel: new running max, bf16 weights,
-// and the rescale of the accumulators.  The running sum is not kept here: it is
-// one more accumulator tile (weights times a column of ones), so the matrix cores
-// add up the rounded weights and the rescale below covers it.
+// Maximum over the four lanes {l, l^16, l^32, l^48} that hold one column's logits,
+// left in all four.  Two lane-swap instructions of gfx950 instead of two trips
+// through the LDS permute unit: v_permlane16_swap exchanges the odd 16-lane rows of
+// its first operand with the even rows of its second, v_permlane32_swap the upper
+// half of the first with the lower half of the second; with both operands holding
+// the same values, the maximum of the two results is the exchange-and-reduce step.
+__device__ inline float column_max(float v) {
+  float a = v, b = v;
+  asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 0\n\tv_max_f32 %0, %0, %1" : "+v"(a), "+v"(b));
+  float c = a, d = a;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 0\n\tv_max_f32 %0, %0, %1" : "+v"(c), "+v"(d));
+  return c;
+}
+
+// Online softmax of one group for this kernel, with a LAZY reference: weights are
+// 2^(x - ref) where ref follows the running maximum only when the maximum has
+// grown by more than kSlack (in log2 units) since ref was set, so weights stay
+// below 2^kSlack (exact in fp32 sums, same relative rounding in bf16) and the
+// accumulators are rescaled a few times per column instead of at every new
+// maximum.  The result acc / sum does not depend on ref.  The running sum is one
+// more accumulator tile (weights times a column of ones on the matrix cores).
+constexpr float kSlack = 8.0f;
+
 template <int D>
-__device__ inline bf16x8 prompt_softmax(const float* x, int lane, float& m, f32x4* acc, f32x4& acc_l) {
+__device__ inline bf16x8 prompt_softmax(const float* x, int lane, float& ref, f32x4* acc, f32x4& acc_l) {
   constexpr int DT = D / 16;
   const int c = lane >> 4;
   float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-  mx = fmaxf(mx, __shfl_xor(mx, 16));
-  mx = fmaxf(mx, __shfl_xor(mx, 32));
-  const float m_new = fmaxf(m, mx);
-  const float m_ref = m_new == -INFINITY ? 0.f : m_new;  // a column that has seen no key yet
-  const float alpha = fast_exp2(m - m_ref);
-  bf16x8 pa;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) pa[i] = (__bf16)fast_exp2(x[i] - m_ref);
-  m = m_new;
-  if (__any(alpha != 1.0f)) {
+  mx = column_max(mx);
+  // ref = -inf until the column sees its first key; -inf + kSlack = -inf, so any finite mx moves it
+  const bool move = mx > ref + kSlack;
+  if (__any(move)) {
+    const float ref_new = move ? mx : ref;
+    const float alpha = move ? fast_exp2(ref - ref_new) : 1.0f;  // exp2(-inf) = 0 on the first key
+    ref = ref_new;
     float a[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) a[r] = __shfl(alpha, 4 * c + r);
@@ -56,6 +72,10 @@ __device__ inline bf16x8 prompt_softmax(const float* x, int lane, float& m, f32x
 #pragma unroll
     for (int r = 0; r < 4; ++r) acc_l[r] *= a[r];
   }
+  const float base = ref == -INFINITY ? 0.f : ref;  // a column that has seen no key yet: weights exp2(-inf) = 0
+  bf16x8 pa;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) pa[i] = (__bf16)fast_exp2(x[i] - base);
   return pa;
 }
 
@@ -110,7 +130,7 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_bf16(AttnParams p) {
     }
   }
 
-  float m_run = -INFINITY;                     // running max of column lane&15 (log2 units)
+  float m_run = -INFINITY;                     // softmax reference of column lane&15 (log2 units)
   f32x4 acc[DT];                               // lane (n + 16c): dims 16dt + n of columns 4c .. 4c+3
   f32x4 acc_l = {0.f, 0.f, 0.f, 0.f};          // running sums of columns 4c .. 4c+3 (the same in every n)
 #pragma unroll
