@@ -150,13 +150,24 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_bf16(AttnParams p) {
       stage[i] = u < 2 * KS ? kp[u * 64] : vp[(u - 2 * KS) * 64];
     }
   };
-  auto stash = [&](int buf) {
+  // Slots beyond the block's last step may be unwritten (NaN): the 0 mask under the
+  // sums is applied once, to the value units of the range's last group, on their way
+  // into LDS (the copy keeps the lane of every 16-byte piece, so the lane's slots are
+  // the consumer's).  Masked slots inside the range hold written data and weight 0.
+  auto stash = [&](int buf, int grp) {
+    uint32_t keep[4] = {~0u, ~0u, ~0u, ~0u};
+    if ((grp << 5) + 31 > t_last) value_masks(grp, 0, t_last, lane, keep);  // uniform over the workgroup
 #pragma unroll
-    for (int i = 0; i < PER_THREAD; ++i) lds[(buf * UNITS + wave + NW * i) * 64 + lane] = stage[i];
+    for (int i = 0; i < PER_THREAD; ++i) {
+      const int u = wave + NW * i;
+      u32x4 v = stage[i];
+      if (u >= 2 * KS) { v.x &= keep[0]; v.y &= keep[1]; v.z &= keep[2]; v.w &= keep[3]; }
+      lds[(buf * UNITS + u) * 64 + lane] = v;
+    }
   };
 
   fetch(g_first);
-  stash(0);
+  stash(0, g_first);
   __syncthreads();
 
   for (int grp = g_first; grp <= g_last; ++grp) {
@@ -177,17 +188,12 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_bf16(AttnParams p) {
       if (cut) mask_logits(grp, lo_col, hi_col, lane, x);
       const bf16x8 pa = prompt_softmax<D>(x, lane, m_run, acc, acc_l);
       acc_l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, as_bf16x8(ones), acc_l, 0, 0, 0);
-      uint32_t keep[4] = {~0u, ~0u, ~0u, ~0u};
-      if (cut) value_masks(grp, lo, t_last, lane, keep);  // slots beyond the block's last step may be unwritten
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt) {
-        u32x4 vv = src[(2 * KS + dt) * 64];
-        vv.x &= keep[0]; vv.y &= keep[1]; vv.z &= keep[2]; vv.w &= keep[3];
-        acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, as_bf16x8(vv), acc[dt], 0, 0, 0);
-      }
+      for (int dt = 0; dt < DT; ++dt)
+        acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, as_bf16x8(src[(2 * KS + dt) * 64]), acc[dt], 0, 0, 0);
     }
 
-    if (more) stash(buf ^ 1);  // nobody reads that buffer in this iteration
+    if (more) stash(buf ^ 1, grp + 1);  // nobody reads that buffer in this iteration
     __syncthreads();           // group n+1 is in LDS; group n's buffer may be overwritten next time
   }
 
