@@ -49,12 +49,15 @@ __device__ inline float column_max(float v) {
 // more accumulator tile (weights times a column of ones on the matrix cores).
 constexpr float kSlack = 8.0f;
 
+// x holds the RAW dot products (masked ones are -inf); `scale` > 0 is s * log2(e),
+// applied to the maximum once and to the weights inside one fused multiply-add.
 template <int D>
-__device__ inline bf16x8 prompt_softmax(const float* x, int lane, float& ref, f32x4* acc, f32x4& acc_l) {
+__device__ inline bf16x8 prompt_softmax(const float* x, float scale, int lane, float& ref, f32x4* acc,
+                                        f32x4& acc_l) {
   constexpr int DT = D / 16;
   const int c = lane >> 4;
   float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-  mx = column_max(mx);
+  mx = column_max(mx) * scale;
   // ref = -inf until the column sees its first key; -inf + kSlack = -inf, so any finite mx moves it
   const bool move = mx > ref + kSlack;
   if (__any(move)) {
@@ -75,7 +78,7 @@ __device__ inline bf16x8 prompt_softmax(const float* x, int lane, float& ref, f3
   const float base = ref == -INFINITY ? 0.f : ref;  // a column that has seen no key yet: weights exp2(-inf) = 0
   bf16x8 pa;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) pa[i] = (__bf16)fast_exp2(x[i] - base);
+  for (int i = 0; i < 8; ++i) pa[i] = (__bf16)fast_exp2(fmaf(x[i], scale, -base));
   return pa;
 }
 
@@ -182,11 +185,20 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_bf16(AttnParams p) {
       const u32x4* src = lds + buf * UNITS * 64 + lane;
 #pragma unroll
       for (int i = 0; i < 2 * KS; ++i) g.k[i] = src[i * 64];
-      float x[8];
-      logits_of_group<D>(p, qreg, g, x);
+      float x[8];  // raw dot products of the two row tiles
+      {
+        f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+          sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(g.k[s]), as_bf16x8(qreg[s]), sa, 0, 0, 0);
+          sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(g.k[KS + s]), as_bf16x8(qreg[s]), sb, 0, 0, 0);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) { x[r] = sa[r]; x[4 + r] = sb[r]; }
+      }
       const bool cut = j0 < w_lo_last || j0 + 31 > w_hi_min;
       if (cut) mask_logits(grp, lo_col, hi_col, lane, x);
-      const bf16x8 pa = prompt_softmax<D>(x, lane, m_run, acc, acc_l);
+      const bf16x8 pa = prompt_softmax<D>(x, p.scale_log2e, lane, m_run, acc, acc_l);
       acc_l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, as_bf16x8(ones), acc_l, 0, 0, 0);
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt)
