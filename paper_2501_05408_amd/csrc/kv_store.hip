@@ -46,6 +46,71 @@ __global__ __launch_bounds__(256) void kv_append_bf16(StoreParams p, const uint1
   }
 }
 
+// bf16, whole 32-slot groups: one wavefront per (sequence, head, group) turns 32
+// consecutive rows of k_new / v_new into the group's operand-major image and writes
+// it as full 1 KiB units.  Keys: every 16-byte piece of a unit is 8 consecutive dims
+// of one row, so it is a gather of 16-byte pieces.  Values: a 16-byte piece holds one
+// dim of 8 slots, so the 32 x D tile goes through LDS (row stride D + 2 elements,
+// which spreads the four rows a column tile's lanes read over different banks).
+// p.t is the first step of the first group (a multiple of 32), p.count the number of
+// groups times 32; rows of sequence b start at k_new[b][0].
+template <int D>
+__global__ __launch_bounds__(64) void kv_append_groups_bf16(StoreParams p, const uint16_t* __restrict__ k_new,
+                                                            const uint16_t* __restrict__ v_new) {
+  constexpr int KS = D / 32, DT = D / 16, LD = D + 2;
+  __shared__ uint16_t tile[32 * LD];
+  const int lane = threadIdx.x;
+  const int g = blockIdx.x, head = blockIdx.y, b = blockIdx.z;
+  const int t0 = p.t + 32 * g;  // first step of this group
+  const int Z = 1 << p.z_log2;
+  const int phys = clamp_block(p.block_table[(int64_t)b * p.max_blocks_per_seq + ((t0 >> p.z_log2) & p.tile_mask)],
+                               p.num_blocks);
+  const int64_t base = (((int64_t)phys * p.Hkv + head) << p.z_log2) * D + (int64_t)(t0 & (Z - 1)) * D;
+  const int64_t row0 = ((int64_t)b * p.src_steps + 32 * g) * p.Hkv + head;  // source row of slot 0 (rows are Hkv apart)
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+  // values -> LDS, 16 bytes per lane and load
+#pragma unroll
+  for (int i = 0; i < (32 * D / 8) / 64; ++i) {
+    const int piece = lane + 64 * i, row = piece / (D / 8), d8 = (piece % (D / 8)) * 8;
+    const u32x4 v = *reinterpret_cast<const u32x4*>(v_new + (row0 + (int64_t)row * p.Hkv) * D + d8);
+    uint32_t* dst = reinterpret_cast<uint32_t*>(tile + row * LD + d8);  // 4-byte aligned: LD and d8 are even
+    dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+  }
+  // keys: lane (row + 16c) of unit (tile, s) = dims 32s + 8c .. +7 of slot 16*tile + row
+  {
+    const int row = lane & 15, c = lane >> 4;
+    u32x4* kp = reinterpret_cast<u32x4*>(static_cast<uint16_t*>(p.k_pool) + base) + lane;
+#pragma unroll
+    for (int tl = 0; tl < 2; ++tl) {
+#pragma unroll
+      for (int s = 0; s < KS; ++s)
+        kp[(tl * KS + s) * 64] =
+            *reinterpret_cast<const u32x4*>(k_new + (row0 + (int64_t)(16 * tl + row) * p.Hkv) * D + 32 * s + 8 * c);
+    }
+  }
+  __syncthreads();
+  // values: lane (n + 16c) of unit dt = dim 16dt + n of slots {4c..4c+3, 16+4c..16+4c+3}
+  {
+    const int n = lane & 15, c = lane >> 4;
+    u32x4* vp = reinterpret_cast<u32x4*>(static_cast<uint16_t*>(p.v_pool) + base) + lane;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      const uint16_t* col = tile + 16 * dt + n;
+      uint32_t e[8];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        e[r] = col[(4 * c + r) * LD];
+        e[4 + r] = col[(16 + 4 * c + r) * LD];
+      }
+      u32x4 o;
+      o.x = e[0] | (e[1] << 16); o.y = e[2] | (e[3] << 16);
+      o.z = e[4] | (e[5] << 16); o.w = e[6] | (e[7] << 16);
+      vp[dt * 64] = o;
+    }
+  }
+}
+
 // f32: one thread per float4 of (b, c, head, d..d+3); both pools are row-major.
 template <int D>
 __global__ __launch_bounds__(256) void kv_append_f32(StoreParams p, const float* __restrict__ k_new,
@@ -99,6 +164,41 @@ __global__ __launch_bounds__(256) void kv_gather(StoreParams p, T* __restrict__ 
 
 hipError_t launch_append(const StoreParams& p, const void* k_new, const void* v_new, int D,
                          int dtype, hipStream_t stream) {
+  // bf16, uniform first step, at least one whole 32-slot group: the groups go through
+  // the group kernel, the rows before the first and after the last whole group
+  // through the element-wise kernel.
+  if (dtype == TEMPO_BF16 && !p.t_per_seq && p.count >= 32) {
+    const int g0 = (p.t + 31) >> 5, g1 = ((p.t + p.count) >> 5) - 1;  // whole groups g0 .. g1
+    if (g1 >= g0) {
+      const uint16_t* k = static_cast<const uint16_t*>(k_new);
+      const uint16_t* v = static_cast<const uint16_t*>(v_new);
+      const int64_t row_elems = (int64_t)p.Hkv * D;
+      const int head_rows = 32 * g0 - p.t, tail_first = 32 * (g1 + 1), tail_rows = p.t + p.count - tail_first;
+      hipError_t e = hipSuccess;
+      if (head_rows > 0) {
+        StoreParams h = p;
+        h.count = head_rows;
+        e = launch_append(h, k, v, D, dtype, stream);
+        if (e != hipSuccess) return e;
+      }
+      StoreParams m = p;
+      m.t = 32 * g0;
+      m.count = 32 * (g1 - g0 + 1);
+      const dim3 grid(g1 - g0 + 1, p.Hkv, p.batch);
+      const uint16_t* km = k + head_rows * row_elems;
+      const uint16_t* vm = v + head_rows * row_elems;
+      e = D == 128 ? launch(kv_append_groups_bf16<128>, grid, dim3(64), 0, stream, m, km, vm)
+                   : launch(kv_append_groups_bf16<64>, grid, dim3(64), 0, stream, m, km, vm);
+      if (e != hipSuccess) return e;
+      if (tail_rows > 0) {
+        StoreParams tl = p;
+        tl.t = tail_first;
+        tl.count = tail_rows;
+        e = launch_append(tl, k + (tail_first - p.t) * row_elems, v + (tail_first - p.t) * row_elems, D, dtype, stream);
+      }
+      return e;
+    }
+  }
   const int threads = 256;
   if (dtype == TEMPO_BF16) {
     const int total = p.batch * p.count * p.Hkv * D;
