@@ -39,8 +39,8 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the partial-attention kernel at the benchmark workload,
 # from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of `bench.py --counters`
 # (profiles/attn_partial_bf16_llama_t4095_hbm_traffic.txt), each scaled by what the
-# same counter reads for the 256 MiB copy kernel: 268,700,636 fetched + 1,711,841 written.
-MEASURED_TRAFFIC_BYTES = 270412477
+# same counter reads for the 256 MiB copy kernel: 268,712,922 fetched + 1,711,861 written.
+MEASURED_TRAFFIC_BYTES = 270424782
 
 
 def _timed(torch, fn, n, warm):
