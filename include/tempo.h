@@ -334,18 +334,24 @@ int tempo_attn_block_window(const tempo_kv* kv, const void* q, void* out, int32_
  * `stream`, nothing allocated).
  *   q, out        device, [batch][count][num_q_heads][head_dim]
  *   k_new, v_new  device, [batch][count][num_kv_heads][head_dim]
+ *   count_per_seq device, int32 [batch], or NULL: sequence b has only count_per_seq[b]
+ *                 (0 .. count) prompt steps; its later rows of q / k_new / v_new are not
+ *                 read into the store, its later rows of out and its later slots in
+ *                 the store are left as they are.  bf16 linear stores only
+ *                 (TEMPO_ERR_SHAPE otherwise); always the prompt kernel.
  *   workspace     device, 256-byte aligned, >= tempo_prefill_workspace_bytes(kv, batch,
  *                 num_q_heads, t + count - 1) bytes
  * All arguments are validated for every block before the first launch.
  */
 int tempo_prefill_causal(const tempo_kv* kv, const void* q, const void* k_new, const void* v_new,
                          void* out, int32_t batch, int32_t num_q_heads, int32_t t, int32_t count,
-                         float scale, void* workspace, size_t workspace_bytes, void* stream);
+                         const int32_t* count_per_seq, float scale, void* workspace,
+                         size_t workspace_bytes, void* stream);
 
 int tempo_prefill_window(const tempo_kv* kv, const void* q, const void* k_new, const void* v_new,
                          void* out, int32_t batch, int32_t num_q_heads, int32_t t, int32_t count,
-                         int32_t window, float scale, void* workspace, size_t workspace_bytes,
-                         void* stream);
+                         const int32_t* count_per_seq, int32_t window, float scale, void* workspace,
+                         size_t workspace_bytes, void* stream);
 
 /* How many launches a tempo_prefill_* call of `count` steps issues at most (host
  * only; 0 on unsupported arguments): 2 when the prompt's query blocks fill the part

@@ -100,7 +100,14 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_bf16(AttnParams p) {
   const int qb = nblocks - 1 - (int)blockIdx.x;  // longest range first
   const int hkv = blockIdx.y, b = blockIdx.z;
   const int c0 = qb * QB;                                           // first step of the block within the call
-  const int C = p.queries - c0 < QB ? p.queries - c0 : QB;         // steps in this block
+  // steps of this sequence in the call: all of them, or its own count
+  int steps_b = p.queries;
+  if (p.count_per_seq) {
+    const int n = ((const_i32_ptr)p.count_per_seq)[b];
+    steps_b = n < 0 ? 0 : (n < p.queries ? n : p.queries);
+  }
+  if (c0 >= steps_b) return;                                        // uniform over the workgroup, before any barrier
+  const int C = steps_b - c0 < QB ? steps_b - c0 : QB;             // steps in this block
   const int ncols = C * p.G;
   const int t_first = p.t + c0, t_last = t_first + C - 1;
   const int lo = (p.window > 0 && t_first - p.window + 1 > 0) ? t_first - p.window + 1 : 0;

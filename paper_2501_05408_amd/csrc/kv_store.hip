@@ -12,6 +12,13 @@
 namespace tempo {
 namespace {
 
+// Rows of the call that sequence b writes (all of them unless per-sequence counts are given).
+__device__ inline int rows_of(const StoreParams& p, int b) {
+  if (!p.count_per_seq) return INT32_MAX;
+  const int n = p.count_per_seq[b];
+  return n < 0 ? 0 : n;
+}
+
 __device__ inline int step_of(const StoreParams& p, int b) {
   int t = p.t_per_seq ? p.t_per_seq[b] : p.t;
   t = t > p.t ? p.t : t;  // the host validated p.t; never index past it
@@ -31,6 +38,7 @@ __global__ __launch_bounds__(256) void kv_append_bf16(StoreParams p, const uint1
   const int head = (idx / D) % p.Hkv;
   const int c = (idx / (D * p.Hkv)) % p.count;
   const int b = idx / (D * p.Hkv * p.count);
+  if (p.row0 + c >= rows_of(p, b)) return;
   const int t = step_of(p, b) + c;
   const int Z = 1 << p.z_log2;
   const int tile = t >> p.z_log2, slot = t & (Z - 1);
@@ -61,6 +69,10 @@ __global__ __launch_bounds__(64) void kv_append_groups_bf16(StoreParams p, const
   __shared__ uint16_t tile[32 * LD];
   const int lane = threadIdx.x;
   const int g = blockIdx.x, head = blockIdx.y, b = blockIdx.z;
+  // slots of this group that sequence b writes: all 32, or fewer where its rows end inside the group
+  const int rows_b = rows_of(p, b);
+  const int valid = rows_b == INT32_MAX ? 32 : rows_b - (p.row0 + 32 * g);
+  if (valid <= 0) return;  // uniform over the workgroup
   const int t0 = p.t + 32 * g;  // first step of this group
   const int Z = 1 << p.z_log2;
   const int phys = clamp_block(p.block_table[(int64_t)b * p.max_blocks_per_seq + ((t0 >> p.z_log2) & p.tile_mask)],
@@ -84,9 +96,11 @@ __global__ __launch_bounds__(64) void kv_append_groups_bf16(StoreParams p, const
 #pragma unroll
     for (int tl = 0; tl < 2; ++tl) {
 #pragma unroll
-      for (int s = 0; s < KS; ++s)
-        kp[(tl * KS + s) * 64] =
-            *reinterpret_cast<const u32x4*>(k_new + (row0 + (int64_t)(16 * tl + row) * p.Hkv) * D + 32 * s + 8 * c);
+      for (int s = 0; s < KS; ++s) {
+        if (16 * tl + row < valid)
+          kp[(tl * KS + s) * 64] =
+              *reinterpret_cast<const u32x4*>(k_new + (row0 + (int64_t)(16 * tl + row) * p.Hkv) * D + 32 * s + 8 * c);
+      }
     }
   }
   __syncthreads();
@@ -106,6 +120,19 @@ __global__ __launch_bounds__(64) void kv_append_groups_bf16(StoreParams p, const
       u32x4 o;
       o.x = e[0] | (e[1] << 16); o.y = e[2] | (e[3] << 16);
       o.z = e[4] | (e[5] << 16); o.w = e[6] | (e[7] << 16);
+      if (valid < 32) {  // the rows end inside this group: keep what the pool holds in the other slots
+        uint32_t m[8];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          m[r] = (4 * c + r) < valid ? 0xFFFFu : 0u;
+          m[4 + r] = (16 + 4 * c + r) < valid ? 0xFFFFu : 0u;
+        }
+        const u32x4 old = vp[dt * 64];
+        const uint32_t mx = m[0] | (m[1] << 16), my = m[2] | (m[3] << 16);
+        const uint32_t mz = m[4] | (m[5] << 16), mw = m[6] | (m[7] << 16);
+        o.x = (o.x & mx) | (old.x & ~mx); o.y = (o.y & my) | (old.y & ~my);
+        o.z = (o.z & mz) | (old.z & ~mz); o.w = (o.w & mw) | (old.w & ~mw);
+      }
       vp[dt * 64] = o;
     }
   }
@@ -122,6 +149,7 @@ __global__ __launch_bounds__(256) void kv_append_f32(StoreParams p, const float*
   const int head = (idx / (D / 4)) % p.Hkv;
   const int c = (idx / ((D / 4) * p.Hkv)) % p.count;
   const int b = idx / ((D / 4) * p.Hkv * p.count);
+  if (p.row0 + c >= rows_of(p, b)) return;
   const int t = step_of(p, b) + c;
   const int Z = 1 << p.z_log2;
   const int tile = t >> p.z_log2, slot = t & (Z - 1);
@@ -177,13 +205,14 @@ hipError_t launch_append(const StoreParams& p, const void* k_new, const void* v_
       hipError_t e = hipSuccess;
       if (head_rows > 0) {
         StoreParams h = p;
-        h.count = head_rows;
+        h.count = head_rows;  // row0 stays: these are the call's first rows
         e = launch_append(h, k, v, D, dtype, stream);
         if (e != hipSuccess) return e;
       }
       StoreParams m = p;
       m.t = 32 * g0;
       m.count = 32 * (g1 - g0 + 1);
+      m.row0 = p.row0 + head_rows;
       const dim3 grid(g1 - g0 + 1, p.Hkv, p.batch);
       const uint16_t* km = k + head_rows * row_elems;
       const uint16_t* vm = v + head_rows * row_elems;
@@ -194,6 +223,7 @@ hipError_t launch_append(const StoreParams& p, const void* k_new, const void* v_
         StoreParams tl = p;
         tl.t = tail_first;
         tl.count = tail_rows;
+        tl.row0 = p.row0 + (tail_first - p.t);
         e = launch_append(tl, k + (tail_first - p.t) * row_elems, v + (tail_first - p.t) * row_elems, D, dtype, stream);
       }
       return e;

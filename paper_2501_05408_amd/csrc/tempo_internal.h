@@ -65,6 +65,8 @@ struct StoreParams {
   int32_t batch;
   int32_t count;             // append: consecutive steps per sequence, rows [B][count][Hkv][D]
   int32_t src_steps;         // steps per sequence in the caller's k_new / v_new (>= count; == count normally)
+  const int32_t* count_per_seq;  // may be null; sequence b writes only its first count_per_seq[b] rows of the call
+  int32_t row0;              // index, on the call's step axis, of this launch's first row (for that test)
 };
 
 struct AttnParams {
@@ -75,6 +77,7 @@ struct AttnParams {
   const void* k_new;         // [B][Hkv][D]; non-null: append step t inside the attention kernel (queries == 1)
   const void* v_new;
   const int32_t* t_per_seq;  // may be null
+  const int32_t* count_per_seq;  // prompt kernel: may be null; sequence b answers only its first count_per_seq[b] steps
   const float* rope_cos;     // [positions][D/2]; non-null: q (and k_new) arrive unrotated and are
   const float* rope_sin;     //   rotated to their step's position inside the kernel
   float* ws_ml;              // [B][C][Hq][S][2]  (running max in log2 units, running sum)

@@ -285,6 +285,59 @@ def test_prompt_kernel_every_step(G, D, Hkv, window):
         assert_close(got[:, t], ref, dtype, f"prompt kernel step {t} G={G} w={window}")
 
 
+# ----------------------------------------------------------------------------
+# Prompts of different lengths in one call: each sequence writes and answers its
+# own steps only; everything beyond (store slots, rows of out) is left untouched.
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("G,D,window,first", [(3, 128, 0, 0), (3, 128, 40, 0), (2, 64, 0, 45), (16, 128, 0, 7)])
+def test_prompt_kernel_per_sequence_lengths(G, D, window, first):
+    B, Hkv, Z, steps = 12, 2, 32, 200
+    Hq = Hkv * G
+    dtype = T.TEMPO_BF16
+    q, K, V = host_inputs(50, B, first + steps, Hq, Hkv, D, dtype)
+    counts = [0, 1, 200, 31, 32, 33, 64, 199, 100, 5, 96, 130]
+    st = BlockStore(B, Hq, Hkv, D, Z, first + steps - 1, dtype, fill="nan")
+    ref_store = BlockStore(B, Hq, Hkv, D, Z, first + steps - 1, dtype, fill="nan")
+    Kd, Vd = dev(K, dtype), dev(V, dtype)
+    qd = dev(np.ascontiguousarray(np.transpose(q, (1, 0, 2, 3))), dtype)
+    if first:                                   # a common history, written the plain way into both stores
+        st.append_block(Kd[:, :first].contiguous(), Vd[:, :first].contiguous(), 0, first)
+        ref_store.append_block(Kd[:, :first].contiguous(), Vd[:, :first].contiguous(), 0, first)
+    cps = torch.tensor(counts, dtype=torch.int32, device=DEV)
+    out = torch.full((B, steps, Hq, D), 7.0, dtype=torch.bfloat16, device=DEV)
+    st.prefill_attend(qd[:, first:].contiguous(), Kd[:, first:].contiguous(), Vd[:, first:].contiguous(), out, first,
+                      steps, window, count_per_seq=cps)
+    # the store: as if every sequence had appended its own steps one by one
+    for c in range(max(counts)):
+        live = torch.tensor([first + min(c, n - 1) if n > 0 else -1 for n in counts], dtype=torch.int32, device=DEV)
+        rows = [b for b in range(B) if counts[b] > c]
+        if not rows:
+            break
+        # sequences whose prompt is over rewrite their last step (same bits); empty ones are handled below
+        ar = torch.arange(B, device=DEV)
+        tt = torch.clamp(live, min=0)
+        ref_store.append(Kd[ar, tt.long()].contiguous(), Vd[ar, tt.long()].contiguous(), first + c, tt)
+    got_k, got_v = st.gather(0, first + steps)
+    ref_k, ref_v = ref_store.gather(0, first + steps)
+    for b in range(B):
+        n = counts[b]
+        if n == 0 and first == 0:
+            continue                            # the reference loop wrote step 0 of empty sequences; compare below
+        assert torch.equal(got_k[b].view(torch.int16), ref_k[b].view(torch.int16)), f"keys of sequence {b}"
+        assert torch.equal(got_v[b].view(torch.int16), ref_v[b].view(torch.int16)), f"values of sequence {b}"
+    if first == 0:                              # an empty prompt leaves its (NaN-filled) blocks alone
+        assert torch.isnan(got_k[0].float()).all() and torch.isnan(got_v[0].float()).all()
+    K64, V64 = K.astype(np.float64), V.astype(np.float64)
+    got = np64(out)
+    for b in range(B):
+        n = counts[b]
+        assert (got[b, n:] == 7.0).all(), f"rows of out beyond the prompt of sequence {b} were written"
+        for c in range(n):
+            t = first + c
+            ref = oracle.attend(q[t][b:b + 1].astype(np.float64), K64[b:b + 1], V64[b:b + 1], t, window, 1.0 / np.sqrt(D))
+            assert_close(got[b:b + 1, c], ref, dtype, f"ragged prompt b={b} step {t}")
+
+
 def test_llama_shape_prefill_bf16_full_size():
     B, Hq, Hkv, D, Z, T_len = 16, 24, 8, 128, 256, 4096
     dtype = T.TEMPO_BF16

@@ -264,8 +264,10 @@ def test_bad_arguments_are_refused_before_any_launch():
 
     def prefill(kv, t=0, count=10, w=None, k=fake):
         if w is None:
-            return lib.tempo_prefill_causal(ctypes.byref(kv), fake, k, fake, fake, 2, 6, t, count, 0.1, None, 0, None)
-        return lib.tempo_prefill_window(ctypes.byref(kv), fake, k, fake, fake, 2, 6, t, count, w, 0.1, None, 0, None)
+            return lib.tempo_prefill_causal(ctypes.byref(kv), fake, k, fake, fake, 2, 6, t, count, None, 0.1, None, 0,
+                                            None)
+        return lib.tempo_prefill_window(ctypes.byref(kv), fake, k, fake, fake, 2, 6, t, count, None, w, 0.1, None, 0,
+                                        None)
 
     assert prefill(good) == T.TEMPO_ERR_WORKSPACE                 # everything else is fine
     assert prefill(good, count=0) == T.TEMPO_ERR_SHAPE
@@ -273,6 +275,9 @@ def test_bad_arguments_are_refused_before_any_launch():
     assert prefill(good, t=250, count=7) == T.TEMPO_ERR_RANGE     # last step 256 needs a fifth block
     assert prefill(good, t=250, count=6) == T.TEMPO_ERR_WORKSPACE
     assert prefill(good, w=0) == T.TEMPO_ERR_RANGE
+    f32_store = kv_desc(T.TEMPO_F32)   # per-sequence prompt lengths: bf16 linear stores only
+    assert lib.tempo_prefill_causal(ctypes.byref(f32_store), fake, fake, fake, fake, 2, 6, 0, 10, fake, 0.1,
+                                    fake << 4, 1 << 30, None) == T.TEMPO_ERR_SHAPE
     assert T.tempo_prefill_workspace_bytes(good, 2, 6, 255) >= T.tempo_attn_block_workspace_bytes(good, 2, 6, 21, 255)
 
     bad_plan = T.tempo_plan(48, 1, 1)
