@@ -353,6 +353,24 @@ int tempo_prefill_window(const tempo_kv* kv, const void* q, const void* k_new, c
                          const int32_t* count_per_seq, int32_t window, float scale, void* workspace,
                          size_t workspace_bytes, void* stream);
 
+/* tempo_prefill_* with the rotary producer fused in: q_raw and k_raw arrive
+ * unrotated; keys are turned to their step's position on the way into the store
+ * (the same bits tempo_rope_kv_append stores), queries when the prompt kernel loads
+ * them.  bf16 linear stores only (TEMPO_ERR_SHAPE otherwise); always the prompt
+ * kernel; rope->positions must exceed t + count - 1.  Other arguments as
+ * tempo_prefill_causal / _window. */
+int tempo_rope_prefill_causal(const tempo_kv* kv, const tempo_rope* rope, const void* q_raw,
+                              const void* k_raw, const void* v_new, void* out, int32_t batch,
+                              int32_t num_q_heads, int32_t t, int32_t count,
+                              const int32_t* count_per_seq, float scale, void* workspace,
+                              size_t workspace_bytes, void* stream);
+
+int tempo_rope_prefill_window(const tempo_kv* kv, const tempo_rope* rope, const void* q_raw,
+                              const void* k_raw, const void* v_new, void* out, int32_t batch,
+                              int32_t num_q_heads, int32_t t, int32_t count,
+                              const int32_t* count_per_seq, int32_t window, float scale,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
 /* How many launches a tempo_prefill_* call of `count` steps issues at most (host
  * only; 0 on unsupported arguments): 2 when the prompt's query blocks fill the part
  * (bf16, linear store: one block-store write, then one launch of the prompt kernel,

@@ -64,6 +64,54 @@ __device__ inline void load_values(const AttnParams& p, int64_t base, int lane, 
 
 // ---- the phases of a group ---------------------------------------------------------
 
+// ---- rotary embedding on 16-byte pieces ----------------------------------------------
+__device__ inline void unpack8(u32x4 v, float* f) {
+  const bf16x8 b = as_bf16x8(v);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) f[e] = (float)b[e];
+}
+__device__ inline u32x4 pack8(const float* f) {
+  bf16x8 b;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) b[e] = (__bf16)f[e];  // round to nearest even
+  return __builtin_bit_cast(u32x4, b);
+}
+// 8 consecutive table entries starting at entry i0 of row `pos`.
+__device__ inline void load_angles(const float* table, int64_t pos, int half, int i0, float* f) {
+  const float4* src = reinterpret_cast<const float4*>(table + pos * half + i0);
+  const float4 a = src[0], b = src[1];
+  f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w;
+  f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
+}
+// Two pieces of one head vector, dims i0 .. i0+7 (`lo`) and i0 + half .. (`hi`), turned
+// to position `pos`; the one place where bf16 pieces are rotated, so that every kernel
+// produces the same bits.
+__device__ inline void rotate_pieces(const float* rope_cos, const float* rope_sin, int64_t pos, int half, int i0,
+                                     u32x4& lo, u32x4& hi) {
+  float cs[8], sn[8], x[8], y[8], xl[8], yh[8];
+  load_angles(rope_cos, pos, half, i0, cs);
+  load_angles(rope_sin, pos, half, i0, sn);
+  unpack8(lo, x);
+  unpack8(hi, y);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    xl[e] = rope_lo(x[e], y[e], cs[e], sn[e]);
+    yh[e] = rope_hi(x[e], y[e], cs[e], sn[e]);
+  }
+  lo = pack8(xl);
+  hi = pack8(yh);
+}
+
+// Query operand registers: qreg[s] holds dims 32s + 8c .. +7, its partner qreg[s + KS/2].
+template <int D>
+__device__ inline void rotate_query(const AttnParams& p, int pos, int lane, u32x4* qreg) {
+  constexpr int KS = D / 32;
+  const int c = lane >> 4;
+#pragma unroll
+  for (int s = 0; s < KS / 2; ++s)
+    rotate_pieces(p.rope_cos, p.rope_sin, pos, D / 2, 32 * s + 8 * c, qreg[s], qreg[s + KS / 2]);
+}
+
 // Q.K^T for the group's two row tiles; logits in base-2 units.
 template <int D>
 __device__ inline void logits_of_group(const AttnParams& p, const u32x4* qreg, const Group<D>& g, float* x) {

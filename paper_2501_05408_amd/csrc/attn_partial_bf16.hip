@@ -124,49 +124,7 @@ __device__ __forceinline__ void append_values(const AttnParams& p, int64_t base,
   }
 }
 
-// ---- rotary embedding of q and of the fetched key row ------------------------------
-__device__ inline void unpack8(u32x4 v, float* f) {
-  const bf16x8 b = as_bf16x8(v);
-#pragma unroll
-  for (int e = 0; e < 8; ++e) f[e] = (float)b[e];
-}
-__device__ inline u32x4 pack8(const float* f) {
-  bf16x8 b;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) b[e] = (__bf16)f[e];  // round to nearest even
-  return __builtin_bit_cast(u32x4, b);
-}
-// 8 consecutive table entries starting at entry i0 of row `pos`.
-__device__ inline void load_angles(const float* table, int64_t pos, int half, int i0, float* f) {
-  const float4* src = reinterpret_cast<const float4*>(table + pos * half + i0);
-  const float4 a = src[0], b = src[1];
-  f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w;
-  f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
-}
-
-// Query operand registers: qreg[s] holds dims 32s + 8c .. +7, its partner qreg[s + KS/2].
-template <int D>
-__device__ inline void rotate_query(const AttnParams& p, int pos, int lane, u32x4* qreg) {
-  constexpr int KS = D / 32;
-  const int c = lane >> 4;
-#pragma unroll
-  for (int s = 0; s < KS / 2; ++s) {
-    float cs[8], sn[8], lo[8], hi[8];
-    load_angles(p.rope_cos, pos, D / 2, 32 * s + 8 * c, cs);
-    load_angles(p.rope_sin, pos, D / 2, 32 * s + 8 * c, sn);
-    unpack8(qreg[s], lo);
-    unpack8(qreg[s + KS / 2], hi);
-    float ylo[8], yhi[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      ylo[e] = rope_lo(lo[e], hi[e], cs[e], sn[e]);
-      yhi[e] = rope_hi(lo[e], hi[e], cs[e], sn[e]);
-    }
-    qreg[s] = pack8(ylo);
-    qreg[s + KS / 2] = pack8(yhi);
-  }
-}
-
+// ---- rotary embedding of the fetched key row ---------------------------------------
 // The row pair fetch_new_row returned: lanes 0..D/8-1 hold the key row (lane l:
 // dims 8l .. 8l+7), whose partner dims sit in lane l ^ (D/16).  All lanes call this.
 template <int D>

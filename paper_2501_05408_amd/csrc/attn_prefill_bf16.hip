@@ -85,7 +85,7 @@ __device__ inline bf16x8 prompt_softmax(const float* x, float scale, int lane, f
 // Steps per workgroup for a query group of G heads: all `waves` x 16 columns.
 __host__ __device__ inline int prefill_block_steps(int G, int waves) { return (16 * waves) / G; }
 
-template <int D, int NW>
+template <int D, int NW, bool kRope>
 __global__ __launch_bounds__(64 * NW) void attn_prefill_bf16(AttnParams p) {
   constexpr int KS = D / 32;
   constexpr int DT = D / 16;
@@ -139,6 +139,7 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_bf16(AttnParams p) {
       qreg[s] = col < ncols ? v : zero;
     }
   }
+  if (kRope) rotate_query<D>(p, hi_col, lane, qreg);  // queries arrive unrotated; hi_col is the column's own step
 
   float m_run = -INFINITY;                     // softmax reference of column lane&15 (log2 units)
   f32x4 acc[DT];                               // lane (n + 16c): dims 16dt + n of columns 4c .. 4c+3
@@ -244,8 +245,12 @@ hipError_t launch_prefill_bf16(const AttnParams& p, int batch, int D, hipStream_
   const dim3 grid(nblocks, p.Hkv, batch);
   const dim3 block(64 * NW);
   const size_t lds = 2 * (size_t)(2 * (D / 32) + D / 16) * 1024;
-  if (D == 128) return launch((attn_prefill_bf16<128, NW>), grid, block, lds, stream, p);
-  return launch((attn_prefill_bf16<64, NW>), grid, block, lds, stream, p);
+  if (p.rope_cos) {
+    if (D == 128) return launch((attn_prefill_bf16<128, NW, true>), grid, block, lds, stream, p);
+    return launch((attn_prefill_bf16<64, NW, true>), grid, block, lds, stream, p);
+  }
+  if (D == 128) return launch((attn_prefill_bf16<128, NW, false>), grid, block, lds, stream, p);
+  return launch((attn_prefill_bf16<64, NW, false>), grid, block, lds, stream, p);
 }
 
 }  // namespace tempo

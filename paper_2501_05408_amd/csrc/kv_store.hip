@@ -7,7 +7,7 @@
 // slot t mod Z (Section 4.3: tile n holds keys [nZ, (n+1)Z)).  An append may
 // carry `count` consecutive steps per sequence (rows [B][count][Hkv][D]): row c
 // goes to step t + c.
-#include "tempo_internal.h"
+#include "attn_bf16_common.h"
 
 namespace tempo {
 namespace {
@@ -49,8 +49,16 @@ __global__ __launch_bounds__(256) void kv_append_bf16(StoreParams p, const uint1
   vp[base + tile_off_v_bf16(D, slot, d)] = v_new[src];
   if ((d & 7) == 0) {
     uint16_t* kp = static_cast<uint16_t*>(p.k_pool);
-    const uint4 unit = *reinterpret_cast<const uint4*>(k_new + src);
-    *reinterpret_cast<uint4*>(kp + base + tile_off_k_bf16(D, slot, d)) = unit;
+    if (!p.rope_cos) {
+      const uint4 unit = *reinterpret_cast<const uint4*>(k_new + src);
+      *reinterpret_cast<uint4*>(kp + base + tile_off_k_bf16(D, slot, d)) = unit;
+    } else if (d < D / 2) {  // rotary: the piece at d and its partner at d + D/2 are turned together
+      u32x4 lo = *reinterpret_cast<const u32x4*>(k_new + src);
+      u32x4 hi = *reinterpret_cast<const u32x4*>(k_new + src + D / 2);
+      rotate_pieces(p.rope_cos, p.rope_sin, t, D / 2, d, lo, hi);
+      *reinterpret_cast<u32x4*>(kp + base + tile_off_k_bf16(D, slot, d)) = lo;
+      *reinterpret_cast<u32x4*>(kp + base + tile_off_k_bf16(D, slot, d + D / 2)) = hi;
+    }
   }
 }
 
@@ -79,7 +87,6 @@ __global__ __launch_bounds__(64) void kv_append_groups_bf16(StoreParams p, const
                                p.num_blocks);
   const int64_t base = (((int64_t)phys * p.Hkv + head) << p.z_log2) * D + (int64_t)(t0 & (Z - 1)) * D;
   const int64_t row0 = ((int64_t)b * p.src_steps + 32 * g) * p.Hkv + head;  // source row of slot 0 (rows are Hkv apart)
-  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
   // values -> LDS, 16 bytes per lane and load
 #pragma unroll
@@ -96,10 +103,15 @@ __global__ __launch_bounds__(64) void kv_append_groups_bf16(StoreParams p, const
 #pragma unroll
     for (int tl = 0; tl < 2; ++tl) {
 #pragma unroll
-      for (int s = 0; s < KS; ++s) {
-        if (16 * tl + row < valid)
-          kp[(tl * KS + s) * 64] =
-              *reinterpret_cast<const u32x4*>(k_new + (row0 + (int64_t)(16 * tl + row) * p.Hkv) * D + 32 * s + 8 * c);
+      for (int s = 0; s < KS / 2; ++s) {
+        if (16 * tl + row < valid) {
+          const uint16_t* src = k_new + (row0 + (int64_t)(16 * tl + row) * p.Hkv) * D + 32 * s + 8 * c;
+          u32x4 lo = *reinterpret_cast<const u32x4*>(src);            // dims 32s + 8c .. +7
+          u32x4 hi = *reinterpret_cast<const u32x4*>(src + D / 2);    // the same dims + D/2: unit s + KS/2
+          if (p.rope_cos) rotate_pieces(p.rope_cos, p.rope_sin, t0 + 16 * tl + row, D / 2, 32 * s + 8 * c, lo, hi);
+          kp[(tl * KS + s) * 64] = lo;
+          kp[(tl * KS + s + KS / 2) * 64] = hi;
+        }
       }
     }
   }

@@ -268,6 +268,8 @@ StoreParams store_params(const tempo_kv* kv, int32_t batch, int32_t t, const int
   p.src_steps = count;
   p.count_per_seq = nullptr;
   p.row0 = 0;
+  p.rope_cos = nullptr;
+  p.rope_sin = nullptr;
   return p;
 }
 
@@ -639,7 +641,7 @@ bool prefill_in_one_launch(const tempo_kv* kv, int32_t batch, int32_t Hq, int32_
 // as many steps as the column tiles hold.
 static int prefill(const tempo_kv* kv, const void* q, const void* k_new, const void* v_new, void* out, int32_t batch,
             int32_t Hq, int32_t t, int32_t count, const int32_t* count_per_seq, int32_t window, float scale,
-            void* workspace, size_t workspace_bytes, void* stream) {
+            void* workspace, size_t workspace_bytes, void* stream, const tempo_rope* rope = nullptr) {
   int rc = check_store(kv);
   if (rc != TEMPO_OK) return rc;
   if (!q || !k_new || !v_new || !out) return TEMPO_ERR_NULL;
@@ -666,18 +668,27 @@ static int prefill(const tempo_kv* kv, const void* q, const void* k_new, const v
 
   // Enough query blocks to fill the part: write the whole prompt, then one launch of
   // the prompt kernel (each workgroup walks its block's whole key range; no partials).
-  // per-sequence prompt lengths exist in the prompt kernel only
-  if (count_per_seq && (kv->dtype != TEMPO_BF16 || kv->ring_blocks != 0 ||
-                        (int64_t)batch * count * kv->num_kv_heads * kv->head_dim > INT32_MAX))
+  // per-sequence prompt lengths and the rotary producer exist in the prompt kernel only
+  if ((count_per_seq || rope) && (kv->dtype != TEMPO_BF16 || kv->ring_blocks != 0 ||
+                                  (int64_t)batch * count * kv->num_kv_heads * kv->head_dim > INT32_MAX))
     return TEMPO_ERR_SHAPE;
-  if (count_per_seq || prefill_in_one_launch(kv, batch, Hq, count)) {
+  if (rope && (rc = check_rope(rope, kv->head_dim, t + count - 1)) != TEMPO_OK) return rc;
+  if (count_per_seq || rope || prefill_in_one_launch(kv, batch, Hq, count)) {
     StoreParams sp = store_params(kv, batch, t, nullptr, count);
     sp.count_per_seq = count_per_seq;
+    if (rope) {
+      sp.rope_cos = rope->cos;
+      sp.rope_sin = rope->sin;
+    }
     if ((rc = launch_status(launch_append(sp, k_new, v_new, kv->head_dim, kv->dtype, s), "kv_append_block")) != TEMPO_OK)
       return rc;
     const tempo_plan unused = {32, 1, 1};
     AttnParams p = attn_params(kv, q, out, Hq, t, nullptr, window, scale, &unused, workspace, batch, count);
     p.count_per_seq = count_per_seq;
+    if (rope) {
+      p.rope_cos = rope->cos;
+      p.rope_sin = rope->sin;
+    }
     return launch_status(launch_prefill_bf16(p, batch, kv->head_dim, s), "attn_prefill");
   }
 
@@ -721,6 +732,25 @@ int tempo_prefill_window(const tempo_kv* kv, const void* q, const void* k_new, c
   if (window < 1 || window > INT32_MAX - 128) return TEMPO_ERR_RANGE;
   return prefill(kv, q, k_new, v_new, out, batch, num_q_heads, t, count, count_per_seq, window, scale, workspace,
                  workspace_bytes, stream);
+}
+
+int tempo_rope_prefill_causal(const tempo_kv* kv, const tempo_rope* rope, const void* q_raw, const void* k_raw,
+                              const void* v_new, void* out, int32_t batch, int32_t num_q_heads, int32_t t,
+                              int32_t count, const int32_t* count_per_seq, float scale, void* workspace,
+                              size_t workspace_bytes, void* stream) {
+  if (!rope) return TEMPO_ERR_NULL;
+  return prefill(kv, q_raw, k_raw, v_new, out, batch, num_q_heads, t, count, count_per_seq, 0, scale, workspace,
+                 workspace_bytes, stream, rope);
+}
+
+int tempo_rope_prefill_window(const tempo_kv* kv, const tempo_rope* rope, const void* q_raw, const void* k_raw,
+                              const void* v_new, void* out, int32_t batch, int32_t num_q_heads, int32_t t,
+                              int32_t count, const int32_t* count_per_seq, int32_t window, float scale,
+                              void* workspace, size_t workspace_bytes, void* stream) {
+  if (!rope) return TEMPO_ERR_NULL;
+  if (window < 1 || window > INT32_MAX - 128) return TEMPO_ERR_RANGE;
+  return prefill(kv, q_raw, k_raw, v_new, out, batch, num_q_heads, t, count, count_per_seq, window, scale,
+                 workspace, workspace_bytes, stream, rope);
 }
 
 int tempo_prefill_launches(const tempo_kv* kv, int32_t batch, int32_t num_q_heads, int32_t count) {

@@ -67,6 +67,8 @@ struct StoreParams {
   int32_t src_steps;         // steps per sequence in the caller's k_new / v_new (>= count; == count normally)
   const int32_t* count_per_seq;  // may be null; sequence b writes only its first count_per_seq[b] rows of the call
   int32_t row0;              // index, on the call's step axis, of this launch's first row (for that test)
+  const float* rope_cos;     // bf16 append: non-null = keys arrive unrotated and are turned to their step's
+  const float* rope_sin;     //   position on the way into the store ([positions][D/2] tables)
 };
 
 struct AttnParams {

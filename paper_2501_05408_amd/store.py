@@ -148,16 +148,24 @@ class BlockStore:
                                       self._block_ws, nbytes)
         return out
 
-    def prefill_attend(self, q, k_new, v_new, out, t, count, window=0, scale=None, count_per_seq=None):
+    def prefill_attend(self, q, k_new, v_new, out, t, count, window=0, scale=None, count_per_seq=None,
+                       rope=False):
         """Write steps t .. t+count-1 and answer all of them in one call
         (q, out [batch][count][Hq][D]; k_new, v_new [batch][count][Hkv][D]).  With
-        count_per_seq (int32 device tensor) sequence b has only that many steps."""
+        count_per_seq (int32 device tensor) sequence b has only that many steps; with
+        rope=True q and k_new arrive unrotated (set_rope tables)."""
         ws_t = self.ring_blocks * self.Z + 128 if self.ring_blocks else self.max_t
         nbytes = T.tempo_prefill_workspace_bytes(self.kv, self.batch, self.Hq, ws_t)
         if getattr(self, "_prefill_ws", None) is None or self._prefill_ws.numel() < nbytes:
             self._prefill_ws = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
         s = self.scale if scale is None else scale
-        if window:
+        if rope and window:
+            T.tempo_rope_prefill_window(self.kv, self.rope, q, k_new, v_new, out, self.batch, self.Hq, t, count,
+                                        count_per_seq, window, s, self._prefill_ws, nbytes)
+        elif rope:
+            T.tempo_rope_prefill_causal(self.kv, self.rope, q, k_new, v_new, out, self.batch, self.Hq, t, count,
+                                        count_per_seq, s, self._prefill_ws, nbytes)
+        elif window:
             T.tempo_prefill_window(self.kv, q, k_new, v_new, out, self.batch, self.Hq, t, count, count_per_seq,
                                    window, s, self._prefill_ws, nbytes)
         else:

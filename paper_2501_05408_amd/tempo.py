@@ -114,6 +114,10 @@ SIGNATURES = {
                                             _vp, ctypes.c_size_t, _vp]),
     "tempo_prefill_window": (ctypes.c_int, [_kvp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _i32,
                                             ctypes.c_float, _vp, ctypes.c_size_t, _vp]),
+    "tempo_rope_prefill_causal": (ctypes.c_int, [_kvp, _ropep, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp,
+                                                 ctypes.c_float, _vp, ctypes.c_size_t, _vp]),
+    "tempo_rope_prefill_window": (ctypes.c_int, [_kvp, _ropep, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _i32,
+                                                 ctypes.c_float, _vp, ctypes.c_size_t, _vp]),
     "tempo_prefill_launches": (ctypes.c_int, [_kvp, _i32, _i32, _i32]),
     "tempo_prefill_workspace_bytes": (ctypes.c_size_t, [_kvp, _i32, _i32, _i32]),
     "tempo_attn_block_with_plan": (ctypes.c_int, [_kvp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _i32, ctypes.c_float,
@@ -364,6 +368,22 @@ def tempo_prefill_window(kv, q, k_new, v_new, out, batch, num_q_heads, t, count,
                                        num_q_heads, t, count, _ptr(count_per_seq), window, scale,
                                        _ptr(workspace), workspace_bytes, _stream(stream)),
            "tempo_prefill_window")
+
+
+def tempo_rope_prefill_causal(kv, rope, q_raw, k_raw, v_new, out, batch, num_q_heads, t, count, count_per_seq,
+                              scale, workspace, workspace_bytes, stream=None):
+    _check(load().tempo_rope_prefill_causal(ctypes.byref(kv), ctypes.byref(rope), _ptr(q_raw), _ptr(k_raw),
+                                            _ptr(v_new), _ptr(out), batch, num_q_heads, t, count,
+                                            _ptr(count_per_seq), scale, _ptr(workspace), workspace_bytes,
+                                            _stream(stream)), "tempo_rope_prefill_causal")
+
+
+def tempo_rope_prefill_window(kv, rope, q_raw, k_raw, v_new, out, batch, num_q_heads, t, count, count_per_seq,
+                              window, scale, workspace, workspace_bytes, stream=None):
+    _check(load().tempo_rope_prefill_window(ctypes.byref(kv), ctypes.byref(rope), _ptr(q_raw), _ptr(k_raw),
+                                            _ptr(v_new), _ptr(out), batch, num_q_heads, t, count,
+                                            _ptr(count_per_seq), window, scale, _ptr(workspace), workspace_bytes,
+                                            _stream(stream)), "tempo_rope_prefill_window")
 
 
 def tempo_prefill_launches(kv: tempo_kv, batch: int, num_q_heads: int, count: int) -> int:

@@ -190,6 +190,49 @@ def test_fused_rope_step_large_positions_ring_bf16():
         assert_close(out, ref, dtype, f"ring rope step t={t0 + i}")
 
 
+# ----------------------------------------------------------------------------
+# A prompt with the rotary producer fused in: keys rotated on their way into the
+# store (the bits tempo_rope_kv_append stores), queries when the prompt kernel
+# loads them; every step against the oracle, per-sequence lengths included.
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("D,G,window", [(128, 3, 0), (64, 2, 60), (128, 1, 0)])
+def test_rope_prompt_every_step(D, G, window):
+    B, Hkv, Z, steps, first = 6, 2, 32, 150, 21
+    Hq = Hkv * G
+    dtype = T.TEMPO_BF16
+    q, K, V = host_inputs(56, B, steps, Hq, Hkv, D, dtype)
+    cos_t, sin_t = tables(steps, D)
+    st = BlockStore(B, Hq, Hkv, D, Z, steps - 1, dtype, fill="nan")
+    one = BlockStore(B, Hq, Hkv, D, Z, steps - 1, dtype, fill="nan")
+    st.set_rope(cos_t, sin_t)
+    one.set_rope(cos_t, sin_t)
+    Kd, Vd = dev(K, dtype), dev(V, dtype)
+    qd = dev(np.ascontiguousarray(np.transpose(q, (1, 0, 2, 3))), dtype)
+    counts = [steps - first, 1, 40, 0, 100, 129]
+    cps = torch.tensor(counts, dtype=torch.int32, device=DEV)
+    o1 = torch.empty((B, first, Hq, D), dtype=torch.bfloat16, device=DEV)
+    st.prefill_attend(qd[:, :first].contiguous(), Kd[:, :first].contiguous(), Vd[:, :first].contiguous(), o1, 0,
+                      first, window, rope=True)
+    o2 = torch.full((B, steps - first, Hq, D), 7.0, dtype=torch.bfloat16, device=DEV)
+    st.prefill_attend(qd[:, first:].contiguous(), Kd[:, first:].contiguous(), Vd[:, first:].contiguous(), o2, first,
+                      steps - first, window, count_per_seq=cps, rope=True)
+    last = [first + n for n in counts]                     # steps each sequence holds
+    for t in range(steps):                                  # the same keys through single rotate-and-append calls
+        tps = torch.tensor([min(t, l - 1) for l in last], dtype=torch.int32, device=DEV)
+        ar = torch.arange(B, device=DEV)
+        one.rope_append(Kd[ar, tps.long()].contiguous(), Vd[ar, tps.long()].contiguous(), t, tps)
+    assert torch.equal(st.k_pool.view(torch.int16), one.k_pool.view(torch.int16))
+    assert torch.equal(st.v_pool.view(torch.int16), one.v_pool.view(torch.int16))
+    qr64, Kr64 = oracle_rotated_kv(q, K, dtype)
+    V64 = V.astype(np.float64)
+    got = np.concatenate([np64(o1), np64(o2)], axis=1)
+    for b in range(B):
+        assert (got[b, last[b]:] == 7.0).all()
+        for t in range(last[b]):
+            ref = oracle.attend(qr64[t][b:b + 1], Kr64[b:b + 1], V64[b:b + 1], t, window, 1.0 / np.sqrt(D))
+            assert_close(got[b:b + 1, t], ref, dtype, f"rope prompt b={b} step {t}")
+
+
 def test_llama_shape_fused_rope_step_full_size():
     B, Hq, Hkv, D, Z, T_len = 16, 24, 8, 128, 256, 4096
     dtype = T.TEMPO_BF16
