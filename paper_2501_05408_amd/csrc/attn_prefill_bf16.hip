@@ -23,6 +23,16 @@
 // follow find it in the caches; the longest blocks are dispatched first.
 #include "attn_bf16_common.h"
 
+// The instantiation that is built: wavefronts per workgroup, column tiles per
+// wavefront, and the occupancy (wavefronts per SIMD) the register allocation must
+// allow.  Measured on the 4096-step x 16-sequence prompt: 8 x 1 2.45 ms, 4 x 2 (two
+// per SIMD) 2.56 ms, 8 x 2 2.70 ms, 4 x 1 3.14 ms.
+#ifndef PROMPT_NW
+#define PROMPT_NW 8
+#define PROMPT_NT 1
+#define PROMPT_MIN_WAVES 1
+#endif
+
 namespace tempo {
 namespace {
 
@@ -82,11 +92,15 @@ __device__ inline bf16x8 prompt_softmax(const float* x, float scale, int lane, f
   return pa;
 }
 
-// Steps per workgroup for a query group of G heads: all `waves` x 16 columns.
-__host__ __device__ inline int prefill_block_steps(int G, int waves) { return (16 * waves) / G; }
+// Steps per workgroup for a query group of G heads: all `waves` x `tiles` x 16 columns.
+__host__ __device__ inline int prefill_block_steps(int G, int waves, int tiles) { return (16 * waves * tiles) / G; }
 
-template <int D, int NW, bool kRope>
-__global__ __launch_bounds__(64 * NW) void attn_prefill_bf16(AttnParams p) {
+// NW wavefronts per workgroup, NT column tiles (of 16 columns) per wavefront.  The
+// key/value operands a wavefront reads from LDS serve all its NT tiles, so LDS
+// traffic per column falls with NT; the accumulators (NT x (D/16 + 1) tiles) set
+// the register budget.
+template <int D, int NW, int NT, bool kRope>
+__global__ __launch_bounds__(64 * NW, PROMPT_MIN_WAVES) void attn_prefill_bf16(AttnParams p) {
   constexpr int KS = D / 32;
   constexpr int DT = D / 16;
   constexpr int UNITS = 2 * KS + DT;          // 1 KiB units of one group: keys then values
@@ -95,7 +109,7 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_bf16(AttnParams p) {
   extern __shared__ u32x4 lds[];              // [2][UNITS][64] x 16 bytes
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int QB = prefill_block_steps(p.G, NW);
+  const int QB = prefill_block_steps(p.G, NW, NT);
   const int nblocks = (p.queries + QB - 1) / QB;
   const int qb = nblocks - 1 - (int)blockIdx.x;  // longest range first
   const int hkv = blockIdx.y, b = blockIdx.z;
@@ -113,22 +127,30 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_bf16(AttnParams p) {
   const int lo = (p.window > 0 && t_first - p.window + 1 > 0) ? t_first - p.window + 1 : 0;
   const int g_first = lo >> 5, g_last = t_last >> 5;
 
-  // This wavefront's 16 columns.  Unused columns behave like the block's last step with q = 0.
-  const int col = 16 * wave + (lane & 15);
-  const int cq = col < ncols ? col / p.G : C - 1;
-  const int gq = col < ncols ? col - cq * p.G : 0;
-  const int hi_col = t_first + cq;
-  const int lo_col = (p.window > 0 && hi_col - p.window + 1 > 0) ? hi_col - p.window + 1 : 0;
-  // wavefront-uniform bounds: the groups this wavefront has any work in, and those no column cuts
-  const int first_col = 16 * wave, last_col = (16 * wave + 15) < ncols - 1 ? (16 * wave + 15) : ncols - 1;
+  // wavefront-uniform bounds over this wavefront's 16 * NT columns: the groups it has
+  // any work in, and those no column cuts
+  const int first_col = 16 * NT * wave;
+  const int last_col = (first_col + 16 * NT - 1) < ncols - 1 ? (first_col + 16 * NT - 1) : ncols - 1;
   const bool idle = first_col >= ncols;                             // a wavefront beyond the block's columns
   const int w_hi = t_first + (idle ? 0 : last_col / p.G);           // newest key any of its columns sees
   const int w_hi_min = t_first + (idle ? 0 : first_col / p.G);      // newest key ALL of its columns see
   const int w_lo_first = (p.window > 0 && w_hi_min - p.window + 1 > 0) ? w_hi_min - p.window + 1 : 0;
   const int w_lo_last = (p.window > 0 && w_hi - p.window + 1 > 0) ? w_hi - p.window + 1 : 0;
 
-  u32x4 qreg[KS];
-  {
+  // Per column tile: this lane's column (unused columns behave like the block's last
+  // step with q = 0), its range, its query operand, its softmax state.
+  int lo_col[NT], hi_col[NT];
+  u32x4 qreg[NT][KS];
+  float m_run[NT];                             // softmax reference of column lane&15 (log2 units)
+  f32x4 acc[NT][DT];                           // lane (n + 16c): dims 16dt + n of columns 4c .. 4c+3
+  f32x4 acc_l[NT];                             // running sums of columns 4c .. 4c+3 (the same in every n)
+#pragma unroll
+  for (int jt = 0; jt < NT; ++jt) {
+    const int col = first_col + 16 * jt + (lane & 15);
+    const int cq = col < ncols ? col / p.G : C - 1;
+    const int gq = col < ncols ? col - cq * p.G : 0;
+    hi_col[jt] = t_first + cq;
+    lo_col[jt] = (p.window > 0 && hi_col[jt] - p.window + 1 > 0) ? hi_col[jt] - p.window + 1 : 0;
     const int c = lane >> 4;
     const uint16_t* qp = static_cast<const uint16_t*>(p.q) +
                          (((int64_t)b * p.io_steps + c0 + cq) * p.Hq + (int64_t)hkv * p.G + gq) * D + 8 * c;
@@ -136,16 +158,14 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_bf16(AttnParams p) {
     for (int s = 0; s < KS; ++s) {
       const u32x4 zero = {0u, 0u, 0u, 0u};
       const u32x4 v = *reinterpret_cast<const u32x4*>(qp + 32 * s);
-      qreg[s] = col < ncols ? v : zero;
+      qreg[jt][s] = col < ncols ? v : zero;
     }
-  }
-  if (kRope) rotate_query<D>(p, hi_col, lane, qreg);  // queries arrive unrotated; hi_col is the column's own step
-
-  float m_run = -INFINITY;                     // softmax reference of column lane&15 (log2 units)
-  f32x4 acc[DT];                               // lane (n + 16c): dims 16dt + n of columns 4c .. 4c+3
-  f32x4 acc_l = {0.f, 0.f, 0.f, 0.f};          // running sums of columns 4c .. 4c+3 (the same in every n)
+    if (kRope) rotate_query<D>(p, hi_col[jt], lane, qreg[jt]);  // queries arrive unrotated; hi_col is the column's own step
+    m_run[jt] = -INFINITY;
+    acc_l[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-  for (int dt = 0; dt < DT; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int dt = 0; dt < DT; ++dt) acc[jt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
   const u32x4 ones = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};  // bf16 1.0 x 8
 
   // Copy of one group: wavefront w moves units w, w + NW, ... (keys are units
@@ -189,28 +209,36 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_bf16(AttnParams p) {
     // Has this wavefront anything to do in this group?  (Uniform over the wavefront.)
     const int j0 = grp << 5;
     if (!idle && j0 <= w_hi && j0 + 31 >= (p.window > 0 ? w_lo_first : 0)) {
-      Group<D> g;
       const u32x4* src = lds + buf * UNITS * 64 + lane;
-#pragma unroll
-      for (int i = 0; i < 2 * KS; ++i) g.k[i] = src[i * 64];
-      float x[8];  // raw dot products of the two row tiles
-      {
-        f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int s = 0; s < KS; ++s) {
-          sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(g.k[s]), as_bf16x8(qreg[s]), sa, 0, 0, 0);
-          sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(g.k[KS + s]), as_bf16x8(qreg[s]), sb, 0, 0, 0);
-        }
-#pragma unroll
-        for (int r = 0; r < 4; ++r) { x[r] = sa[r]; x[4 + r] = sb[r]; }
-      }
       const bool cut = j0 < w_lo_last || j0 + 31 > w_hi_min;
-      if (cut) mask_logits(grp, lo_col, hi_col, lane, x);
-      const bf16x8 pa = prompt_softmax<D>(x, p.scale_log2e, lane, m_run, acc, acc_l);
-      acc_l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, as_bf16x8(ones), acc_l, 0, 0, 0);
+      bf16x8 pa[NT];
+      {
+        Group<D> g;  // only the key half is used: the operands serve all NT tiles
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt)
-        acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, as_bf16x8(src[(2 * KS + dt) * 64]), acc[dt], 0, 0, 0);
+        for (int i = 0; i < 2 * KS; ++i) g.k[i] = src[i * 64];
+#pragma unroll
+        for (int jt = 0; jt < NT; ++jt) {
+          float x[8];  // raw dot products of the two row tiles
+          f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int s = 0; s < KS; ++s) {
+            sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(g.k[s]), as_bf16x8(qreg[jt][s]), sa, 0, 0, 0);
+            sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(g.k[KS + s]), as_bf16x8(qreg[jt][s]), sb, 0, 0, 0);
+          }
+#pragma unroll
+          for (int r = 0; r < 4; ++r) { x[r] = sa[r]; x[4 + r] = sb[r]; }
+          if (cut) mask_logits(grp, lo_col[jt], hi_col[jt], lane, x);
+          pa[jt] = prompt_softmax<D>(x, p.scale_log2e, lane, m_run[jt], acc[jt], acc_l[jt]);
+          acc_l[jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa[jt], as_bf16x8(ones), acc_l[jt], 0, 0, 0);
+        }
+      }
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) {
+        const u32x4 vv = src[(2 * KS + dt) * 64];
+#pragma unroll
+        for (int jt = 0; jt < NT; ++jt)
+          acc[jt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa[jt], as_bf16x8(vv), acc[jt][dt], 0, 0, 0);
+      }
     }
 
     if (more) stash(buf ^ 1, grp + 1);  // nobody reads that buffer in this iteration
@@ -220,37 +248,43 @@ __global__ __launch_bounds__(64 * NW) void attn_prefill_bf16(AttnParams p) {
   // Every column saw its own key, so its sum is > 0.  Columns (4c + r) of acc, value dims 16dt + n.
   const int n = lane & 15, c = lane >> 4;
 #pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const int j = 16 * wave + 4 * c + r;
-    const float l_j = acc_l[r];
-    if (j < ncols) {
-      const int jc = j / p.G, jg = j - jc * p.G;
-      __bf16* orow = static_cast<__bf16*>(p.out) +
-                     (((int64_t)b * p.io_steps + c0 + jc) * p.Hq + (int64_t)hkv * p.G + jg) * D;
-      const float inv = 1.0f / l_j;
+  for (int jt = 0; jt < NT; ++jt) {
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt) orow[16 * dt + n] = (__bf16)(acc[dt][r] * inv);
+    for (int r = 0; r < 4; ++r) {
+      const int j = first_col + 16 * jt + 4 * c + r;
+      const float l_j = acc_l[jt][r];
+      if (j < ncols) {
+        const int jc = j / p.G, jg = j - jc * p.G;
+        __bf16* orow = static_cast<__bf16*>(p.out) +
+                       (((int64_t)b * p.io_steps + c0 + jc) * p.Hq + (int64_t)hkv * p.G + jg) * D;
+        const float inv = 1.0f / l_j;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) orow[16 * dt + n] = (__bf16)(acc[jt][dt][r] * inv);
+      }
     }
   }
 }
 
 }  // namespace
 
-int prefill_bf16_block_steps(int G) { return prefill_block_steps(G, 8); }
+// The instantiation in use: wavefronts per workgroup and column tiles per wavefront.
+constexpr int kPromptWaves = PROMPT_NW, kPromptTiles = PROMPT_NT;
+
+int prefill_bf16_block_steps(int G) { return prefill_block_steps(G, kPromptWaves, kPromptTiles); }
 
 hipError_t launch_prefill_bf16(const AttnParams& p, int batch, int D, hipStream_t stream) {
-  constexpr int NW = 8;
-  const int QB = prefill_block_steps(p.G, NW);
+  constexpr int NW = kPromptWaves, NT = kPromptTiles;
+  const int QB = prefill_block_steps(p.G, NW, NT);
   const int nblocks = (p.queries + QB - 1) / QB;
   const dim3 grid(nblocks, p.Hkv, batch);
   const dim3 block(64 * NW);
   const size_t lds = 2 * (size_t)(2 * (D / 32) + D / 16) * 1024;
   if (p.rope_cos) {
-    if (D == 128) return launch((attn_prefill_bf16<128, NW, true>), grid, block, lds, stream, p);
-    return launch((attn_prefill_bf16<64, NW, true>), grid, block, lds, stream, p);
+    if (D == 128) return launch((attn_prefill_bf16<128, NW, NT, true>), grid, block, lds, stream, p);
+    return launch((attn_prefill_bf16<64, NW, NT, true>), grid, block, lds, stream, p);
   }
-  if (D == 128) return launch((attn_prefill_bf16<128, NW, false>), grid, block, lds, stream, p);
-  return launch((attn_prefill_bf16<64, NW, false>), grid, block, lds, stream, p);
+  if (D == 128) return launch((attn_prefill_bf16<128, NW, NT, false>), grid, block, lds, stream, p);
+  return launch((attn_prefill_bf16<64, NW, NT, false>), grid, block, lds, stream, p);
 }
 
 }  // namespace tempo
