@@ -530,10 +530,29 @@ def main() -> int:
             "sample": f"full batch of 16 sequences at t=4095 (one layer, attention only), "
                       f"median of {len(times)} runs, {med * 1e3:.1f} ms per step",
         }
+        # the oracle at the steps of the per-t curve (two runs each, the faster one)
+        per_t = {}
+        for tt in (255, 511, 1023, 2047):
+            best = None
+            for _ in range(2):
+                c0 = time.perf_counter()
+                oracle.attend(qc, Kc, Vc, tt, 0, scale)   # reads keys 0..tt only
+                d = time.perf_counter() - c0
+                best = d if best is None or d < best else best
+            per_t[str(tt)] = round(best * 1e3, 2)
+        per_t[str(t)] = round(med * 1e3, 2)
+        result["cpu_baseline"]["ms_per_step_at_t"] = per_t
         del Kc, Vc
 
     # --- extras: per-t curve and a whole decode run with real per-step appends ------
     if not args.no_extras:
+        # the same step on ONE layer's pool (256 MiB of keys/values, the size of the last-level
+        # cache): not the headline, reported so the effect of rotating pools is visible
+        st0 = stores[0]
+        dt1 = _timed(torch, lambda i: st0.step_causal(q, st0.k_last, st0.v_last, outs[0], t), args.steps, args.warmup)
+        result["unrotated_single_pool"] = {"ms_per_step": round(dt1 * 1e3, 5),
+                                           "kv_gbs": round(step_bytes / dt1 / 1e9, 1),
+                                           "note": "one 256 MiB pool reused every step (partly cache resident)"}
         curve = {}
         for tt in (255, 511, 1023, 2047, 4095):
             n = 100
