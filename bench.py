@@ -91,8 +91,8 @@ def other_workloads(torch, T, BlockStore, synth, dev, kv_bytes_per_token):
                                "kv_gbs": round(16 * 4096 * kv_bytes_per_token / dt / 1e9, 1),
                                "splits": plan.num_splits, "tokens_per_split": plan.tokens_per_split,
                                "waves": plan.waves}
-    # wider blocks: 10 steps (30 columns, two column tiles) and 21 steps (63 columns, four tiles)
-    for C in (10, 21):
+    # wider blocks through the LDS-staged kernel: 10, 21 and 42 steps (30, 63 and 126 columns)
+    for C in (10, 21, 42):
         qc = synth.device_normal((16, C, Hq, D), 177, torch.bfloat16, dev)
         kc = synth.device_normal((16, C, Hkv, D), 178, torch.bfloat16, dev)
         vc = synth.device_normal((16, C, Hkv, D), 179, torch.bfloat16, dev)
@@ -121,7 +121,7 @@ def other_workloads(torch, T, BlockStore, synth, dev, kv_bytes_per_token):
     tflops = 16 * pairs * 4 * D * Hq / dt / 1e12
     out["prompt_b16_t4096"] = {"ms": round(dt * 1e3, 3), "tokens_per_s": round(16 * P / dt, 1),
                                "tflops": round(tflops, 1),
-                               "roofline": {"kernel": "attn_prefill_bf16<128, 8>", "bound": "mfma",
+                               "roofline": {"kernel": "attn_prefill_bf16<128, 8, 1, false>", "bound": "mfma",
                                             "achieved": round(tflops, 1), "peak": 2500.0, "unit": "TFLOP/s",
                                             "frac": round(tflops / 2500.0, 4)},
                                "note": "one tempo_prefill_causal call (block-store write + prompt kernel); "
@@ -251,7 +251,7 @@ def prompt_only(torch, T, BlockStore, synth, dev, repeats):
     flops = B * (P * (P + 1) // 2) * 4 * D * Hq
     return {"workload": "prompt of 4096 steps x 16 sequences, llama-3.2-3b attention shape, one tempo_prefill_causal call",
             "ms": round(dt * 1e3, 3), "tokens_per_s": round(B * P / dt, 1), "algorithmic_flops_per_call": flops,
-            "roofline": {"kernel": "attn_prefill_bf16<128, 8>", "bound": "mfma", "achieved": round(flops / dt / 1e12, 1),
+            "roofline": {"kernel": "attn_prefill_bf16<128, 8, 1, false>", "bound": "mfma", "achieved": round(flops / dt / 1e12, 1),
                          "peak": 2500.0, "unit": "TFLOP/s", "frac": round(flops / dt / 1e12 / 2500.0, 4)}}
 
 
@@ -481,7 +481,7 @@ def main() -> int:
                            "launches": "tempo_kv_append + tempo_attn_decode_causal"},
         "steps_per_s": round(args.steps / elapsed, 1),
         "roofline": {
-            "kernel": "attn_partial_bf16<128, false, 1>",
+            "kernel": "attn_partial_bf16<128, false>",
             "bound": "hbm",
             "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBS,

@@ -306,10 +306,10 @@ int tempo_rope_decode_step_window(const tempo_kv* kv, const tempo_rope* rope, co
  *   q, out   device, [batch][queries][num_q_heads][head_dim], kv->dtype
  *   t        first step of the block (uniform), or with t_per_seq the upper bound of
  *            the per-sequence first steps t_per_seq[b]
- * Limits: queries >= 1 and queries * (num_q_heads / num_kv_heads) <= 64
+ * Limits: queries >= 1 and queries * (num_q_heads / num_kv_heads) <= 128
  * (TEMPO_ERR_SHAPE otherwise): up to 16 such (step, head) columns ride in the
- * padding of the single-step kernel's tiles, 17..64 use kernels with two or four
- * column tiles per wavefront.  workspace: device, 256-byte aligned, at least
+ * padding of the single-step kernel's tiles, 17..128 use the LDS-staged kernel
+ * (eight wavefronts of 16 columns share one copy of every key/value group).  workspace: device, 256-byte aligned, at least
  * tempo_attn_block_workspace_bytes(kv, batch, num_q_heads, queries, t) bytes.
  * Other arguments, launches and errors as tempo_attn_decode_causal / _window.
  */
@@ -329,7 +329,7 @@ int tempo_attn_block_window(const tempo_kv* kv, const void* q, void* out, int32_
  * t .. t+count-1 of every sequence in ONE call.  The keys/values of those steps are
  * written to the store and every step's query attends over its own range (keys
  * 0 .. t+c, or its window), exactly as `count` single decode steps would.  Work is
- * issued in blocks of 64 / (num_q_heads / num_kv_heads) steps: per block one
+ * issued in blocks of 128 / (num_q_heads / num_kv_heads) steps: per block one
  * tempo_kv_append_block and one tempo_attn_block_* (all launches asynchronous on
  * `stream`, nothing allocated).
  *   q, out        device, [batch][count][num_q_heads][head_dim]
@@ -384,8 +384,8 @@ size_t tempo_prefill_workspace_bytes(const tempo_kv* kv, int32_t batch, int32_t 
 
 /* tempo_attn_block_causal (window = 0) or _window with the caller's plan instead of
  * the library's (for sweeping plans).  The plan must cover the union of the block's
- * ranges and satisfy the limits of tempo_attn_block_plan's results (at most 4
- * wavefronts above 32 columns, wave-merge area within 64 KiB of LDS); workspace at
+ * ranges and satisfy the limits of tempo_attn_block_plan's results (up to 16
+ * columns: wave-merge area within 64 KiB of LDS; above: waves is ignored); workspace at
  * least batch * queries * num_q_heads rows of plan->num_splits partials
  * (tempo_attn_plan_workspace_bytes with batch * queries as the batch). */
 int tempo_attn_block_with_plan(const tempo_kv* kv, const void* q, void* out, int32_t batch,

@@ -61,6 +61,15 @@ def _drop_remarks(lines):
     return out
 
 
+# Kernels whose speed depends on how many wavefronts fit a SIMD: (mangled-name
+# fragment, minimum "Occupancy [waves/SIMD]").  A source change that pushes the
+# register count over the edge fails the build instead of silently costing 30%.
+MIN_OCCUPANCY = [
+    ("attn_partial_bf16ILi128E", 3),           # decode kernel, D = 128: <= 170 VGPRs
+    ("attn_prefill_bf16ILi128ELi8ELi1E", 4),   # prompt kernel, D = 128: two workgroups of 8 per compute unit
+]
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(OBJDIR, os.path.splitext(src)[0] + ".o")
     cmd = [_hipcc()] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
@@ -69,7 +78,7 @@ def _compile(src: str) -> str:
     lines = [l for l in r.stderr.splitlines() if noise not in l]
     # Resource remarks: a kernel that falls back to scratch memory (a register array
     # the compiler could not keep in registers) is several times slower; refuse it.
-    kernel, spilled = None, []
+    kernel, spilled, crowded = None, [], []
     for l in lines:
         m = re.search(r"remark: Function Name: (\S+)", l)
         if m:
@@ -77,11 +86,18 @@ def _compile(src: str) -> str:
         m = re.search(r"remark:\s+ScratchSize \[bytes/lane\]: (\d+)", l)
         if m and int(m.group(1)) > 0:
             spilled.append(f"{kernel}: {m.group(1)} bytes/lane of scratch")
+        m = re.search(r"remark:\s+Occupancy \[waves/SIMD\]: (\d+)", l)
+        if m:
+            for frag, need in MIN_OCCUPANCY:
+                if frag in kernel and int(m.group(1)) < need:
+                    crowded.append(f"{kernel}: occupancy {m.group(1)} waves/SIMD, needs {need}")
     err = "\n".join(_drop_remarks(lines))
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{err}")
     if spilled:
         raise RuntimeError(f"{src}: kernels must not use scratch memory:\n  " + "\n  ".join(spilled))
+    if crowded:
+        raise RuntimeError(f"{src}: register use went over an occupancy edge:\n  " + "\n  ".join(crowded))
     if err.strip():
         sys.stderr.write(err + "\n")
     return obj

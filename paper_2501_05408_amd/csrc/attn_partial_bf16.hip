@@ -31,7 +31,8 @@
 // Block of queries.  The 16 columns can also hold C consecutive query steps of
 // the G heads (column = c*G + g, C*G <= 16): step t+c sees keys up to t+c (and
 // from its own window start), which is one more per-lane bound in the index mask.
-// The keys and values are still read once, now for C steps.
+// The keys and values are still read once, now for C steps.  Blocks of more than
+// 16 columns are served by the LDS-staged kernel of attn_prefill_bf16.hip.
 //
 // Rotary embedding (kRope instantiations).  q, and the k_new of a fused append,
 // arrive unrotated; the kernel turns them to their step's position with fp32
@@ -148,11 +149,8 @@ __device__ inline u32x4 rotate_fetched_key(const AttnParams& p, int pos, int lan
   return fetched;
 }
 
-// NT = column tiles per wavefront: 16 * NT columns of (query step, head) pairs.
-// NT = 1 is the decode kernel; wider blocks of queries (prompt processing) multiply
-// the MFMA work done per key/value byte read.
-template <int D, bool kRope, int NT>
-__global__ __launch_bounds__(NT <= 2 ? 512 : 256) void attn_partial_bf16(AttnParams p) {
+template <int D, bool kRope>
+__global__ __launch_bounds__(512) void attn_partial_bf16(AttnParams p) {
   constexpr int KS = D / 32;
   constexpr int DT = D / 16;
   extern __shared__ float smem[];
@@ -185,17 +183,16 @@ __global__ __launch_bounds__(NT <= 2 ? 512 : 256) void attn_partial_bf16(AttnPar
     load_values<D>(p, base, lane, g);
   }
 
-  // Columns: j = cq*G + gq for query step cq and head gq of the group; ncols = C*G <= 16*NT.
+  // Columns: j = cq*G + gq for query step cq and head gq of the group; ncols = C*G <= 16.
   const int ncols = p.queries * p.G;
-  const int tile_cols = ncols < 16 ? ncols : 16;  // columns of a full tile (only the last tile may hold fewer)
 
   // A fused append lands in group t_b>>5, which only the newest split holds; the
   // wavefront that will reach that group fetches the new rows right away.  Its LDS
   // staging area is a region of its own behind the wave-merge area.
   int grp_new = -1;
-  uint16_t* stage = reinterpret_cast<uint16_t*>(smem + nwaves * (32 + tile_cols * D));
+  uint16_t* stage = reinterpret_cast<uint16_t*>(smem + nwaves * (32 + ncols * D));
   u32x4 fetched = {0u, 0u, 0u, 0u};
-  if (NT == 1 && p.k_new && split == rg.nchunks - 1 && ((t_b >> 5) - grp) % nwaves == 0 && (t_b >> 5) >= grp) {
+  if (p.k_new && split == rg.nchunks - 1 && ((t_b >> 5) - grp) % nwaves == 0 && (t_b >> 5) >= grp) {
     grp_new = t_b >> 5;
     fetched = fetch_new_row<D>(p, b, hkv, lane);
     if (kRope) fetched = rotate_fetched_key<D>(p, t_b, lane, fetched);
@@ -210,19 +207,17 @@ __global__ __launch_bounds__(NT <= 2 ? 512 : 256) void attn_partial_bf16(AttnPar
   // keys are read, masked out of the logits and zeroed in the value operand)
   const int seen_hi = (t_b + p.queries - 1) < end ? (t_b + p.queries - 1) : end;
 
-  // Per column tile: this lane's column, its own range cut to the split, and its
-  // query operand: lane (j + 16c) holds dims 32s + 8c .. +7 of column j (0 for
-  // unused columns, which behave like the last query step).
-  int lo_col[NT], hi_col[NT];
-  u32x4 qreg[NT][KS];
-#pragma unroll
-  for (int jt = 0; jt < NT; ++jt) {
-    const int col = 16 * jt + (lane & 15);
-    const int cq = col < ncols ? col / p.G : p.queries - 1;
-    const int gq = col < ncols ? col - cq * p.G : 0;
-    hi_col[jt] = (t_b + cq) < end ? (t_b + cq) : end;
-    const int lo_q = (p.window > 0 && t_b + cq - p.window + 1 > 0) ? t_b + cq - p.window + 1 : 0;
-    lo_col[jt] = lo_q > start ? lo_q : start;
+  // This lane's column, its own range cut to the split, and its query operand: lane
+  // (j + 16c) holds dims 32s + 8c .. +7 of column j (0 for unused columns, which
+  // behave like the last query step).
+  const int col = lane & 15;
+  const int cq = col < ncols ? col / p.G : p.queries - 1;
+  const int gq = col < ncols ? col - cq * p.G : 0;
+  const int hi_col = (t_b + cq) < end ? (t_b + cq) : end;
+  const int lo_q = (p.window > 0 && t_b + cq - p.window + 1 > 0) ? t_b + cq - p.window + 1 : 0;
+  const int lo_col = lo_q > start ? lo_q : start;
+  u32x4 qreg[KS];
+  {
     const int c = lane >> 4;
     const uint16_t* qp = static_cast<const uint16_t*>(p.q) +
                          (((int64_t)b * p.io_steps + cq) * p.Hq + (int64_t)hkv * p.G + gq) * D + 8 * c;
@@ -230,179 +225,124 @@ __global__ __launch_bounds__(NT <= 2 ? 512 : 256) void attn_partial_bf16(AttnPar
     for (int s = 0; s < KS; ++s) {
       const u32x4 zero = {0u, 0u, 0u, 0u};
       const u32x4 v = *reinterpret_cast<const u32x4*>(qp + 32 * s);
-      qreg[jt][s] = col < ncols ? v : zero;
+      qreg[s] = col < ncols ? v : zero;
     }
-    if (kRope) rotate_query<D>(p, t_b + cq, lane, qreg[jt]);
   }
+  if (kRope) rotate_query<D>(p, t_b + cq, lane, qreg);
 
-  WaveState<D> st[NT];
+  WaveState<D> st;
+  st.m = -INFINITY;
+  st.l = 0.f;
 #pragma unroll
-  for (int jt = 0; jt < NT; ++jt) {
-    st[jt].m = -INFINITY;
-    st[jt].l = 0.f;
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt) st[jt].acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-  }
+  for (int dt = 0; dt < DT; ++dt) st.acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   while (grp <= g_last) {
     const int nxt = grp + nwaves;
     const bool more = nxt <= g_last;
     const int64_t base_nxt = more ? group_base<D>(p, b, hkv, nxt) : 0;  // scalar loads, off the vector path
-    if (NT == 1 && grp == grp_new) append_keys<D>(p, base, t_b, lane, fetched, stage, g);
+    if (grp == grp_new) append_keys<D>(p, base, t_b, lane, fetched, stage, g);
 
+    float x[8];
+    logits_of_group<D>(p, qreg, g, x);
+    if (more) load_keys<D>(p, base_nxt, lane, g);  // the key registers are free again
+
+    uint32_t keep[4];
     const bool cut = (grp << 5) < all_lo || (grp << 5) + 31 > all_hi;  // wave-uniform
-    bf16x8 pa[NT];
-    if (NT == 1) {
-      float x[8];
-      logits_of_group<D>(p, qreg[0], g, x);
-      if (more) load_keys<D>(p, base_nxt, lane, g);  // the key registers are free again
-      if (cut) mask_logits(grp, lo_col[0], hi_col[0], lane, x);
-      pa[0] = softmax_update<D>(x, lane, st[0]);
-    } else {
-#pragma unroll
-      for (int jt = 0; jt < NT; ++jt) {
-        float x[8];
-        logits_of_group<D>(p, qreg[jt], g, x);
-        if (cut) mask_logits(grp, lo_col[jt], hi_col[jt], lane, x);
-        pa[jt] = softmax_update<D>(x, lane, st[jt]);
-      }
-      if (more) load_keys<D>(p, base_nxt, lane, g);  // after the last tile's Q.K^T
+    if (cut) {
+      mask_logits(grp, lo_col, hi_col, lane, x);
+      value_masks(grp, start, seen_hi, lane, keep);
     }
+    const bf16x8 pa = softmax_update<D>(x, lane, st);
 
-    if (NT == 1 && grp == grp_new) append_values<D>(p, base, t_b, lane, stage, g);
-    // 0 mask under the sums: unwritten slots may hold NaN, and 0 * NaN is NaN
-    if (NT == 1) {
-      if (cut) {
-        uint32_t keep[4];
-        value_masks(grp, start, seen_hi, lane, keep);
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-          g.v[dt].x &= keep[0]; g.v[dt].y &= keep[1]; g.v[dt].z &= keep[2]; g.v[dt].w &= keep[3];
-        }
-      }
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt)
-        st[0].acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa[0], as_bf16x8(g.v[dt]), st[0].acc[dt], 0, 0, 0);
-    } else {
-      // Masked copies instead of masking the register image in place, one value unit
-      // at a time and shared by the column tiles (all-ones masks when nothing is cut).
-      // With several column tiles, hipcc 7.2 compiled the in-place form into code that
-      // reused value registers as temporaries before the products had read them.
-      uint32_t keep[4] = {~0u, ~0u, ~0u, ~0u};
-      if (cut) value_masks(grp, start, seen_hi, lane, keep);
+    if (grp == grp_new) append_values<D>(p, base, t_b, lane, stage, g);
+    if (cut) {  // 0 mask under the sums: unwritten slots may hold NaN, and 0 * NaN is NaN
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) {
-        u32x4 vv = g.v[dt];
-        vv.x &= keep[0]; vv.y &= keep[1]; vv.z &= keep[2]; vv.w &= keep[3];
-#pragma unroll
-        for (int jt = 0; jt < NT; ++jt)
-          st[jt].acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa[jt], as_bf16x8(vv), st[jt].acc[dt], 0, 0, 0);
+        g.v[dt].x &= keep[0]; g.v[dt].y &= keep[1]; g.v[dt].z &= keep[2]; g.v[dt].w &= keep[3];
       }
     }
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+      st.acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, as_bf16x8(g.v[dt]), st.acc[dt], 0, 0, 0);
     if (more) load_values<D>(p, base_nxt, lane, g);  // the value registers are free again
 
     grp = nxt;
     base = base_nxt;
   }
 
-  // Wave results -> LDS -> merge, one column tile per pass.  Columns live in
-  // lane&15 for (m, l) and in (4c + r) for acc.
+  // Wave result -> LDS.  Columns live in lane&15 for (m, l) and in (4c + r) for acc.
+  float l_tot = st.l + __shfl_xor(st.l, 16);
+  l_tot += __shfl_xor(l_tot, 32);
   float* sm_m = smem;                       // [nwaves][16]
   float* sm_l = smem + nwaves * 16;         // [nwaves][16]
-  float* sm_acc = smem + nwaves * 32;       // [nwaves][tile_cols][D]
+  float* sm_acc = smem + nwaves * 32;       // [nwaves][ncols][D]
+  if (lane < 16) {
+    sm_m[wave * 16 + lane] = st.m;
+    sm_l[wave * 16 + lane] = l_tot;
+  }
+  {
+    const int n = lane & 15, c = lane >> 4;
 #pragma unroll
-  for (int jt = 0; jt < NT; ++jt) {
-    const int cols_here = ncols - 16 * jt < 16 ? ncols - 16 * jt : 16;  // may be <= 0: nothing to do
-    if (jt > 0) __syncthreads();  // the previous pass has been read
-    if (cols_here > 0) {
-      float l_tot = st[jt].l + __shfl_xor(st[jt].l, 16);
-      l_tot += __shfl_xor(l_tot, 32);
-      if (lane < 16) {
-        sm_m[wave * 16 + lane] = st[jt].m;
-        sm_l[wave * 16 + lane] = l_tot;
-      }
-      const int n = lane & 15, c = lane >> 4;
+    for (int r = 0; r < 4; ++r) {
+      const int j = 4 * c + r;
+      if (j < ncols) {
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int j = 4 * c + r;
-        if (j < cols_here) {
-#pragma unroll
-          for (int dt = 0; dt < DT; ++dt) sm_acc[(wave * tile_cols + j) * D + 16 * dt + n] = st[jt].acc[dt][r];
-        }
+        for (int dt = 0; dt < DT; ++dt) sm_acc[(wave * ncols + j) * D + 16 * dt + n] = st.acc[dt][r];
       }
     }
-    __syncthreads();
+  }
+  __syncthreads();
 
-    // Merge the wavefronts of the workgroup (same rule the split combine uses).  A
-    // column that saw no key in this split leaves (m, l, acc) = (-inf, 0, 0).
-    for (int idx = threadIdx.x; idx < cols_here * D; idx += blockDim.x) {
-      const int j = idx / D, d = idx - j * D;
-      float M = -INFINITY;
-      for (int w = 0; w < nwaves; ++w) M = fmaxf(M, sm_m[w * 16 + j]);
-      float num = 0.f, den = 0.f;
-      for (int w = 0; w < nwaves; ++w) {
-        const float mw = sm_m[w * 16 + j];
-        if (mw == -INFINITY) continue;  // a wavefront that saw no key of this column
-        const float wgt = fast_exp2(mw - M);
-        num += wgt * sm_acc[(w * tile_cols + j) * D + d];
-        den += wgt * sm_l[w * 16 + j];
-      }
-      const int col = 16 * jt + j;
-      const int jc = col / p.G, jg = col - jc * p.G;
-      const int64_t row = ((int64_t)b * p.queries + jc) * p.Hq + (int64_t)hkv * p.G + jg;
-      if (p.direct) {
-        const int64_t orow = ((int64_t)b * p.io_steps + jc) * p.Hq + (int64_t)hkv * p.G + jg;
-        static_cast<__bf16*>(p.out)[orow * D + d] = (__bf16)(num / den);
-      } else {
-        const int64_t part = row * p.num_splits + split;
-        p.ws_acc[part * D + d] = num;
-        if (d == 0) {
-          p.ws_ml[part * 2] = M;
-          p.ws_ml[part * 2 + 1] = den;
-        }
+  // Merge the wavefronts of the workgroup (same rule the split combine uses).  A
+  // column that saw no key in this split leaves (m, l, acc) = (-inf, 0, 0).
+  for (int idx = threadIdx.x; idx < ncols * D; idx += blockDim.x) {
+    const int j = idx / D, d = idx - j * D;
+    float M = -INFINITY;
+    for (int w = 0; w < nwaves; ++w) M = fmaxf(M, sm_m[w * 16 + j]);
+    float num = 0.f, den = 0.f;
+    for (int w = 0; w < nwaves; ++w) {
+      const float mw = sm_m[w * 16 + j];
+      if (mw == -INFINITY) continue;  // a wavefront that saw no key of this column
+      const float wgt = fast_exp2(mw - M);
+      num += wgt * sm_acc[(w * ncols + j) * D + d];
+      den += wgt * sm_l[w * 16 + j];
+    }
+    const int jc = j / p.G, jg = j - jc * p.G;
+    const int64_t row = ((int64_t)b * p.queries + jc) * p.Hq + (int64_t)hkv * p.G + jg;
+    if (p.direct) {
+      const int64_t orow = ((int64_t)b * p.io_steps + jc) * p.Hq + (int64_t)hkv * p.G + jg;
+      static_cast<__bf16*>(p.out)[orow * D + d] = (__bf16)(num / den);
+    } else {
+      const int64_t part = row * p.num_splits + split;
+      p.ws_acc[part * D + d] = num;
+      if (d == 0) {
+        p.ws_ml[part * 2] = M;
+        p.ws_ml[part * 2 + 1] = den;
       }
     }
   }
 }
 
 }  // namespace
-
-// Column tiles a block of `columns` (query step, head) pairs needs: 1, 2 or 4.
-int partial_bf16_column_tiles(int columns) { return columns <= 16 ? 1 : (columns <= 32 ? 2 : 4); }
 
 size_t partial_bf16_lds_bytes(int waves, int columns, int D) {
-  const int tile_cols = columns < 16 ? columns : 16;
-  // wave-merge area of one column tile, then room for one staged key row and one value row (bf16)
-  return (size_t)waves * (32 + (size_t)tile_cols * D) * sizeof(float) + 2 * (size_t)D * sizeof(uint16_t);
+  // wave-merge area, then room for one staged key row and one value row (bf16)
+  return (size_t)waves * (32 + (size_t)columns * D) * sizeof(float) + 2 * (size_t)D * sizeof(uint16_t);
 }
 
-namespace {
-template <int D, bool kRope, int NT>
-hipError_t launch_nt(const AttnParams& p, dim3 grid, dim3 block, size_t lds, hipStream_t stream) {
-  return launch((attn_partial_bf16<D, kRope, NT>), grid, block, lds, stream, p);
-}
-}  // namespace
-
+// Up to 16 (step, head) columns; wider blocks use the LDS-staged kernel.
 hipError_t launch_partial_bf16(const AttnParams& p, int batch, int D, int grid_splits, int waves,
                                hipStream_t stream) {
+  if (p.queries * p.G > 16) return hipErrorInvalidConfiguration;
   const dim3 grid(p.Hkv, batch, grid_splits);
-  const int nt = partial_bf16_column_tiles(p.queries * p.G);
-  if (nt > 2 && waves > 4) return hipErrorInvalidConfiguration;  // the four-tile kernel is built for <= 256 threads
   const dim3 block(64 * waves);
   const size_t lds = partial_bf16_lds_bytes(waves, p.queries * p.G, D);
-  if (p.rope_cos) {  // rotary entry points answer one step per call
-    if (nt != 1) return hipErrorInvalidConfiguration;
-    if (D == 128) return launch_nt<128, true, 1>(p, grid, block, lds, stream);
-    return launch_nt<64, true, 1>(p, grid, block, lds, stream);
+  if (p.rope_cos) {
+    if (D == 128) return launch((attn_partial_bf16<128, true>), grid, block, lds, stream, p);
+    return launch((attn_partial_bf16<64, true>), grid, block, lds, stream, p);
   }
-  if (D == 128) {
-    if (nt == 1) return launch_nt<128, false, 1>(p, grid, block, lds, stream);
-    if (nt == 2) return launch_nt<128, false, 2>(p, grid, block, lds, stream);
-    return launch_nt<128, false, 4>(p, grid, block, lds, stream);
-  }
-  if (nt == 1) return launch_nt<64, false, 1>(p, grid, block, lds, stream);
-  if (nt == 2) return launch_nt<64, false, 2>(p, grid, block, lds, stream);
-  return launch_nt<64, false, 4>(p, grid, block, lds, stream);
+  if (D == 128) return launch((attn_partial_bf16<128, false>), grid, block, lds, stream, p);
+  return launch((attn_partial_bf16<64, false>), grid, block, lds, stream, p);
 }
 
 }  // namespace tempo

@@ -18,6 +18,13 @@
 // loads into registers at the top of the iteration, LDS stores at its end)
 // overlaps the arithmetic on group n; one barrier per group.
 //
+// Blocks against a long history.  The same kernel serves a block of up to 128
+// columns in front of a long key range (chunked prompt processing, speculative
+// decoding with many steps): the key range is then cut into splits as in the decode
+// kernel, one workgroup per (sequence, kv head, split) writes a partial
+// (reference, sum, accumulator) per column, and the split combine finishes.  The
+// keys/values are read from HBM once per workgroup for all its columns.
+//
 // Workgroups of one (sequence, head) are adjacent in the grid and run together, so
 // the pool is streamed from HBM about once per (sequence, head) and the blocks that
 // follow find it in the caches; the longest blocks are dispatched first.
@@ -111,7 +118,8 @@ __global__ __launch_bounds__(64 * NW, PROMPT_MIN_WAVES) void attn_prefill_bf16(A
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int QB = prefill_block_steps(p.G, NW, NT);
   const int nblocks = (p.queries + QB - 1) / QB;
-  const int qb = nblocks - 1 - (int)blockIdx.x;  // longest range first
+  const int qb = nblocks - 1 - (int)(blockIdx.x % nblocks);  // longest range first
+  const int zsplit = (int)(blockIdx.x / nblocks);             // 0 unless the key range is split
   const int hkv = blockIdx.y, b = blockIdx.z;
   const int c0 = qb * QB;                                           // first step of the block within the call
   // steps of this sequence in the call: all of them, or its own count
@@ -123,19 +131,33 @@ __global__ __launch_bounds__(64 * NW, PROMPT_MIN_WAVES) void attn_prefill_bf16(A
   if (c0 >= steps_b) return;                                        // uniform over the workgroup, before any barrier
   const int C = steps_b - c0 < QB ? steps_b - c0 : QB;             // steps in this block
   const int ncols = C * p.G;
-  const int t_first = p.t + c0, t_last = t_first + C - 1;
+  int t_base = p.t_per_seq ? ((const_i32_ptr)p.t_per_seq)[b] : p.t; // first step of the call for this sequence
+  t_base = t_base > p.t ? p.t : (t_base < 0 ? 0 : t_base);
+  const int t_first = t_base + c0, t_last = t_first + C - 1;
   const int lo = (p.window > 0 && t_first - p.window + 1 > 0) ? t_first - p.window + 1 : 0;
-  const int g_first = lo >> 5, g_last = t_last >> 5;
+  // The split of the key range this workgroup walks (the whole range when not split:
+  // tps_log2 = 30), newest split first as in the decode kernel.
+  const int chunk0 = lo >> p.tps_log2;
+  const int nchunks = (t_last >> p.tps_log2) - chunk0 + 1;
+  if (zsplit >= nchunks) return;                                    // uniform over the workgroup
+  const int split = nchunks - 1 - zsplit;
+  const int cs = (chunk0 + split) << p.tps_log2, ce = cs + ((1 << p.tps_log2) - 1);
+  const int start = lo > cs ? lo : cs;
+  const int end = t_last < ce ? t_last : ce;
+  const int g_first = start >> 5, g_last = end >> 5;
 
-  // wavefront-uniform bounds over this wavefront's 16 * NT columns: the groups it has
-  // any work in, and those no column cuts
+  // wavefront-uniform bounds over this wavefront's 16 * NT columns, cut to the split:
+  // the groups it has any work in, and those no column cuts
   const int first_col = 16 * NT * wave;
   const int last_col = (first_col + 16 * NT - 1) < ncols - 1 ? (first_col + 16 * NT - 1) : ncols - 1;
   const bool idle = first_col >= ncols;                             // a wavefront beyond the block's columns
-  const int w_hi = t_first + (idle ? 0 : last_col / p.G);           // newest key any of its columns sees
-  const int w_hi_min = t_first + (idle ? 0 : first_col / p.G);      // newest key ALL of its columns see
-  const int w_lo_first = (p.window > 0 && w_hi_min - p.window + 1 > 0) ? w_hi_min - p.window + 1 : 0;
-  const int w_lo_last = (p.window > 0 && w_hi - p.window + 1 > 0) ? w_hi - p.window + 1 : 0;
+  const int own_hi = t_first + (idle ? 0 : last_col / p.G);         // newest key any of its columns sees
+  const int own_hi_min = t_first + (idle ? 0 : first_col / p.G);    // newest key ALL of its columns see
+  const int own_lo_first = (p.window > 0 && own_hi_min - p.window + 1 > 0) ? own_hi_min - p.window + 1 : 0;
+  const int own_lo_last = (p.window > 0 && own_hi - p.window + 1 > 0) ? own_hi - p.window + 1 : 0;
+  const int w_hi = own_hi < end ? own_hi : end, w_hi_min = own_hi_min < end ? own_hi_min : end;
+  const int w_lo_first = own_lo_first > start ? own_lo_first : start;
+  const int w_lo_last = own_lo_last > start ? own_lo_last : start;
 
   // Per column tile: this lane's column (unused columns behave like the block's last
   // step with q = 0), its range, its query operand, its softmax state.
@@ -149,8 +171,10 @@ __global__ __launch_bounds__(64 * NW, PROMPT_MIN_WAVES) void attn_prefill_bf16(A
     const int col = first_col + 16 * jt + (lane & 15);
     const int cq = col < ncols ? col / p.G : C - 1;
     const int gq = col < ncols ? col - cq * p.G : 0;
-    hi_col[jt] = t_first + cq;
-    lo_col[jt] = (p.window > 0 && hi_col[jt] - p.window + 1 > 0) ? hi_col[jt] - p.window + 1 : 0;
+    const int step = t_first + cq;             // the column's own step: its newest key and its position
+    hi_col[jt] = step < end ? step : end;
+    const int lo_own = (p.window > 0 && step - p.window + 1 > 0) ? step - p.window + 1 : 0;
+    lo_col[jt] = lo_own > start ? lo_own : start;
     const int c = lane >> 4;
     const uint16_t* qp = static_cast<const uint16_t*>(p.q) +
                          (((int64_t)b * p.io_steps + c0 + cq) * p.Hq + (int64_t)hkv * p.G + gq) * D + 8 * c;
@@ -160,7 +184,7 @@ __global__ __launch_bounds__(64 * NW, PROMPT_MIN_WAVES) void attn_prefill_bf16(A
       const u32x4 v = *reinterpret_cast<const u32x4*>(qp + 32 * s);
       qreg[jt][s] = col < ncols ? v : zero;
     }
-    if (kRope) rotate_query<D>(p, hi_col[jt], lane, qreg[jt]);  // queries arrive unrotated; hi_col is the column's own step
+    if (kRope) rotate_query<D>(p, step, lane, qreg[jt]);  // queries arrive unrotated
     m_run[jt] = -INFINITY;
     acc_l[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -208,7 +232,7 @@ __global__ __launch_bounds__(64 * NW, PROMPT_MIN_WAVES) void attn_prefill_bf16(A
 
     // Has this wavefront anything to do in this group?  (Uniform over the wavefront.)
     const int j0 = grp << 5;
-    if (!idle && j0 <= w_hi && j0 + 31 >= (p.window > 0 ? w_lo_first : 0)) {
+    if (!idle && j0 <= w_hi && j0 + 31 >= w_lo_first) {
       const u32x4* src = lds + buf * UNITS * 64 + lane;
       const bool cut = j0 < w_lo_last || j0 + 31 > w_hi_min;
       bf16x8 pa[NT];
@@ -245,7 +269,10 @@ __global__ __launch_bounds__(64 * NW, PROMPT_MIN_WAVES) void attn_prefill_bf16(A
     __syncthreads();           // group n+1 is in LDS; group n's buffer may be overwritten next time
   }
 
-  // Every column saw its own key, so its sum is > 0.  Columns (4c + r) of acc, value dims 16dt + n.
+  // Columns (4c + r) of acc, value dims 16dt + n.  Whole range: every column saw its own
+  // key, so its sum is > 0 and the output is acc / sum.  One split of the range: the
+  // column's partial (reference, sum, accumulator) goes to the workspace; a column
+  // that saw no key in this split leaves (-inf, 0, 0).
   const int n = lane & 15, c = lane >> 4;
 #pragma unroll
   for (int jt = 0; jt < NT; ++jt) {
@@ -253,13 +280,25 @@ __global__ __launch_bounds__(64 * NW, PROMPT_MIN_WAVES) void attn_prefill_bf16(A
     for (int r = 0; r < 4; ++r) {
       const int j = first_col + 16 * jt + 4 * c + r;
       const float l_j = acc_l[jt][r];
+      const float ref_j = __shfl(m_run[jt], 4 * c + r);  // the reference lives in lane (column & 15)
       if (j < ncols) {
         const int jc = j / p.G, jg = j - jc * p.G;
-        __bf16* orow = static_cast<__bf16*>(p.out) +
-                       (((int64_t)b * p.io_steps + c0 + jc) * p.Hq + (int64_t)hkv * p.G + jg) * D;
-        const float inv = 1.0f / l_j;
+        if (p.direct) {
+          __bf16* orow = static_cast<__bf16*>(p.out) +
+                         (((int64_t)b * p.io_steps + c0 + jc) * p.Hq + (int64_t)hkv * p.G + jg) * D;
+          const float inv = 1.0f / l_j;
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) orow[16 * dt + n] = (__bf16)(acc[jt][dt][r] * inv);
+          for (int dt = 0; dt < DT; ++dt) orow[16 * dt + n] = (__bf16)(acc[jt][dt][r] * inv);
+        } else {
+          const int64_t row = ((int64_t)b * p.queries + c0 + jc) * p.Hq + (int64_t)hkv * p.G + jg;
+          const int64_t part = row * p.num_splits + split;
+#pragma unroll
+          for (int dt = 0; dt < DT; ++dt) p.ws_acc[part * D + 16 * dt + n] = acc[jt][dt][r];
+          if (n == 0) {
+            p.ws_ml[part * 2] = ref_j;
+            p.ws_ml[part * 2 + 1] = l_j;
+          }
+        }
       }
     }
   }
@@ -267,16 +306,20 @@ __global__ __launch_bounds__(64 * NW, PROMPT_MIN_WAVES) void attn_prefill_bf16(A
 
 }  // namespace
 
-// The instantiation in use: wavefronts per workgroup and column tiles per wavefront.
+// The prompt path uses kPromptWaves wavefronts of kPromptTiles tiles; a single block
+// of fewer columns gets a workgroup of just enough wavefronts (2, 4 or 8), so that
+// several workgroups share a compute unit and the kernel stays bound by HBM.
 constexpr int kPromptWaves = PROMPT_NW, kPromptTiles = PROMPT_NT;
 
 int prefill_bf16_block_steps(int G) { return prefill_block_steps(G, kPromptWaves, kPromptTiles); }
 
-hipError_t launch_prefill_bf16(const AttnParams& p, int batch, int D, hipStream_t stream) {
-  constexpr int NW = kPromptWaves, NT = kPromptTiles;
+namespace {
+template <int NW>
+hipError_t launch_prefill_nw(const AttnParams& p, int batch, int D, int grid_splits, hipStream_t stream) {
+  constexpr int NT = kPromptTiles;
   const int QB = prefill_block_steps(p.G, NW, NT);
   const int nblocks = (p.queries + QB - 1) / QB;
-  const dim3 grid(nblocks, p.Hkv, batch);
+  const dim3 grid(nblocks * grid_splits, p.Hkv, batch);
   const dim3 block(64 * NW);
   const size_t lds = 2 * (size_t)(2 * (D / 32) + D / 16) * 1024;
   if (p.rope_cos) {
@@ -285,6 +328,16 @@ hipError_t launch_prefill_bf16(const AttnParams& p, int batch, int D, hipStream_
   }
   if (D == 128) return launch((attn_prefill_bf16<128, NW, NT, false>), grid, block, lds, stream, p);
   return launch((attn_prefill_bf16<64, NW, NT, false>), grid, block, lds, stream, p);
+}
+}  // namespace
+
+// grid_splits: splits of the key range to launch (1 = every workgroup walks its
+// block's whole range and writes `out`; p.tps_log2 must then be 30).
+hipError_t launch_prefill_bf16(const AttnParams& p, int batch, int D, int grid_splits, hipStream_t stream) {
+  const int columns = p.queries * p.G;
+  if (kPromptTiles == 1 && columns <= 32) return launch_prefill_nw<2>(p, batch, D, grid_splits, stream);
+  if (kPromptTiles == 1 && columns <= 64) return launch_prefill_nw<4>(p, batch, D, grid_splits, stream);
+  return launch_prefill_nw<kPromptWaves>(p, batch, D, grid_splits, stream);
 }
 
 }  // namespace tempo

@@ -48,10 +48,10 @@ int check_heads(const tempo_kv* kv, int32_t batch, int32_t Hq) {
   return TEMPO_OK;
 }
 
-// A block of C consecutive query steps shares the columns of the bf16 kernel's
-// tiles with the query group: C * (Hq / Hkv) <= 64, up to four tiles of 16 columns
-// per wavefront (the same limit for fp32).
-constexpr int kMaxColumns = 64;
+// A block of C consecutive query steps: its C * (Hq / Hkv) (step, head) columns
+// either ride in the 16-column tile of the decode kernel or, up to 128, are spread
+// over the eight wavefronts of the LDS-staged kernel (the same limit for fp32).
+constexpr int kMaxColumns = 128;
 int check_queries(const tempo_kv* kv, int32_t Hq, int32_t queries) {
   if (queries < 1 || queries > kMaxColumns) return TEMPO_ERR_SHAPE;
   if ((int64_t)queries * (Hq / kv->num_kv_heads) > kMaxColumns) return TEMPO_ERR_SHAPE;
@@ -297,8 +297,8 @@ int check_attn(const tempo_kv* kv, int32_t batch, int32_t Hq, int32_t t, int32_t
   if ((rc = check_plan(plan, t, window, ragged, queries, pad_t)) != TEMPO_OK) return rc;
   if (kv->dtype == TEMPO_BF16) {
     const int columns = queries * (Hq / kv->num_kv_heads);
-    if (partial_bf16_lds_bytes(plan->waves, columns, kv->head_dim) > kMaxLds) return TEMPO_ERR_SHAPE;
-    if (partial_bf16_column_tiles(columns) > 2 && plan->waves > 4) return TEMPO_ERR_SHAPE;
+    // more than 16 columns go to the LDS-staged kernel, whose launch shape is fixed
+    if (columns <= 16 && partial_bf16_lds_bytes(plan->waves, columns, kv->head_dim) > kMaxLds) return TEMPO_ERR_SHAPE;
   }
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return TEMPO_ERR_WORKSPACE;
   if (workspace_bytes < plan_bytes(kv, (int64_t)batch * queries * Hq, plan->num_splits)) return TEMPO_ERR_WORKSPACE;
@@ -322,6 +322,8 @@ int do_partial(const tempo_kv* kv, const void* q, const void* k_new, const void*
     p.rope_sin = rope->sin;
   }
   const int32_t gs = grid_splits(plan, t, t_per_seq, window, queries, pad_t);
+  if (kv->dtype == TEMPO_BF16 && queries * p.G > 16)  // a wide block: the LDS-staged kernel, key range split as planned
+    return launch_status(launch_prefill_bf16(p, batch, kv->head_dim, gs, stream), "attn_block_partial");
   const hipError_t e = kv->dtype == TEMPO_BF16
                            ? launch_partial_bf16(p, batch, kv->head_dim, gs, plan->waves, stream)
                            : launch_partial_f32(p, batch, kv->head_dim, gs, plan->waves, stream);
@@ -346,9 +348,24 @@ void make_block_plan(const tempo_kv* kv, int32_t batch, int32_t Hq, int32_t t, i
   make_plan(kv, batch, Hq, last_step(t, queries), union_window(window, queries), ragged, plan);
   if (kv->dtype != TEMPO_BF16) return;
   const int columns = queries * (Hq / kv->num_kv_heads);
-  // the kernel for four column tiles keeps four tiles of accumulators in registers
-  // and is built for workgroups of at most four wavefronts
-  if (partial_bf16_column_tiles(columns) > 2 && plan->waves > 4) plan->waves = 4;
+  if (columns > 16) {
+    // The LDS-staged kernel: its workgroups do more arithmetic per key than the decode
+    // kernel's, so two per compute unit are wanted (measured at batch 16 x 8 heads,
+    // t = 4095: 4 splits of 1024 keys 62-79 us for 30-126 columns, 2 splits 80-82 us).
+    // Longest split length of at least 256 keys that gives >= 512 workgroups, else 256.
+    const int32_t t_eff = last_step(t, queries), w_eff = union_window(window, queries);
+    const int64_t pairs = (int64_t)batch * kv->num_kv_heads;
+    int k = 8;
+    for (int cand = 30; cand >= 8; --cand) {
+      if (pairs * splits_bound(t_eff, w_eff, cand) >= 2 * kComputeUnits) { k = cand; break; }
+    }
+    while (splits_bound(t_eff, w_eff, k) > kMaxSplits) ++k;
+    if (ragged && k > 10 && splits_bound(t_eff, w_eff, 10) <= kMaxSplits) k = 10;  // as for single steps
+    plan->tokens_per_split = 1 << k;
+    plan->num_splits = splits_bound(t_eff, w_eff, k);
+    plan->waves = 8;  // ignored: the launch picks 2, 4 or 8 wavefronts by the column count
+    return;
+  }
   while (plan->waves > 1 && partial_bf16_lds_bytes(plan->waves, columns, kv->head_dim) > kMaxLds) plan->waves /= 2;
 }
 
@@ -682,14 +699,15 @@ static int prefill(const tempo_kv* kv, const void* q, const void* k_new, const v
     }
     if ((rc = launch_status(launch_append(sp, k_new, v_new, kv->head_dim, kv->dtype, s), "kv_append_block")) != TEMPO_OK)
       return rc;
-    const tempo_plan unused = {32, 1, 1};
-    AttnParams p = attn_params(kv, q, out, Hq, t, nullptr, window, scale, &unused, workspace, batch, count);
+    const tempo_plan whole = {1 << 30, 1, 8};  // no split of the key range: every workgroup walks its block's own
+    AttnParams p = attn_params(kv, q, out, Hq, t, nullptr, window, scale, &whole, workspace, batch, count);
+    p.direct = 1;
     p.count_per_seq = count_per_seq;
     if (rope) {
       p.rope_cos = rope->cos;
       p.rope_sin = rope->sin;
     }
-    return launch_status(launch_prefill_bf16(p, batch, kv->head_dim, s), "attn_prefill");
+    return launch_status(launch_prefill_bf16(p, batch, kv->head_dim, 1, s), "attn_prefill");
   }
 
   // Otherwise block by block: split-KV partial attention keeps the part busy when the

@@ -145,10 +145,9 @@ hipError_t launch_gather(const StoreParams& p, void* k_out, void* v_out, int D, 
                          int count, hipStream_t stream);
 hipError_t launch_partial_bf16(const AttnParams& p, int batch, int D, int grid_splits, int waves,
                                hipStream_t stream);
-int partial_bf16_column_tiles(int columns);                        // 1, 2 or 4 tiles of 16 columns
 size_t partial_bf16_lds_bytes(int waves, int columns, int D);      // dynamic LDS of that launch
 int prefill_bf16_block_steps(int G);                               // query steps per workgroup of the prompt kernel
-hipError_t launch_prefill_bf16(const AttnParams& p, int batch, int D, hipStream_t stream);
+hipError_t launch_prefill_bf16(const AttnParams& p, int batch, int D, int grid_splits, hipStream_t stream);
 hipError_t launch_partial_f32(const AttnParams& p, int batch, int D, int grid_splits, int waves,
                               hipStream_t stream);
 

@@ -107,9 +107,10 @@ def test_block_fp32_every_start(window, C):
 # range misses a split; both combine kernels), pool poisoned beyond the last step.
 # ----------------------------------------------------------------------------
 @pytest.mark.parametrize("G,C,D", [(3, 5, 128), (1, 16, 128), (4, 4, 64), (2, 3, 128), (16, 1, 64), (5, 3, 128),
-                                   # more than 16 columns: two and four column tiles per wavefront
+                                   # more than 16 columns: the LDS-staged kernel, up to 128 columns
                                    (3, 10, 128), (3, 21, 128), (1, 64, 64), (4, 16, 128), (2, 9, 64), (16, 4, 128),
-                                   (1, 17, 128), (5, 7, 64)])
+                                   (1, 17, 128), (5, 7, 64), (3, 42, 128), (1, 128, 64), (4, 32, 128), (16, 8, 64),
+                                   (2, 33, 128)])
 @pytest.mark.parametrize("window", [0, 1, 2, 33, 64, 65, 200])
 def test_block_bf16_every_start(G, C, D, window):
     B, Hkv, Z, steps = 1, 2, 64, 700
@@ -194,11 +195,11 @@ def test_block_on_ring_store_bf16():
 
 
 # ----------------------------------------------------------------------------
-# Full-size Llama shape: blocks of 5 steps (5 x 3 heads = 15 of the 16 columns)
-# and of 21 steps (63 columns, four column tiles), including blocks that straddle
-# the planner's split boundary at key 2048.
+# Full-size Llama shape: blocks of 5 steps (5 x 3 heads = 15 of the 16 columns),
+# of 21 and of 42 steps (63 and 126 columns, the LDS-staged kernel), including blocks
+# that straddle the planner's split boundary at key 2048.
 # ----------------------------------------------------------------------------
-@pytest.mark.parametrize("C", [5, 21])
+@pytest.mark.parametrize("C", [5, 21, 42])
 def test_llama_shape_block_bf16_full_size(C):
     B, Hq, Hkv, D, Z, T_len = 16, 24, 8, 128, 256, 4096
     dtype = T.TEMPO_BF16

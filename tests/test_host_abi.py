@@ -122,7 +122,7 @@ def test_block_plan_fits_its_workspace_bound_and_lds():
     D = 128
     for dtype, Hq, Hkv in ((T.TEMPO_BF16, 24, 8), (T.TEMPO_BF16, 16, 1), (T.TEMPO_BF16, 2, 2), (T.TEMPO_F32, 8, 2)):
         G = Hq // Hkv
-        for queries in sorted({1, min(2, 64 // G), 16 // G, 32 // G, 64 // G}):
+        for queries in sorted({1, min(2, 128 // G), 16 // G, 32 // G, 128 // G}):
             for batch in (1, 16, 64):
                 for max_t in (0, 40, 4095, 70000):
                     kv = kv_desc(dtype, D=D, Hkv=Hkv, Z=64, max_blocks=(max_t + queries) // 64 + 1)
@@ -139,12 +139,13 @@ def test_block_plan_fits_its_workspace_bound_and_lds():
                                 need = -(-rows * plan.num_splits * 8 // 256) * 256 + \
                                     -(-rows * plan.num_splits * D * 4 // 256) * 256
                                 assert need <= bound
-                                if dtype == T.TEMPO_BF16:   # wave-merge area + staged rows within 64 KiB
-                                    assert plan.waves * (32 + min(16, queries * G) * D) * 4 + 4 * D <= 65536
-                                    assert queries * G <= 32 or plan.waves <= 4
+                                if dtype == T.TEMPO_BF16 and queries * G <= 16:   # wave-merge area + staged rows within 64 KiB
+                                    assert plan.waves * (32 + queries * G * D) * 4 + 4 * D <= 65536
+                                elif dtype == T.TEMPO_BF16:                       # the LDS-staged kernel's fixed shape
+                                    assert plan.waves == 8
     with pytest.raises(T.TempoError):
-        T.tempo_attn_block_plan(kv_desc(T.TEMPO_BF16, Hkv=2), 1, 8, 17, 10)     # 17 x 4 columns > 64
-    assert T.tempo_attn_block_workspace_bytes(kv_desc(T.TEMPO_BF16, Hkv=2), 1, 8, 17, 10) == 0
+        T.tempo_attn_block_plan(kv_desc(T.TEMPO_BF16, Hkv=2), 1, 8, 33, 10)     # 33 x 4 columns > 128
+    assert T.tempo_attn_block_workspace_bytes(kv_desc(T.TEMPO_BF16, Hkv=2), 1, 8, 33, 10) == 0
     assert T.tempo_attn_block_workspace_bytes(kv_desc(T.TEMPO_BF16, Hkv=2), 1, 8, 0, 10) == 0
 
 
@@ -210,8 +211,8 @@ def test_bad_arguments_are_refused_before_any_launch():
         return lib.tempo_attn_block_window(ctypes.byref(kv), fake, fake, 2, Hq, queries, t, None, w, 0.1, None, 0, None)
 
     assert block(good, 0) == T.TEMPO_ERR_SHAPE
-    assert block(good, 22) == T.TEMPO_ERR_SHAPE                  # 22 steps x 3 heads > 64 columns
-    assert block(good, 21) == T.TEMPO_ERR_WORKSPACE              # 63 columns: four column tiles
+    assert block(good, 43) == T.TEMPO_ERR_SHAPE                  # 43 steps x 3 heads > 128 columns
+    assert block(good, 42) == T.TEMPO_ERR_WORKSPACE              # 126 columns: the LDS-staged kernel
     assert block(good, 5) == T.TEMPO_ERR_WORKSPACE               # everything else is fine
     assert block(good, 5, t=4 * 64 - 5) == T.TEMPO_ERR_WORKSPACE  # last step is the store's last slot
     assert block(good, 5, t=4 * 64 - 4) == T.TEMPO_ERR_RANGE     # last step needs a fifth block
@@ -278,7 +279,7 @@ def test_bad_arguments_are_refused_before_any_launch():
     f32_store = kv_desc(T.TEMPO_F32)   # per-sequence prompt lengths: bf16 linear stores only
     assert lib.tempo_prefill_causal(ctypes.byref(f32_store), fake, fake, fake, fake, 2, 6, 0, 10, fake, 0.1,
                                     fake << 4, 1 << 30, None) == T.TEMPO_ERR_SHAPE
-    assert T.tempo_prefill_workspace_bytes(good, 2, 6, 255) >= T.tempo_attn_block_workspace_bytes(good, 2, 6, 21, 255)
+    assert T.tempo_prefill_workspace_bytes(good, 2, 6, 255) >= T.tempo_attn_block_workspace_bytes(good, 2, 6, 42, 255)
 
     bad_plan = T.tempo_plan(48, 1, 1)
     assert lib.tempo_attn_decode_partial(ctypes.byref(good), fake, None, None, 2, 6, 5, None, 0, 0.1,
