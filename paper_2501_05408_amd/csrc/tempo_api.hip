@@ -388,6 +388,15 @@ int decode(const tempo_kv* kv, const void* q, const void* k_new, const void* v_n
                        pad_t)) != TEMPO_OK)
     return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  // With more (sequence, head) pairs than compute units the in-kernel block-store write
+  // costs more than a launch of its own (measured at 512 pairs: +7.5 us inside the
+  // attention kernel, +4 us as a separate launch; at 128 pairs +1 us inside): write first.
+  if (k_new && !rope && kv->dtype == TEMPO_BF16 && (int64_t)batch * kv->num_kv_heads > kComputeUnits) {
+    const StoreParams sp = store_params(kv, batch, t, t_per_seq);
+    if ((rc = launch_status(launch_append(sp, k_new, v_new, kv->head_dim, kv->dtype, s), "kv_append")) != TEMPO_OK)
+      return rc;
+    k_new = v_new = nullptr;
+  }
   rc = do_partial(kv, q, k_new, v_new, out, batch, Hq, t, t_per_seq, window, scale, &plan, workspace, s, queries,
                   rope, pad_t);
   if (rc != TEMPO_OK || plan.num_splits == 1) return rc;  // a single split wrote `out` itself
