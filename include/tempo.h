@@ -38,7 +38,10 @@
  *
  * Supported shapes: head_dim in {64, 128}; block_size a power of two, >= 32
  * for bf16 and >= 4 for f32; num_q_heads a multiple of num_kv_heads with a
- * group of at most 16 query heads per key/value head.
+ * group of at most 128 query heads per key/value head (bf16: a group of up to
+ * 16 heads is served by the single-step kernel, which can write the step's
+ * key/value itself; a larger group by the LDS-staged kernel of the block entry
+ * points, with the store written by a launch of its own first).
  */
 #ifndef TEMPO_H
 #define TEMPO_H
@@ -420,12 +423,13 @@ int tempo_kv_append_block(const tempo_kv* kv, const void* k_new, const void* v_n
  * Partial attention and split combine as two separate launches, with an explicit
  * plan (for profiling one kernel at a time and for sweeping plans).  window = 0
  * is causal.  k_new / v_new are both NULL (the pool already holds step t) or both
- * set (step t is appended by this launch, as in tempo_decode_step_*).
+ * set (step t is appended by this launch, as in tempo_decode_step_*; bf16 groups
+ * of more than 16 query heads: TEMPO_ERR_SHAPE, write the store first).
  * tempo_attn_decode_partial writes one (max, sum, accumulator)
  * partial per (sequence, query head, non-empty split) into workspace
  * (Section 4.3: per-tile reductions under -inf / 0 masks);
- * tempo_attn_decode_combine sums the partials into out (Section 4.3: "sums
- * together each masked attention tile").  plan->num_splits must cover the range
+ * tempo_attn_decode_combine adds the per-tile partial results up into out (the
+ * final summation over masked tiles of Section 4.3).  plan->num_splits must cover the range
  * of step t, at least (t div tps) - (lo div tps) + 1 splits, and with t_per_seq
  * the range of any step up to t (what tempo_attn_plan returns).
  */

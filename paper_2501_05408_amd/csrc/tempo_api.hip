@@ -41,17 +41,19 @@ int check_store(const tempo_kv* kv) {
   return TEMPO_OK;
 }
 
-int check_heads(const tempo_kv* kv, int32_t batch, int32_t Hq) {
-  if (batch < 1 || batch > 65535) return TEMPO_ERR_SHAPE;
-  if (Hq < 1 || Hq % kv->num_kv_heads != 0) return TEMPO_ERR_SHAPE;
-  if (Hq / kv->num_kv_heads > 16 || Hq > 65535) return TEMPO_ERR_SHAPE;
-  return TEMPO_OK;
-}
-
 // A block of C consecutive query steps: its C * (Hq / Hkv) (step, head) columns
 // either ride in the 16-column tile of the decode kernel or, up to 128, are spread
 // over the eight wavefronts of the LDS-staged kernel (the same limit for fp32).
+// A single step of a group of more than 16 query heads is such a block of one step.
 constexpr int kMaxColumns = 128;
+
+int check_heads(const tempo_kv* kv, int32_t batch, int32_t Hq) {
+  if (batch < 1 || batch > 65535) return TEMPO_ERR_SHAPE;
+  if (Hq < 1 || Hq % kv->num_kv_heads != 0) return TEMPO_ERR_SHAPE;
+  if (Hq / kv->num_kv_heads > kMaxColumns || Hq > 65535) return TEMPO_ERR_SHAPE;
+  return TEMPO_OK;
+}
+
 int check_queries(const tempo_kv* kv, int32_t Hq, int32_t queries) {
   if (queries < 1 || queries > kMaxColumns) return TEMPO_ERR_SHAPE;
   if ((int64_t)queries * (Hq / kv->num_kv_heads) > kMaxColumns) return TEMPO_ERR_SHAPE;
@@ -391,10 +393,15 @@ int decode(const tempo_kv* kv, const void* q, const void* k_new, const void* v_n
   // With more (sequence, head) pairs than compute units the in-kernel block-store write
   // costs more than a launch of its own (measured at 512 pairs: +7.5 us inside the
   // attention kernel, +4 us as a separate launch; at 128 pairs +1 us inside): write first.
-  if (k_new && !rope && kv->dtype == TEMPO_BF16 && (int64_t)batch * kv->num_kv_heads > kComputeUnits) {
+  // A group of more than 16 query heads runs in the LDS-staged kernel, which reads the
+  // store only: the write (rotating the key when tables are given) goes first there too,
+  // and the kernel rotates the queries.
+  const bool wide = kv->dtype == TEMPO_BF16 && queries * (Hq / kv->num_kv_heads) > 16;
+  if (k_new && kv->dtype == TEMPO_BF16 && (wide || (!rope && (int64_t)batch * kv->num_kv_heads > kComputeUnits))) {
     const StoreParams sp = store_params(kv, batch, t, t_per_seq);
-    if ((rc = launch_status(launch_append(sp, k_new, v_new, kv->head_dim, kv->dtype, s), "kv_append")) != TEMPO_OK)
-      return rc;
+    const hipError_t e = rope ? launch_rope_append(sp, rope->cos, rope->sin, k_new, v_new, kv->head_dim, kv->dtype, s)
+                              : launch_append(sp, k_new, v_new, kv->head_dim, kv->dtype, s);
+    if ((rc = launch_status(e, "kv_append")) != TEMPO_OK) return rc;
     k_new = v_new = nullptr;
   }
   rc = do_partial(kv, q, k_new, v_new, out, batch, Hq, t, t_per_seq, window, scale, &plan, workspace, s, queries,
@@ -453,7 +460,7 @@ int tempo_attn_plan(const tempo_kv* kv, int32_t batch, int32_t num_q_heads, int3
   if (!plan) return TEMPO_ERR_NULL;
   if ((rc = check_heads(kv, batch, num_q_heads)) != TEMPO_OK) return rc;
   if (t_max < 0 || window < 0) return TEMPO_ERR_RANGE;
-  make_plan(kv, batch, num_q_heads, t_max, window, ragged != 0, plan);
+  make_block_plan(kv, batch, num_q_heads, t_max, window, ragged != 0, 1, plan);
   return TEMPO_OK;
 }
 
@@ -835,6 +842,8 @@ int tempo_attn_decode_partial(const tempo_kv* kv, const void* q, const void* k_n
   if (rc != TEMPO_OK) return rc;
   if (!q || ((k_new == nullptr) != (v_new == nullptr))) return TEMPO_ERR_NULL;
   if ((rc = check_attn(kv, batch, num_q_heads, t, window, t_per_seq != nullptr, plan, workspace, workspace_bytes)) != TEMPO_OK) return rc;
+  // the kernel that serves a group of more than 16 heads does not write the store
+  if (k_new && kv->dtype == TEMPO_BF16 && num_q_heads / kv->num_kv_heads > 16) return TEMPO_ERR_SHAPE;
   return do_partial(kv, q, k_new, v_new, nullptr, batch, num_q_heads, t, t_per_seq, window, scale, plan,
                     workspace, static_cast<hipStream_t>(stream));
 }

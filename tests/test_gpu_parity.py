@@ -147,7 +147,7 @@ def test_bf16_every_step_causal_and_window(window):
 
 @pytest.mark.parametrize("dtype", [T.TEMPO_BF16, T.TEMPO_F32])
 @pytest.mark.parametrize("D", [64, 128])
-@pytest.mark.parametrize("G", [1, 2, 3, 4, 5, 8, 16])
+@pytest.mark.parametrize("G", [1, 2, 3, 4, 5, 8, 16, 17, 24, 32, 71, 128])
 def test_group_sizes_and_head_dims(dtype, D, G):
     B, Hkv, Z, steps = 2, 2, 32, 140
     Hq = Hkv * G

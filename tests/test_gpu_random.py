@@ -27,7 +27,7 @@ def config(case):
     r = draw(1000 + case, 12, 0, 1 << 20)
     dtype = T.TEMPO_BF16 if r[0] % 4 else T.TEMPO_F32
     D = (64, 128)[r[1] % 2]
-    G = (1, 2, 3, 4, 5, 8, 16)[r[2] % 7]
+    G = (1, 2, 3, 4, 5, 8, 16, 20, 40)[r[2] % 9]
     Hkv = (1, 2, 3)[r[3] % 3]
     B = 1 + r[4] % 5
     Z = (32, 64, 128)[r[5] % 3] if dtype == T.TEMPO_BF16 else (4, 8, 32, 64)[r[5] % 4]

@@ -137,6 +137,53 @@ def test_fused_rope_step_every_step(dtype, window, D):
 
 
 # ----------------------------------------------------------------------------
+# Groups of more than 16 query heads per key/value head (multi-query layouts): the
+# step entry points write the store with a launch of their own and answer through
+# the LDS-staged kernel.  Same checks as above, plus the plain fused step.
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", [T.TEMPO_BF16, T.TEMPO_F32])
+@pytest.mark.parametrize("G,window", [(24, 0), (32, 45), (71, 0), (128, 70)])
+def test_large_group_steps_every_step(dtype, G, window):
+    B, Hkv, D, Z, steps = 2, 2, 128, 32, 150
+    Hq = Hkv * G
+    q, K, V = host_inputs(57 + G, B, steps, Hq, Hkv, D, dtype)
+    cos_t, sin_t = tables(steps, D)
+    table, nb = random_table(57, B, steps // Z + 1)
+    fused = BlockStore(B, Hq, Hkv, D, Z, steps - 1, dtype, num_blocks=nb, block_table=table, fill="nan")
+    plain = BlockStore(B, Hq, Hkv, D, Z, steps - 1, dtype, num_blocks=nb, block_table=table, fill="nan")
+    unrot = BlockStore(B, Hq, Hkv, D, Z, steps - 1, dtype, num_blocks=nb, block_table=table, fill="nan")
+    fused.set_rope(cos_t, sin_t)
+    plain.set_rope(cos_t, sin_t)
+    qd, Kd, Vd = dev(q, dtype), dev(K, dtype), dev(V, dtype)
+    out_f = torch.empty((steps, B, Hq, D), dtype=TDT[dtype], device=DEV)
+    out_p = torch.empty_like(out_f)
+    out_u = torch.empty_like(out_f)
+    for t in range(steps):
+        k, v = Kd[:, t].contiguous(), Vd[:, t].contiguous()
+        fused.rope_step(qd[t], k, v, out_f[t], t, window)
+        plain.rope_append(k, v, t)
+        qr = plain.rope_rotate(qd[t], torch.empty_like(qd[t]), t)
+        if window:
+            plain.attend_window(qr, out_p[t], t, window)
+            unrot.step_window(qd[t], k, v, out_u[t], t, window)
+        else:
+            plain.attend_causal(qr, out_p[t], t)
+            unrot.step_causal(qd[t], k, v, out_u[t], t)
+    torch.cuda.synchronize()
+    assert torch.equal(fused.k_pool.view(torch.uint8), plain.k_pool.view(torch.uint8))
+    assert torch.equal(fused.v_pool.view(torch.uint8), plain.v_pool.view(torch.uint8))
+    assert torch.equal(out_f.view(torch.uint8), out_p.view(torch.uint8))
+    qr64, Kr64 = oracle_rotated_kv(q, K, dtype)
+    K64, V64 = K.astype(np.float64), V.astype(np.float64)
+    got, got_u = np64(out_f), np64(out_u)
+    for t in range(steps):
+        ref = oracle.attend(qr64[t], Kr64, V64, t, window, 1.0 / np.sqrt(D))
+        assert_close(got[t], ref, dtype, f"large group rope step G={G} t={t} w={window}")
+        ref = oracle.attend(q[t].astype(np.float64), K64, V64, t, window, 1.0 / np.sqrt(D))
+        assert_close(got_u[t], ref, dtype, f"large group step G={G} t={t} w={window}")
+
+
+# ----------------------------------------------------------------------------
 # Per-sequence steps: each sequence is rotated to, written at and answered for
 # its own position.
 # ----------------------------------------------------------------------------

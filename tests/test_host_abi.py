@@ -171,7 +171,7 @@ def test_bad_arguments_are_refused_before_any_launch():
         return lib.tempo_attn_decode_causal(ctypes.byref(kv), q, out, 2, Hq, t, None, 0.1, ws, ws_bytes, None)
 
     assert causal(good, Hq=5) == T.TEMPO_ERR_SHAPE              # not a multiple of Hkv
-    assert causal(good, Hq=2 * 17) == T.TEMPO_ERR_SHAPE         # group larger than 16
+    assert causal(good, Hq=2 * 129) == T.TEMPO_ERR_SHAPE        # group larger than 128
     assert causal(good, q=None) == T.TEMPO_ERR_NULL
     assert causal(good, t=1000) == T.TEMPO_ERR_RANGE
     assert causal(good, ws=None) == T.TEMPO_ERR_WORKSPACE
