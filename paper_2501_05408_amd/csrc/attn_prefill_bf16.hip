@@ -14,8 +14,8 @@
 // output is written directly.  The key/value image of a group (16 KiB at D = 128)
 // is the same for all wavefronts: the workgroup copies it once from the pool into
 // LDS (it is already in MFMA operand order there, 1 KiB units) and every wavefront
-// reads its operands from LDS.  Two LDS buffers: the copy of group n+1 (global
-// loads into registers at the top of the iteration, LDS stores at its end)
+// reads its operands from LDS.  LDS buffers in a ring: the copy of a later group
+// (global -> LDS loads issued at the top of the iteration, waited for at its end)
 // overlaps the arithmetic on group n; one barrier per group.
 //
 // Blocks against a long history.  The same kernel serves a block of up to 128
@@ -39,9 +39,19 @@
 #define PROMPT_NT 1
 #define PROMPT_MIN_WAVES 1
 #endif
+#ifndef PROMPT_NBUF_SMALL
+#define PROMPT_NBUF_SMALL 2
+#define PROMPT_NBUF_SPLIT 2
+#endif
+#ifndef PROMPT_NBUF_DIRECT
+#define PROMPT_NBUF_DIRECT 2
+#endif
 
 namespace tempo {
 namespace {
+
+typedef __attribute__((address_space(3))) void* lds_ptr;
+typedef const __attribute__((address_space(1))) void* global_ptr;
 
 // Maximum over the four lanes {l, l^16, l^32, l^48} that hold one column's logits,
 // left in all four.  Two lane-swap instructions of gfx950 instead of two trips
@@ -106,21 +116,32 @@ __host__ __device__ inline int prefill_block_steps(int G, int waves, int tiles) 
 // key/value operands a wavefront reads from LDS serve all its NT tiles, so LDS
 // traffic per column falls with NT; the accumulators (NT x (D/16 + 1) tiles) set
 // the register budget.
-template <int D, int NW, int NT, bool kRope>
+template <int D, int NW, int NT, int NBUF, bool kRope>
 __global__ __launch_bounds__(64 * NW, PROMPT_MIN_WAVES) void attn_prefill_bf16(AttnParams p) {
   constexpr int KS = D / 32;
   constexpr int DT = D / 16;
   constexpr int UNITS = 2 * KS + DT;          // 1 KiB units of one group: keys then values
   constexpr int PER_THREAD = UNITS / NW;      // units each wavefront copies per group
   static_assert(UNITS % NW == 0, "units must divide among the wavefronts");
-  extern __shared__ u32x4 lds[];              // [2][UNITS][64] x 16 bytes
+  extern __shared__ u32x4 lds[];              // [NBUF][UNITS][64] x 16 bytes
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int QB = prefill_block_steps(p.G, NW, NT);
   const int nblocks = (p.queries + QB - 1) / QB;
-  const int qb = nblocks - 1 - (int)(blockIdx.x % nblocks);  // longest range first
-  const int zsplit = (int)(blockIdx.x / nblocks);             // 0 unless the key range is split
-  const int hkv = blockIdx.y, b = blockIdx.z;
+  // Which (block, split, kv head, sequence) this workgroup takes.  Workgroups are handed
+  // to the 8 accelerator dies (XCDs, each with its own L2) round-robin by linear index;
+  // the blocks of one (sequence, head) read the same keys/values, so each die is given a
+  // contiguous run of the work list instead: workgroup L takes item (L mod 8) * (n / 8)
+  // + L / 8 (remainder items spread over the first dies), and the blocks that run
+  // together on a die share its L2.
+  const unsigned nx = gridDim.x, ny = gridDim.y, total = nx * ny * gridDim.z;
+  const unsigned linear = blockIdx.x + nx * (blockIdx.y + ny * blockIdx.z);
+  const unsigned die = linear & 7u, share = total >> 3, extra = total & 7u;
+  const unsigned item = die * share + (die < extra ? die : extra) + (linear >> 3);
+  const unsigned ix = item % nx, iyz = item / nx;
+  const int qb = nblocks - 1 - (int)(ix % nblocks);           // longest range first
+  const int zsplit = (int)(ix / nblocks);                     // 0 unless the key range is split
+  const int hkv = (int)(iyz % ny), b = (int)(iyz / ny);
   const int c0 = qb * QB;                                           // first step of the block within the call
   // steps of this sequence in the call: all of them, or its own count
   int steps_b = p.queries;
@@ -194,6 +215,27 @@ __global__ __launch_bounds__(64 * NW, PROMPT_MIN_WAVES) void attn_prefill_bf16(A
 
   // Copy of one group: wavefront w moves units w, w + NW, ... (keys are units
   // 0 .. 2KS-1 of the key pool's group, values units 2KS .. of the value pool's).
+  // The pool image is already what the consumers read, so the copy goes from global
+  // memory straight into LDS (gfx950's 16-byte global -> LDS load: lane i's piece lands
+  // at the wavefront's LDS base + 16 i), two groups ahead of the arithmetic, through
+  // three LDS buffers; completion is counted by the vector-memory counter.
+  auto copy_direct = [&](int buf, int grp) {
+    const int64_t base = group_base<D>(p, b, hkv, grp);
+    const u32x4* kp = reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(p.k_pool) + base) + lane;
+    const u32x4* vp = reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(p.v_pool) + base) + lane;
+#pragma unroll
+    for (int i = 0; i < PER_THREAD; ++i) {
+      const int u = wave + NW * i;  // wave-uniform
+      const u32x4* from = u < 2 * KS ? kp + u * 64 : vp + (u - 2 * KS) * 64;
+      __builtin_amdgcn_global_load_lds((global_ptr)from, (lds_ptr)(lds + (buf * UNITS + u) * 64), 16, 0, 0);
+    }
+  };
+  // Slots beyond the block's last step may be unwritten (NaN): the 0 mask under the
+  // sums is applied once, to the value units of the range's last group.  That one group
+  // goes through registers (load, mask, LDS store; the copy keeps the lane of every
+  // 16-byte piece, so the lane's slots are the consumer's).  Masked slots inside the
+  // range hold written data and weight 0.
+  const bool tail = (g_last << 5) + 31 > t_last;  // uniform over the workgroup
   u32x4 stage[PER_THREAD];
   auto fetch = [&](int grp) {
     const int64_t base = group_base<D>(p, b, hkv, grp);
@@ -201,17 +243,13 @@ __global__ __launch_bounds__(64 * NW, PROMPT_MIN_WAVES) void attn_prefill_bf16(A
     const u32x4* vp = reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(p.v_pool) + base) + lane;
 #pragma unroll
     for (int i = 0; i < PER_THREAD; ++i) {
-      const int u = wave + NW * i;  // wave-uniform
+      const int u = wave + NW * i;
       stage[i] = u < 2 * KS ? kp[u * 64] : vp[(u - 2 * KS) * 64];
     }
   };
-  // Slots beyond the block's last step may be unwritten (NaN): the 0 mask under the
-  // sums is applied once, to the value units of the range's last group, on their way
-  // into LDS (the copy keeps the lane of every 16-byte piece, so the lane's slots are
-  // the consumer's).  Masked slots inside the range hold written data and weight 0.
   auto stash = [&](int buf, int grp) {
-    uint32_t keep[4] = {~0u, ~0u, ~0u, ~0u};
-    if ((grp << 5) + 31 > t_last) value_masks(grp, 0, t_last, lane, keep);  // uniform over the workgroup
+    uint32_t keep[4];
+    value_masks(grp, 0, t_last, lane, keep);
 #pragma unroll
     for (int i = 0; i < PER_THREAD; ++i) {
       const int u = wave + NW * i;
@@ -220,15 +258,37 @@ __global__ __launch_bounds__(64 * NW, PROMPT_MIN_WAVES) void attn_prefill_bf16(A
       lds[(buf * UNITS + u) * 64 + lane] = v;
     }
   };
+  // Wait until this wavefront's loads have landed (all of them, or all but the newest
+  // group's) and its LDS stores are done, then meet the other wavefronts.  Written out
+  // instead of __syncthreads(): its fence would wait for every outstanding global -> LDS
+  // load, the ones for the group after next included, which is the overlap this loop is
+  // built for.  The "memory" clobbers keep the compiler from moving LDS accesses across.
+  auto meet = [&](bool newest_pending) {
+    if (newest_pending && NBUF == 3) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PER_THREAD) : "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  };
 
-  fetch(g_first);
-  stash(0, g_first);
-  __syncthreads();
+  // Groups g_first and g_first + 1 before the loop, group n + 2 at the top of iteration n.
+  bool second = false;
+  if (tail && g_first == g_last) {
+    fetch(g_first);
+    stash(0, g_first);
+  } else {
+    copy_direct(0, g_first);
+    second = NBUF == 3 && g_first + 1 <= g_last && !(tail && g_first + 1 == g_last);
+    if (second) copy_direct(1, g_first + 1);
+  }
+  meet(second);
 
+  int buf = 0;  // LDS buffer of the current group; group n + k sits in buffer (buf + k) mod NBUF
   for (int grp = g_first; grp <= g_last; ++grp) {
-    const int buf = (grp - g_first) & 1;
-    const bool more = grp < g_last;  // uniform over the workgroup
-    if (more) fetch(grp + 1);
+    const int buf1 = buf == NBUF - 1 ? 0 : buf + 1;               // buffer of group n + 1
+    const int bufa = buf == 0 ? NBUF - 1 : buf - 1;                // buffer of group n + NBUF - 1
+    const bool via_regs = tail && grp + 1 == g_last;               // the next group is the masked one
+    const bool ahead = grp + NBUF - 1 <= g_last && !(tail && grp + NBUF - 1 == g_last);
+    if (ahead) copy_direct(bufa, grp + NBUF - 1);  // that buffer held group n - 1: everybody is past it
+    if (via_regs) fetch(grp + 1);
 
     // Has this wavefront anything to do in this group?  (Uniform over the wavefront.)
     const int j0 = grp << 5;
@@ -265,8 +325,10 @@ __global__ __launch_bounds__(64 * NW, PROMPT_MIN_WAVES) void attn_prefill_bf16(A
       }
     }
 
-    if (more) stash(buf ^ 1, grp + 1);  // nobody reads that buffer in this iteration
-    __syncthreads();           // group n+1 is in LDS; group n's buffer may be overwritten next time
+    // group n + 1 must be in LDS before anybody starts on it; group n + 2 may still be in flight
+    if (via_regs) stash(buf1, grp + 1);
+    meet(ahead);  // via_regs implies !ahead: the masked group is the last one
+    buf = buf1;
   }
 
   // Columns (4c + r) of acc, value dims 16dt + n.  Whole range: every column saw its own
@@ -314,20 +376,20 @@ constexpr int kPromptWaves = PROMPT_NW, kPromptTiles = PROMPT_NT;
 int prefill_bf16_block_steps(int G) { return prefill_block_steps(G, kPromptWaves, kPromptTiles); }
 
 namespace {
-template <int NW>
+template <int NW, int NBUF>
 hipError_t launch_prefill_nw(const AttnParams& p, int batch, int D, int grid_splits, hipStream_t stream) {
   constexpr int NT = kPromptTiles;
   const int QB = prefill_block_steps(p.G, NW, NT);
   const int nblocks = (p.queries + QB - 1) / QB;
   const dim3 grid(nblocks * grid_splits, p.Hkv, batch);
   const dim3 block(64 * NW);
-  const size_t lds = 2 * (size_t)(2 * (D / 32) + D / 16) * 1024;
+  const size_t lds = NBUF * (size_t)(2 * (D / 32) + D / 16) * 1024;
   if (p.rope_cos) {
-    if (D == 128) return launch((attn_prefill_bf16<128, NW, NT, true>), grid, block, lds, stream, p);
-    return launch((attn_prefill_bf16<64, NW, NT, true>), grid, block, lds, stream, p);
+    if (D == 128) return launch((attn_prefill_bf16<128, NW, NT, NBUF, true>), grid, block, lds, stream, p);
+    return launch((attn_prefill_bf16<64, NW, NT, NBUF, true>), grid, block, lds, stream, p);
   }
-  if (D == 128) return launch((attn_prefill_bf16<128, NW, NT, false>), grid, block, lds, stream, p);
-  return launch((attn_prefill_bf16<64, NW, NT, false>), grid, block, lds, stream, p);
+  if (D == 128) return launch((attn_prefill_bf16<128, NW, NT, NBUF, false>), grid, block, lds, stream, p);
+  return launch((attn_prefill_bf16<64, NW, NT, NBUF, false>), grid, block, lds, stream, p);
 }
 }  // namespace
 
@@ -335,9 +397,10 @@ hipError_t launch_prefill_nw(const AttnParams& p, int batch, int D, int grid_spl
 // block's whole range and writes `out`; p.tps_log2 must then be 30).
 hipError_t launch_prefill_bf16(const AttnParams& p, int batch, int D, int grid_splits, hipStream_t stream) {
   const int columns = p.queries * p.G;
-  if (kPromptTiles == 1 && columns <= 32) return launch_prefill_nw<2>(p, batch, D, grid_splits, stream);
-  if (kPromptTiles == 1 && columns <= 64) return launch_prefill_nw<4>(p, batch, D, grid_splits, stream);
-  return launch_prefill_nw<kPromptWaves>(p, batch, D, grid_splits, stream);
+  if (kPromptTiles == 1 && columns <= 32) return launch_prefill_nw<2, PROMPT_NBUF_SMALL>(p, batch, D, grid_splits, stream);
+  if (kPromptTiles == 1 && columns <= 64) return launch_prefill_nw<4, PROMPT_NBUF_SMALL>(p, batch, D, grid_splits, stream);
+  if (!p.direct) return launch_prefill_nw<kPromptWaves, PROMPT_NBUF_SPLIT>(p, batch, D, grid_splits, stream);
+  return launch_prefill_nw<kPromptWaves, PROMPT_NBUF_DIRECT>(p, batch, D, grid_splits, stream);
 }
 
 }  // namespace tempo
