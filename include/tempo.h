@@ -196,7 +196,8 @@ int tempo_kv_gather(const tempo_kv* kv, void* k_out, void* v_out, int32_t batch,
  * = attention of q[b][h][:] (device, same shape) over keys/values 0..t of
  * sequence b.  If t_per_seq (device, [batch]) is not NULL, sequence b is at step
  * t_per_seq[b] and t must be an upper bound of those steps (it fixes the launch
- * geometry).  scale is the constant s of Eq. 1.  workspace: device, 256-byte
+ * geometry).  scale is the constant s of Eq. 1, finite and > 0 (TEMPO_ERR_RANGE
+ * otherwise, in every entry point that takes it).  workspace: device, 256-byte
  * aligned, at least tempo_attn_workspace_bytes(kv, batch, num_q_heads, t) bytes;
  * its contents need no initialisation and one workspace serves one call at a
  * time.  Launches: partial attention per split, then the split combine (a step

@@ -66,7 +66,7 @@ def _drop_remarks(lines):
 # register count over the edge fails the build instead of silently costing 30%.
 MIN_OCCUPANCY = [
     ("attn_partial_bf16ILi128E", 3),           # decode kernel, D = 128: <= 170 VGPRs
-    ("attn_prefill_bf16ILi128ELi8ELi1E", 4),   # prompt kernel, D = 128: two workgroups of 8 per compute unit
+    ("attn_prefill_bf16ILi128ELi8ELb", 4),   # prompt kernel, D = 128: two workgroups of 8 per compute unit
 ]
 
 

@@ -30,21 +30,12 @@
 // follow find it in the caches; the longest blocks are dispatched first.
 #include "attn_bf16_common.h"
 
-// The instantiation that is built: wavefronts per workgroup, column tiles per
-// wavefront, and the occupancy (wavefronts per SIMD) the register allocation must
-// allow.  Measured on the 4096-step x 16-sequence prompt: 8 x 1 2.45 ms, 4 x 2 (two
-// per SIMD) 2.56 ms, 8 x 2 2.70 ms, 4 x 1 3.14 ms.
+// The instantiation that is built for prompts: wavefronts per workgroup (each with one
+// tile of 16 columns) and the occupancy (wavefronts per SIMD) the register allocation
+// must allow.
 #ifndef PROMPT_NW
 #define PROMPT_NW 8
-#define PROMPT_NT 1
 #define PROMPT_MIN_WAVES 1
-#endif
-#ifndef PROMPT_NBUF_SMALL
-#define PROMPT_NBUF_SMALL 2
-#define PROMPT_NBUF_SPLIT 2
-#endif
-#ifndef PROMPT_NBUF_DIRECT
-#define PROMPT_NBUF_DIRECT 2
 #endif
 
 namespace tempo {
@@ -67,6 +58,12 @@ __device__ inline float column_max(float v) {
   return c;
 }
 
+__device__ inline float max3(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+
 // Online softmax of one group for this kernel, with a LAZY reference: weights are
 // 2^(x - ref) where ref follows the running maximum only when the maximum has
 // grown by more than kSlack (in log2 units) since ref was set, so weights stay
@@ -76,14 +73,15 @@ __device__ inline float column_max(float v) {
 // more accumulator tile (weights times a column of ones on the matrix cores).
 constexpr float kSlack = 8.0f;
 
-// x holds the RAW dot products (masked ones are -inf); `scale` > 0 is s * log2(e),
-// applied to the maximum once and to the weights inside one fused multiply-add.
+// First half: move the reference if this group's maximum calls for it.  x holds the
+// RAW dot products (masked ones are -inf); `scale` > 0 is s * log2(e).
 template <int D>
-__device__ inline bf16x8 prompt_softmax(const float* x, float scale, int lane, float& ref, f32x4* acc,
-                                        f32x4& acc_l) {
+__device__ inline void softmax_reference(const float* x, float scale, int lane, float& ref, f32x4* acc,
+                                         f32x4& acc_l) {
   constexpr int DT = D / 16;
   const int c = lane >> 4;
-  float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+  // (three-operand maxima written out: fmaxf() first canonicalises each matrix-core result)
+  float mx = max3(max3(max3(max3(x[0], x[1], x[2]), x[3], x[4]), x[5], x[6]), x[7], x[7]);
   mx = column_max(mx) * scale;
   // ref = -inf until the column sees its first key; -inf + kSlack = -inf, so any finite mx moves it
   const bool move = mx > ref + kSlack;
@@ -102,6 +100,11 @@ __device__ inline bf16x8 prompt_softmax(const float* x, float scale, int lane, f
 #pragma unroll
     for (int r = 0; r < 4; ++r) acc_l[r] *= a[r];
   }
+}
+
+// Second half: the bf16 weights 2^(scale * x - ref), the scale applied inside one fused
+// multiply-add.
+__device__ inline bf16x8 softmax_weights(const float* x, float scale, float ref) {
   const float base = ref == -INFINITY ? 0.f : ref;  // a column that has seen no key yet: weights exp2(-inf) = 0
   bf16x8 pa;
 #pragma unroll
@@ -109,24 +112,32 @@ __device__ inline bf16x8 prompt_softmax(const float* x, float scale, int lane, f
   return pa;
 }
 
-// Steps per workgroup for a query group of G heads: all `waves` x `tiles` x 16 columns.
-__host__ __device__ inline int prefill_block_steps(int G, int waves, int tiles) { return (16 * waves * tiles) / G; }
+// Steps per workgroup for a query group of G heads: all 16 x `waves` columns.
+__host__ __device__ inline int prefill_block_steps(int G, int waves) { return (16 * waves) / G; }
 
-// NW wavefronts per workgroup, NT column tiles (of 16 columns) per wavefront.  The
-// key/value operands a wavefront reads from LDS serve all its NT tiles, so LDS
-// traffic per column falls with NT; the accumulators (NT x (D/16 + 1) tiles) set
-// the register budget.
-template <int D, int NW, int NT, int NBUF, bool kRope>
+// NW wavefronts per workgroup, 16 columns per wavefront.  (Two column tiles per
+// wavefront would halve the LDS reads per column, but the accumulators then cost a
+// wavefront of occupancy: measured slower, 2.56 against 2.45 ms on the 4096-step prompt.)
+//
+// The loop is software-pipelined by one group: iteration n computes the logits of group
+// n + 1 (matrix cores) next to the softmax of group n (vector ALU), then the
+// weights x values products of group n.  The two kinds of work of one wavefront are
+// independent inside an iteration, so they overlap instead of alternating.  Keys
+// therefore run one group ahead of values through LDS: two key buffers (groups n + 1,
+// n + 2) and two value buffers (groups n, n + 1).
+template <int D, int NW, bool kRope>
 __global__ __launch_bounds__(64 * NW, PROMPT_MIN_WAVES) void attn_prefill_bf16(AttnParams p) {
   constexpr int KS = D / 32;
   constexpr int DT = D / 16;
-  constexpr int UNITS = 2 * KS + DT;          // 1 KiB units of one group: keys then values
-  constexpr int PER_THREAD = UNITS / NW;      // units each wavefront copies per group
-  static_assert(UNITS % NW == 0, "units must divide among the wavefronts");
-  extern __shared__ u32x4 lds[];              // [NBUF][UNITS][64] x 16 bytes
+  constexpr int KU = 2 * KS;                  // 1 KiB units of one group's keys
+  constexpr int UNITS = KU + DT;              // ... and of its keys and values together
+  constexpr int PER_THREAD = (UNITS + NW - 1) / NW;  // units each wavefront copies per iteration (at most)
+  extern __shared__ u32x4 lds[];              // keys [2][KU][64] x 16 bytes, then values [2][DT][64] x 16 bytes
+  u32x4* const lds_k = lds;
+  u32x4* const lds_v = lds + 2 * KU * 64;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int QB = prefill_block_steps(p.G, NW, NT);
+  const int QB = prefill_block_steps(p.G, NW);
   const int nblocks = (p.queries + QB - 1) / QB;
   // Which (block, split, kv head, sequence) this workgroup takes.  Workgroups are handed
   // to the 8 accelerator dies (XCDs, each with its own L2) round-robin by linear index;
@@ -167,10 +178,10 @@ __global__ __launch_bounds__(64 * NW, PROMPT_MIN_WAVES) void attn_prefill_bf16(A
   const int end = t_last < ce ? t_last : ce;
   const int g_first = start >> 5, g_last = end >> 5;
 
-  // wavefront-uniform bounds over this wavefront's 16 * NT columns, cut to the split:
+  // wavefront-uniform bounds over this wavefront's 16 columns, cut to the split:
   // the groups it has any work in, and those no column cuts
-  const int first_col = 16 * NT * wave;
-  const int last_col = (first_col + 16 * NT - 1) < ncols - 1 ? (first_col + 16 * NT - 1) : ncols - 1;
+  const int first_col = 16 * wave;
+  const int last_col = (first_col + 15) < ncols - 1 ? (first_col + 15) : ncols - 1;
   const bool idle = first_col >= ncols;                             // a wavefront beyond the block's columns
   const int own_hi = t_first + (idle ? 0 : last_col / p.G);         // newest key any of its columns sees
   const int own_hi_min = t_first + (idle ? 0 : first_col / p.G);    // newest key ALL of its columns see
@@ -179,23 +190,21 @@ __global__ __launch_bounds__(64 * NW, PROMPT_MIN_WAVES) void attn_prefill_bf16(A
   const int w_hi = own_hi < end ? own_hi : end, w_hi_min = own_hi_min < end ? own_hi_min : end;
   const int w_lo_first = own_lo_first > start ? own_lo_first : start;
   const int w_lo_last = own_lo_last > start ? own_lo_last : start;
+  // has this wavefront any work in group g / does some column's range cut group g?  (wave-uniform)
+  auto active = [&](int g) { return !idle && (g << 5) <= w_hi && (g << 5) + 31 >= w_lo_first; };
+  auto is_cut = [&](int g) { return (g << 5) < w_lo_last || (g << 5) + 31 > w_hi_min; };
 
-  // Per column tile: this lane's column (unused columns behave like the block's last
-  // step with q = 0), its range, its query operand, its softmax state.
-  int lo_col[NT], hi_col[NT];
-  u32x4 qreg[NT][KS];
-  float m_run[NT];                             // softmax reference of column lane&15 (log2 units)
-  f32x4 acc[NT][DT];                           // lane (n + 16c): dims 16dt + n of columns 4c .. 4c+3
-  f32x4 acc_l[NT];                             // running sums of columns 4c .. 4c+3 (the same in every n)
-#pragma unroll
-  for (int jt = 0; jt < NT; ++jt) {
-    const int col = first_col + 16 * jt + (lane & 15);
-    const int cq = col < ncols ? col / p.G : C - 1;
-    const int gq = col < ncols ? col - cq * p.G : 0;
-    const int step = t_first + cq;             // the column's own step: its newest key and its position
-    hi_col[jt] = step < end ? step : end;
-    const int lo_own = (p.window > 0 && step - p.window + 1 > 0) ? step - p.window + 1 : 0;
-    lo_col[jt] = lo_own > start ? lo_own : start;
+  // This lane's column (unused columns behave like the block's last step with q = 0),
+  // its range, its query operand, its softmax state.
+  const int col = first_col + (lane & 15);
+  const int cq = col < ncols ? col / p.G : C - 1;
+  const int gq = col < ncols ? col - cq * p.G : 0;
+  const int step = t_first + cq;               // the column's own step: its newest key and its position
+  const int hi_col = step < end ? step : end;
+  const int lo_own = (p.window > 0 && step - p.window + 1 > 0) ? step - p.window + 1 : 0;
+  const int lo_col = lo_own > start ? lo_own : start;
+  u32x4 qreg[KS];
+  {
     const int c = lane >> 4;
     const uint16_t* qp = static_cast<const uint16_t*>(p.q) +
                          (((int64_t)b * p.io_steps + c0 + cq) * p.Hq + (int64_t)hkv * p.G + gq) * D + 8 * c;
@@ -203,132 +212,143 @@ __global__ __launch_bounds__(64 * NW, PROMPT_MIN_WAVES) void attn_prefill_bf16(A
     for (int s = 0; s < KS; ++s) {
       const u32x4 zero = {0u, 0u, 0u, 0u};
       const u32x4 v = *reinterpret_cast<const u32x4*>(qp + 32 * s);
-      qreg[jt][s] = col < ncols ? v : zero;
+      qreg[s] = col < ncols ? v : zero;
     }
-    if (kRope) rotate_query<D>(p, step, lane, qreg[jt]);  // queries arrive unrotated
-    m_run[jt] = -INFINITY;
-    acc_l[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt) acc[jt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (kRope) rotate_query<D>(p, step, lane, qreg);  // queries arrive unrotated
   }
+  float m_run = -INFINITY;                     // softmax reference of column lane&15 (log2 units)
+  f32x4 acc[DT];                               // lane (n + 16c): dims 16dt + n of columns 4c .. 4c+3
+  f32x4 acc_l = {0.f, 0.f, 0.f, 0.f};          // running sums of columns 4c .. 4c+3 (the same in every n)
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
   const u32x4 ones = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};  // bf16 1.0 x 8
 
-  // Copy of one group: wavefront w moves units w, w + NW, ... (keys are units
-  // 0 .. 2KS-1 of the key pool's group, values units 2KS .. of the value pool's).
-  // The pool image is already what the consumers read, so the copy goes from global
-  // memory straight into LDS (gfx950's 16-byte global -> LDS load: lane i's piece lands
-  // at the wavefront's LDS base + 16 i), two groups ahead of the arithmetic, through
-  // three LDS buffers; completion is counted by the vector-memory counter.
-  auto copy_direct = [&](int buf, int grp) {
-    const int64_t base = group_base<D>(p, b, hkv, grp);
-    const u32x4* kp = reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(p.k_pool) + base) + lane;
-    const u32x4* vp = reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(p.v_pool) + base) + lane;
+  // Copy of a group: wavefront w moves units w, w + NW, ... of the group's 1 KiB units
+  // (keys first, then values).  The pool image is already what the consumers read, so
+  // the copy goes from global memory straight into LDS (gfx950's 16-byte global -> LDS
+  // load: lane i's piece lands at the wavefront's LDS base + 16 i); completion is counted
+  // by the vector-memory counter.
+  // Where a group sits in either pool: its block-table entry (a scalar load, asked for
+  // one iteration before it is needed so that nobody waits for it) and the offset that
+  // follows from it.
+  const_i32_ptr table = (const_i32_ptr)p.block_table + (int64_t)b * p.max_blocks_per_seq;
+  auto entry_of = [&](int g) {
+    const int gc = g < g_last ? g : g_last;  // never past the range's last tile
+    return table[((gc << 5) >> p.z_log2) & p.tile_mask];
+  };
+  auto offset_of = [&](int entry, int g) -> int64_t {
+    const int phys = clamp_block(entry, p.num_blocks);
+    return (((int64_t)phys * p.Hkv + hkv) << p.z_log2) * D + (int64_t)((g << 5) & ((1 << p.z_log2) - 1)) * D;
+  };
+  auto issue_keys = [&](int gk, int64_t offset) {
+    if (gk > g_last) return;  // uniform over the workgroup
+    const char* from = reinterpret_cast<const char*>(static_cast<const uint16_t*>(p.k_pool) + offset);
 #pragma unroll
     for (int i = 0; i < PER_THREAD; ++i) {
       const int u = wave + NW * i;  // wave-uniform
-      const u32x4* from = u < 2 * KS ? kp + u * 64 : vp + (u - 2 * KS) * 64;
-      __builtin_amdgcn_global_load_lds((global_ptr)from, (lds_ptr)(lds + (buf * UNITS + u) * 64), 16, 0, 0);
+      if (u < KU)  // (wavefronts beyond the units copy nothing)
+        __builtin_amdgcn_global_load_lds((global_ptr)(from + u * 1024 + lane * 16),
+                                         (lds_ptr)(lds_k + ((gk & 1) * KU + u) * 64), 16, 0, 0);
+    }
+  };
+  auto issue_values = [&](int gv, int64_t offset) {
+    if (gv > g_last) return;
+    const char* from = reinterpret_cast<const char*>(static_cast<const uint16_t*>(p.v_pool) + offset);
+#pragma unroll
+    for (int i = 0; i < PER_THREAD; ++i) {
+      const int u = wave + NW * i - KU;
+      if (u >= 0 && u < DT)
+        __builtin_amdgcn_global_load_lds((global_ptr)(from + u * 1024 + lane * 16),
+                                         (lds_ptr)(lds_v + ((gv & 1) * DT + u) * 64), 16, 0, 0);
     }
   };
   // Slots beyond the block's last step may be unwritten (NaN): the 0 mask under the
-  // sums is applied once, to the value units of the range's last group.  That one group
-  // goes through registers (load, mask, LDS store; the copy keeps the lane of every
-  // 16-byte piece, so the lane's slots are the consumer's).  Masked slots inside the
-  // range hold written data and weight 0.
+  // sums is applied once, to the value units of the range's last group, in LDS, by the
+  // wavefront that copied the unit and after its copy has landed (the copy keeps the
+  // lane of every 16-byte piece, so a lane masks the slots its consumers will read from
+  // it).  Masked slots inside the range hold written data and weight 0.
   const bool tail = (g_last << 5) + 31 > t_last;  // uniform over the workgroup
-  u32x4 stage[PER_THREAD];
-  auto fetch = [&](int grp) {
-    const int64_t base = group_base<D>(p, b, hkv, grp);
-    const u32x4* kp = reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(p.k_pool) + base) + lane;
-    const u32x4* vp = reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(p.v_pool) + base) + lane;
-#pragma unroll
-    for (int i = 0; i < PER_THREAD; ++i) {
-      const int u = wave + NW * i;
-      stage[i] = u < 2 * KS ? kp[u * 64] : vp[(u - 2 * KS) * 64];
-    }
-  };
-  auto stash = [&](int buf, int grp) {
+  auto mask_values = [&](int gv) {  // gv == g_last, and tail
     uint32_t keep[4];
-    value_masks(grp, 0, t_last, lane, keep);
+    value_masks(gv, 0, t_last, lane, keep);
 #pragma unroll
     for (int i = 0; i < PER_THREAD; ++i) {
-      const int u = wave + NW * i;
-      u32x4 v = stage[i];
-      if (u >= 2 * KS) { v.x &= keep[0]; v.y &= keep[1]; v.z &= keep[2]; v.w &= keep[3]; }
-      lds[(buf * UNITS + u) * 64 + lane] = v;
+      const int u = wave + NW * i - KU;
+      if (u < 0 || u >= DT) continue;
+      u32x4* at = lds_v + ((gv & 1) * DT + u) * 64 + lane;
+      u32x4 v = *at;
+      v.x &= keep[0]; v.y &= keep[1]; v.z &= keep[2]; v.w &= keep[3];
+      *at = v;
     }
   };
-  // Wait until this wavefront's loads have landed (all of them, or all but the newest
-  // group's) and its LDS stores are done, then meet the other wavefronts.  Written out
-  // instead of __syncthreads(): its fence would wait for every outstanding global -> LDS
-  // load, the ones for the group after next included, which is the overlap this loop is
-  // built for.  The "memory" clobbers keep the compiler from moving LDS accesses across.
-  auto meet = [&](bool newest_pending) {
-    if (newest_pending && NBUF == 3) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PER_THREAD) : "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  // End of an iteration: wait until this wavefront's copies have landed, fix up what it
+  // must, wait for its LDS stores, then meet the other wavefronts.  Written out instead
+  // of __syncthreads() so that the waits are the ones this loop needs; the "memory"
+  // clobbers keep the compiler from moving LDS accesses across.
+  auto landed = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
+  auto meet = [&]() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
+
+  // Raw dot products of this wavefront's columns with the 32 keys of group g (two row tiles).
+  auto logits = [&](int g, float* x) {
+    const u32x4* src = lds_k + (g & 1) * KU * 64 + lane;
+    f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(src[s * 64]), as_bf16x8(qreg[s]), sa, 0, 0, 0);
+      sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(src[(KS + s) * 64]), as_bf16x8(qreg[s]), sb, 0, 0, 0);
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) { x[r] = sa[r]; x[4 + r] = sb[r]; }
   };
 
-  // Groups g_first and g_first + 1 before the loop, group n + 2 at the top of iteration n.
-  bool second = false;
-  if (tail && g_first == g_last) {
-    fetch(g_first);
-    stash(0, g_first);
-  } else {
-    copy_direct(0, g_first);
-    second = NBUF == 3 && g_first + 1 <= g_last && !(tail && g_first + 1 == g_last);
-    if (second) copy_direct(1, g_first + 1);
+  int64_t off_v;     // offset of group n + 1: its keys were copied an iteration before its values
+  int entry_next;    // block-table entry of group n + 2
+  {
+    const int e0 = entry_of(g_first), e1 = entry_of(g_first + 1);
+    entry_next = entry_of(g_first + 2);
+    const int64_t off0 = offset_of(e0, g_first);
+    off_v = offset_of(e1, g_first + 1);
+    issue_keys(g_first, off0);
+    issue_keys(g_first + 1, off_v);
+    issue_values(g_first, off0);
   }
-  meet(second);
+  landed();
+  if (tail && g_first == g_last) mask_values(g_first);
+  meet();
+  float xc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};  // logits of the current group
+  if (active(g_first)) logits(g_first, xc);
 
-  int buf = 0;  // LDS buffer of the current group; group n + k sits in buffer (buf + k) mod NBUF
   for (int grp = g_first; grp <= g_last; ++grp) {
-    const int buf1 = buf == NBUF - 1 ? 0 : buf + 1;               // buffer of group n + 1
-    const int bufa = buf == 0 ? NBUF - 1 : buf - 1;                // buffer of group n + NBUF - 1
-    const bool via_regs = tail && grp + 1 == g_last;               // the next group is the masked one
-    const bool ahead = grp + NBUF - 1 <= g_last && !(tail && grp + NBUF - 1 == g_last);
-    if (ahead) copy_direct(bufa, grp + NBUF - 1);  // that buffer held group n - 1: everybody is past it
-    if (via_regs) fetch(grp + 1);
+    // Buffers (g + 2) & 1 of the keys and (g + 1) & 1 of the values held groups g and
+    // g - 1, which everybody finished in the previous iteration.
+    const int64_t off_k = offset_of(entry_next, grp + 2);
+    entry_next = entry_of(grp + 3);
+    issue_keys(grp + 2, off_k);
+    issue_values(grp + 1, off_v);
+    off_v = off_k;
 
-    // Has this wavefront anything to do in this group?  (Uniform over the wavefront.)
-    const int j0 = grp << 5;
-    if (!idle && j0 <= w_hi && j0 + 31 >= w_lo_first) {
-      const u32x4* src = lds + buf * UNITS * 64 + lane;
-      const bool cut = j0 < w_lo_last || j0 + 31 > w_hi_min;
-      bf16x8 pa[NT];
-      {
-        Group<D> g;  // only the key half is used: the operands serve all NT tiles
+    if (active(grp)) {
+      if (is_cut(grp)) mask_logits(grp, lo_col, hi_col, lane, xc);
+      softmax_reference<D>(xc, p.scale_log2e, lane, m_run, acc, acc_l);
+      // The next group's logits: independent of the softmax below.  Beyond the last group
+      // this reads a key buffer of an earlier group (or LDS nobody wrote); the result is unused.
+      float xn[8];
+      logits(grp + 1, xn);
+      const bf16x8 pa = softmax_weights(xc, p.scale_log2e, m_run);
+      acc_l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, as_bf16x8(ones), acc_l, 0, 0, 0);
+      const u32x4* src = lds_v + (grp & 1) * DT * 64 + lane;
 #pragma unroll
-        for (int i = 0; i < 2 * KS; ++i) g.k[i] = src[i * 64];
+      for (int dt = 0; dt < DT; ++dt)
+        acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, as_bf16x8(src[dt * 64]), acc[dt], 0, 0, 0);
 #pragma unroll
-        for (int jt = 0; jt < NT; ++jt) {
-          float x[8];  // raw dot products of the two row tiles
-          f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-          for (int s = 0; s < KS; ++s) {
-            sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(g.k[s]), as_bf16x8(qreg[jt][s]), sa, 0, 0, 0);
-            sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(g.k[KS + s]), as_bf16x8(qreg[jt][s]), sb, 0, 0, 0);
-          }
-#pragma unroll
-          for (int r = 0; r < 4; ++r) { x[r] = sa[r]; x[4 + r] = sb[r]; }
-          if (cut) mask_logits(grp, lo_col[jt], hi_col[jt], lane, x);
-          pa[jt] = prompt_softmax<D>(x, p.scale_log2e, lane, m_run[jt], acc[jt], acc_l[jt]);
-          acc_l[jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa[jt], as_bf16x8(ones), acc_l[jt], 0, 0, 0);
-        }
-      }
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt) {
-        const u32x4 vv = src[(2 * KS + dt) * 64];
-#pragma unroll
-        for (int jt = 0; jt < NT; ++jt)
-          acc[jt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa[jt], as_bf16x8(vv), acc[jt][dt], 0, 0, 0);
-      }
+      for (int i = 0; i < 8; ++i) xc[i] = xn[i];
+    } else if (grp + 1 <= g_last && active(grp + 1)) {
+      logits(grp + 1, xc);
     }
 
-    // group n + 1 must be in LDS before anybody starts on it; group n + 2 may still be in flight
-    if (via_regs) stash(buf1, grp + 1);
-    meet(ahead);  // via_regs implies !ahead: the masked group is the last one
-    buf = buf1;
+    landed();
+    if (tail && grp + 1 == g_last) mask_values(grp + 1);
+    meet();  // groups n + 1 (values) and n + 2 (keys) are in LDS; nobody reads group n any more
   }
 
   // Columns (4c + r) of acc, value dims 16dt + n.  Whole range: every column saw its own
@@ -337,29 +357,26 @@ __global__ __launch_bounds__(64 * NW, PROMPT_MIN_WAVES) void attn_prefill_bf16(A
   // that saw no key in this split leaves (-inf, 0, 0).
   const int n = lane & 15, c = lane >> 4;
 #pragma unroll
-  for (int jt = 0; jt < NT; ++jt) {
+  for (int r = 0; r < 4; ++r) {
+    const int j = first_col + 4 * c + r;
+    const float l_j = acc_l[r];
+    const float ref_j = __shfl(m_run, 4 * c + r);  // the reference lives in lane (column & 15)
+    if (j < ncols) {
+      const int jc = j / p.G, jg = j - jc * p.G;
+      if (p.direct) {
+        __bf16* orow = static_cast<__bf16*>(p.out) +
+                       (((int64_t)b * p.io_steps + c0 + jc) * p.Hq + (int64_t)hkv * p.G + jg) * D;
+        const float inv = 1.0f / l_j;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int j = first_col + 16 * jt + 4 * c + r;
-      const float l_j = acc_l[jt][r];
-      const float ref_j = __shfl(m_run[jt], 4 * c + r);  // the reference lives in lane (column & 15)
-      if (j < ncols) {
-        const int jc = j / p.G, jg = j - jc * p.G;
-        if (p.direct) {
-          __bf16* orow = static_cast<__bf16*>(p.out) +
-                         (((int64_t)b * p.io_steps + c0 + jc) * p.Hq + (int64_t)hkv * p.G + jg) * D;
-          const float inv = 1.0f / l_j;
+        for (int dt = 0; dt < DT; ++dt) orow[16 * dt + n] = (__bf16)(acc[dt][r] * inv);
+      } else {
+        const int64_t row = ((int64_t)b * p.queries + c0 + jc) * p.Hq + (int64_t)hkv * p.G + jg;
+        const int64_t part = row * p.num_splits + split;
 #pragma unroll
-          for (int dt = 0; dt < DT; ++dt) orow[16 * dt + n] = (__bf16)(acc[jt][dt][r] * inv);
-        } else {
-          const int64_t row = ((int64_t)b * p.queries + c0 + jc) * p.Hq + (int64_t)hkv * p.G + jg;
-          const int64_t part = row * p.num_splits + split;
-#pragma unroll
-          for (int dt = 0; dt < DT; ++dt) p.ws_acc[part * D + 16 * dt + n] = acc[jt][dt][r];
-          if (n == 0) {
-            p.ws_ml[part * 2] = ref_j;
-            p.ws_ml[part * 2 + 1] = l_j;
-          }
+        for (int dt = 0; dt < DT; ++dt) p.ws_acc[part * D + 16 * dt + n] = acc[dt][r];
+        if (n == 0) {
+          p.ws_ml[part * 2] = ref_j;
+          p.ws_ml[part * 2 + 1] = l_j;
         }
       }
     }
@@ -368,28 +385,27 @@ __global__ __launch_bounds__(64 * NW, PROMPT_MIN_WAVES) void attn_prefill_bf16(A
 
 }  // namespace
 
-// The prompt path uses kPromptWaves wavefronts of kPromptTiles tiles; a single block
-// of fewer columns gets a workgroup of just enough wavefronts (2, 4 or 8), so that
-// several workgroups share a compute unit and the kernel stays bound by HBM.
-constexpr int kPromptWaves = PROMPT_NW, kPromptTiles = PROMPT_NT;
+// The prompt path uses kPromptWaves wavefronts; a single block of fewer columns gets a
+// workgroup of just enough wavefronts (2, 4 or 8), so that several workgroups share a
+// compute unit and the kernel stays bound by HBM.
+constexpr int kPromptWaves = PROMPT_NW;
 
-int prefill_bf16_block_steps(int G) { return prefill_block_steps(G, kPromptWaves, kPromptTiles); }
+int prefill_bf16_block_steps(int G) { return prefill_block_steps(G, kPromptWaves); }
 
 namespace {
-template <int NW, int NBUF>
+template <int NW>
 hipError_t launch_prefill_nw(const AttnParams& p, int batch, int D, int grid_splits, hipStream_t stream) {
-  constexpr int NT = kPromptTiles;
-  const int QB = prefill_block_steps(p.G, NW, NT);
+  const int QB = prefill_block_steps(p.G, NW);
   const int nblocks = (p.queries + QB - 1) / QB;
   const dim3 grid(nblocks * grid_splits, p.Hkv, batch);
   const dim3 block(64 * NW);
-  const size_t lds = NBUF * (size_t)(2 * (D / 32) + D / 16) * 1024;
+  const size_t lds = 2 * (size_t)(2 * (D / 32) + D / 16) * 1024;
   if (p.rope_cos) {
-    if (D == 128) return launch((attn_prefill_bf16<128, NW, NT, NBUF, true>), grid, block, lds, stream, p);
-    return launch((attn_prefill_bf16<64, NW, NT, NBUF, true>), grid, block, lds, stream, p);
+    if (D == 128) return launch((attn_prefill_bf16<128, NW, true>), grid, block, lds, stream, p);
+    return launch((attn_prefill_bf16<64, NW, true>), grid, block, lds, stream, p);
   }
-  if (D == 128) return launch((attn_prefill_bf16<128, NW, NT, NBUF, false>), grid, block, lds, stream, p);
-  return launch((attn_prefill_bf16<64, NW, NT, NBUF, false>), grid, block, lds, stream, p);
+  if (D == 128) return launch((attn_prefill_bf16<128, NW, false>), grid, block, lds, stream, p);
+  return launch((attn_prefill_bf16<64, NW, false>), grid, block, lds, stream, p);
 }
 }  // namespace
 
@@ -397,10 +413,9 @@ hipError_t launch_prefill_nw(const AttnParams& p, int batch, int D, int grid_spl
 // block's whole range and writes `out`; p.tps_log2 must then be 30).
 hipError_t launch_prefill_bf16(const AttnParams& p, int batch, int D, int grid_splits, hipStream_t stream) {
   const int columns = p.queries * p.G;
-  if (kPromptTiles == 1 && columns <= 32) return launch_prefill_nw<2, PROMPT_NBUF_SMALL>(p, batch, D, grid_splits, stream);
-  if (kPromptTiles == 1 && columns <= 64) return launch_prefill_nw<4, PROMPT_NBUF_SMALL>(p, batch, D, grid_splits, stream);
-  if (!p.direct) return launch_prefill_nw<kPromptWaves, PROMPT_NBUF_SPLIT>(p, batch, D, grid_splits, stream);
-  return launch_prefill_nw<kPromptWaves, PROMPT_NBUF_DIRECT>(p, batch, D, grid_splits, stream);
+  if (columns <= 32) return launch_prefill_nw<2>(p, batch, D, grid_splits, stream);
+  if (columns <= 64) return launch_prefill_nw<4>(p, batch, D, grid_splits, stream);
+  return launch_prefill_nw<kPromptWaves>(p, batch, D, grid_splits, stream);
 }
 
 }  // namespace tempo

@@ -61,6 +61,10 @@ int check_queries(const tempo_kv* kv, int32_t Hq, int32_t queries) {
   return TEMPO_OK;
 }
 
+// The constant s of Eq. 1: finite and positive (the kernels take maxima of raw dot
+// products and scale afterwards).
+int check_scale(float scale) { return (scale > 0.0f && scale <= 3.0e38f) ? TEMPO_OK : TEMPO_ERR_RANGE; }
+
 // The steps a block of queries starting at t touches: the last step, and the
 // window measured from the last step that spans the union of the queries' ranges.
 int32_t last_step(int32_t t, int32_t queries) { return t + (queries - 1); }
@@ -381,6 +385,7 @@ int decode(const tempo_kv* kv, const void* q, const void* k_new, const void* v_n
   if ((rc = check_heads(kv, batch, Hq)) != TEMPO_OK) return rc;
   if ((rc = check_queries(kv, Hq, queries)) != TEMPO_OK) return rc;
   if (t < 0 || window < 0 || t > INT32_MAX - 64) return TEMPO_ERR_RANGE;
+  if ((rc = check_scale(scale)) != TEMPO_OK) return rc;
   if (rope && (rc = check_rope(rope, kv->head_dim, last_step(t, queries))) != TEMPO_OK) return rc;
   if (pad_t < 0 || pad_t > INT32_MAX - 64) return TEMPO_ERR_RANGE;
   tempo_plan plan;
@@ -681,6 +686,7 @@ static int prefill(const tempo_kv* kv, const void* q, const void* k_new, const v
   if ((rc = check_heads(kv, batch, Hq)) != TEMPO_OK) return rc;
   if (count < 1 || count > (1 << 24)) return TEMPO_ERR_SHAPE;
   if (t < 0 || window < 0 || t > INT32_MAX - 64 - count) return TEMPO_ERR_RANGE;
+  if ((rc = check_scale(scale)) != TEMPO_OK) return rc;
   if ((rc = check_step(kv, t + count - 1)) != TEMPO_OK) return rc;
   const int G = Hq / kv->num_kv_heads;
   const int32_t block = kMaxColumns / G;  // steps per block: all four column tiles
@@ -807,6 +813,7 @@ int tempo_attn_block_with_plan(const tempo_kv* kv, const void* q, void* out, int
   int rc = check_layout(kv);
   if (rc != TEMPO_OK) return rc;
   if (!q || !out || !plan) return TEMPO_ERR_NULL;
+  if ((rc = check_scale(scale)) != TEMPO_OK) return rc;
   if ((rc = check_attn(kv, batch, num_q_heads, t, window, t_per_seq != nullptr, plan, workspace, workspace_bytes,
                        queries)) != TEMPO_OK)
     return rc;
@@ -841,6 +848,7 @@ int tempo_attn_decode_partial(const tempo_kv* kv, const void* q, const void* k_n
   int rc = check_layout(kv);
   if (rc != TEMPO_OK) return rc;
   if (!q || ((k_new == nullptr) != (v_new == nullptr))) return TEMPO_ERR_NULL;
+  if ((rc = check_scale(scale)) != TEMPO_OK) return rc;
   if ((rc = check_attn(kv, batch, num_q_heads, t, window, t_per_seq != nullptr, plan, workspace, workspace_bytes)) != TEMPO_OK) return rc;
   // the kernel that serves a group of more than 16 heads does not write the store
   if (k_new && kv->dtype == TEMPO_BF16 && num_q_heads / kv->num_kv_heads > 16) return TEMPO_ERR_SHAPE;

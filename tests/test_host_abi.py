@@ -173,6 +173,9 @@ def test_bad_arguments_are_refused_before_any_launch():
     assert causal(good, Hq=5) == T.TEMPO_ERR_SHAPE              # not a multiple of Hkv
     assert causal(good, Hq=2 * 129) == T.TEMPO_ERR_SHAPE        # group larger than 128
     assert causal(good, q=None) == T.TEMPO_ERR_NULL
+    for bad_scale in (0.0, -0.1, float("inf"), float("nan")):   # Eq. 1's constant s is finite and positive
+        assert lib.tempo_attn_decode_causal(ctypes.byref(good), fake, fake, 2, 6, 5, None, bad_scale, fake << 4,
+                                            1 << 30, None) == T.TEMPO_ERR_RANGE
     assert causal(good, t=1000) == T.TEMPO_ERR_RANGE
     assert causal(good, ws=None) == T.TEMPO_ERR_WORKSPACE
     assert causal(good, ws=(fake << 4) + 8) == T.TEMPO_ERR_WORKSPACE     # misaligned
