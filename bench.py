@@ -121,7 +121,7 @@ def other_workloads(torch, T, BlockStore, synth, dev, kv_bytes_per_token):
     tflops = 16 * pairs * 4 * D * Hq / dt / 1e12
     out["prompt_b16_t4096"] = {"ms": round(dt * 1e3, 3), "tokens_per_s": round(16 * P / dt, 1),
                                "tflops": round(tflops, 1),
-                               "roofline": {"kernel": "attn_prefill_bf16<128, 8, 1, false>", "bound": "mfma",
+                               "roofline": {"kernel": "attn_prefill_bf16<128, 8, false>", "bound": "mfma",
                                             "achieved": round(tflops, 1), "peak": 2500.0, "unit": "TFLOP/s",
                                             "frac": round(tflops / 2500.0, 4)},
                                "note": "one tempo_prefill_causal call (block-store write + prompt kernel); "
@@ -251,7 +251,7 @@ def prompt_only(torch, T, BlockStore, synth, dev, repeats):
     flops = B * (P * (P + 1) // 2) * 4 * D * Hq
     return {"workload": "prompt of 4096 steps x 16 sequences, llama-3.2-3b attention shape, one tempo_prefill_causal call",
             "ms": round(dt * 1e3, 3), "tokens_per_s": round(B * P / dt, 1), "algorithmic_flops_per_call": flops,
-            "roofline": {"kernel": "attn_prefill_bf16<128, 8, 1, false>", "bound": "mfma", "achieved": round(flops / dt / 1e12, 1),
+            "roofline": {"kernel": "attn_prefill_bf16<128, 8, false>", "bound": "mfma", "achieved": round(flops / dt / 1e12, 1),
                          "peak": 2500.0, "unit": "TFLOP/s", "frac": round(flops / dt / 1e12 / 2500.0, 4)}}
 
 
