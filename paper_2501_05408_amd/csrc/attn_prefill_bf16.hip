@@ -14,9 +14,9 @@
 // output is written directly.  The key/value image of a group (16 KiB at D = 128)
 // is the same for all wavefronts: the workgroup copies it once from the pool into
 // LDS (it is already in MFMA operand order there, 1 KiB units) and every wavefront
-// reads its operands from LDS.  LDS buffers in a ring: the copy of a later group
-// (global -> LDS loads issued at the top of the iteration, waited for at its end)
-// overlaps the arithmetic on group n; one barrier per group.
+// reads its operands from LDS.  Two key and two value buffers: the copies for later
+// groups (global -> LDS loads issued at the top of an iteration, waited for at its
+// end) overlap the arithmetic of the iteration; one barrier per group.
 //
 // Blocks against a long history.  The same kernel serves a block of up to 128
 // columns in front of a long key range (chunked prompt processing, speculative
@@ -25,9 +25,9 @@
 // (reference, sum, accumulator) per column, and the split combine finishes.  The
 // keys/values are read from HBM once per workgroup for all its columns.
 //
-// Workgroups of one (sequence, head) are adjacent in the grid and run together, so
-// the pool is streamed from HBM about once per (sequence, head) and the blocks that
-// follow find it in the caches; the longest blocks are dispatched first.
+// Workgroups of one (sequence, head) are adjacent in the work list and run together on
+// one die, so the pool is streamed from HBM about once per (sequence, head) and the
+// blocks that follow find it in that die's L2; the longest blocks come first.
 #include "attn_bf16_common.h"
 
 // The instantiation that is built for prompts: wavefronts per workgroup (each with one
