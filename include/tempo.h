@@ -142,6 +142,32 @@ int tempo_visible_range(int32_t t, int32_t window, int32_t Z, int32_t* lo, int32
 int tempo_append_slot(int32_t t, int32_t Z, int32_t* tile, int32_t* slot);
 
 /*
+ * Which stored steps may be released once step t has been answered (Section 5.2,
+ * scheduling deallocations: what a step produced is released after the last step
+ * that reads it, found from the inverse of the consumer's dependence).  With a
+ * window of `window` visible keys, key j is read by steps j .. j+window-1, so after
+ * step t the keys 0 .. t-window+1 are dead.  Writes: dead_keys = their number
+ * (clamped to [0, t+1]), dead_tiles = dead_keys div Z = the leading blocks of a
+ * linear store that no later step reads and the caller may hand to another
+ * sequence.  window = 0 (causal): nothing is ever dead, both are 0.  Either
+ * pointer may be NULL.  Pure host function; TEMPO_ERR_RANGE for t < 0, t = INT32_MAX,
+ * window < 0, Z < 1.
+ */
+int tempo_kv_release(int32_t t, int32_t window, int32_t Z, int32_t* dead_keys, int32_t* dead_tiles);
+
+/*
+ * Size of a window store (Section 6: a window-accessed tensor lives in a
+ * pre-allocated circular buffer sized by the window): the smallest ring_blocks (a
+ * power of two) with which calls that answer `queries` consecutive steps with this
+ * window always find their visible range resident, wherever the steps fall
+ * relative to the tile boundaries: floor((window + queries - 3) / Z) + 2 tiles
+ * (1 if window + queries = 2), rounded up to a power of two.  Pure host function;
+ * TEMPO_ERR_RANGE for window < 1, Z < 1, queries < 1 or a result beyond 2^30;
+ * ring_blocks must not be NULL.
+ */
+int tempo_ring_blocks(int32_t window, int32_t Z, int32_t queries, int32_t* ring_blocks);
+
+/*
  * Element offset, from the start of k_pool (which = 0) or v_pool (which = 1),
  * of dimension d of slot `slot` of kv head `head` of physical block `block`.
  * Only the layout fields of kv are read.  Returns -1 for arguments out of range.

@@ -29,7 +29,9 @@
  * the padded+masked formulation, the paper's tiled three-reduction form, the
  * paper's printed inverse-window example; for the rotary embedding: closed
  * forms at chosen angles, norm preservation, the relative-position identity and
- * composition of rotations).  Nothing is "parity unpinned".
+ * composition of rotations; for releases and ring sizes: the paper's printed
+ * inverse-window example read as "last reader of key j", and closed forms).
+ * Nothing is "parity unpinned".
  */
 #include <math.h>
 #include <stddef.h>
@@ -114,6 +116,68 @@ int tempo_oracle_append_slot(int t, int Z, int* tile, int* slot) {
   }
   *tile = n; *slot = s;
   return 0;
+}
+
+/*
+ * Which stored keys are dead once step t has been answered?  (Section 5.2,
+ * scheduling deallocations: what step j produced may be released only after the
+ * last step that reads it, which follows from the inverse of the consumer's
+ * dependence.)  Key j is dead after step t if none of the later steps sees it;
+ * later steps are tried one by one up to the first that cannot see any key <= t.
+ *   dead_keys    number of leading dead keys 0 .. dead_keys-1
+ *   dead_tiles   number of leading tiles (of Z keys) all of whose keys are dead
+ * Causal (window 0): every later step sees every key, nothing is ever dead.
+ * Returns 0, or -1 for t < 0, window < 0 or Z < 1.
+ */
+int tempo_oracle_release(int t, int window, int Z, int* dead_keys, int* dead_tiles) {
+  if (t < 0 || window < 0 || Z < 1) return -1;
+  int dead = 0;
+  for (int j = 0; j <= t; ++j) {
+    int seen_later = 0;
+    if (window == 0) seen_later = 1;
+    for (int later = t + 1; !seen_later && later <= t + window; ++later) {
+      if (visible(j, later, window)) seen_later = 1;
+    }
+    if (seen_later) break;
+    ++dead;
+  }
+  int tiles = 0;
+  for (int first = 0; first + Z <= dead; first += Z) ++tiles;  /* whole tiles inside the dead prefix */
+  *dead_keys = dead;
+  *dead_tiles = tiles;
+  return 0;
+}
+
+/*
+ * How many blocks must a circular (window) store of tile size Z hold per sequence
+ * so that a call answering `queries` consecutive steps with this window finds every
+ * tile it reads still resident, wherever the steps fall relative to the tile
+ * boundaries?  (Section 6, window store: a pre-allocated circular buffer sized by the
+ * window.)  By trying every first step over several tile periods and counting the
+ * tiles between the oldest visible key of the first step and the newest key of the
+ * last; the result is rounded up to a power of two (the ring's table index is a
+ * bit mask).  Returns the count, or -1 for window < 1, Z < 1 or queries < 1.
+ */
+int tempo_oracle_ring_blocks(int window, int Z, int queries) {
+  if (window < 1 || Z < 1 || queries < 1) return -1;
+  int most = 0;
+  for (int first = 0; first < window + 4 * Z; ++first) {
+    const int last = first + queries - 1;
+    int oldest = -1;
+    for (int j = 0; j <= first; ++j) {
+      if (visible(j, first, window)) { oldest = j; break; }
+    }
+    /* walk the keys in order, opening a new tile every Z keys; count the tiles that hold a key that matters */
+    int tiles = 0, counted_tile = -1, tile = 0, slot = 0;
+    for (int j = 0; j <= last; ++j) {
+      if (j >= oldest && tile != counted_tile) { ++tiles; counted_tile = tile; }
+      if (++slot == Z) { slot = 0; ++tile; }
+    }
+    if (tiles > most) most = tiles;
+  }
+  int ring = 1;
+  while (ring < most) ring *= 2;
+  return ring;
 }
 
 /*

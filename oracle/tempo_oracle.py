@@ -44,6 +44,10 @@ def _bind(path: str):
         lib.tempo_oracle_tile_visible_count.restype = ctypes.c_int
         lib.tempo_oracle_append_slot.argtypes = [ctypes.c_int, ctypes.c_int, ip, ip]
         lib.tempo_oracle_append_slot.restype = ctypes.c_int
+        lib.tempo_oracle_release.argtypes = [ctypes.c_int] * 3 + [ip, ip]
+        lib.tempo_oracle_release.restype = ctypes.c_int
+        lib.tempo_oracle_ring_blocks.argtypes = [ctypes.c_int] * 3
+        lib.tempo_oracle_ring_blocks.restype = ctypes.c_int
         lib.tempo_oracle_attend.argtypes = [dp, dp, dp] + [ctypes.c_int] * 5 + [ip, ctypes.c_int,
                                                                              ctypes.c_double, dp]
         lib.tempo_oracle_attend.restype = ctypes.c_int
@@ -86,6 +90,23 @@ def append_slot(t: int, Z: int):
     if rc != 0:
         raise ValueError("oracle: bad argument to append_slot")
     return tile.value, slot.value
+
+
+def release(t: int, window: int, Z: int):
+    """(dead_keys, dead_tiles) once step t has been answered (Section 5.2, deallocations)."""
+    keys, tiles = ctypes.c_int(0), ctypes.c_int(0)
+    rc = _load().tempo_oracle_release(t, window, Z, ctypes.byref(keys), ctypes.byref(tiles))
+    if rc != 0:
+        raise ValueError("oracle: bad argument to release")
+    return keys.value, tiles.value
+
+
+def ring_blocks(window: int, Z: int, queries: int = 1) -> int:
+    """Blocks per sequence of a circular store that serves `queries` steps per call (Section 6)."""
+    rc = _load().tempo_oracle_ring_blocks(window, Z, queries)
+    if rc < 0:
+        raise ValueError("oracle: bad argument to ring_blocks")
+    return rc
 
 
 def attend(q, K, V, t, window: int, scale: float) -> np.ndarray:

@@ -440,6 +440,29 @@ int tempo_append_slot(int32_t t, int32_t Z, int32_t* tile, int32_t* slot) {
   return TEMPO_OK;
 }
 
+int tempo_kv_release(int32_t t, int32_t window, int32_t Z, int32_t* dead_keys, int32_t* dead_tiles) {
+  if (t < 0 || t == INT32_MAX || window < 0 || Z < 1) return TEMPO_ERR_RANGE;  // t + 1 keys must be countable
+  // the last reader of key j is step j + window - 1: dead after step t iff j <= t - window + 1
+  int64_t dead = window == 0 ? 0 : (int64_t)t - window + 2;
+  if (dead < 0) dead = 0;
+  if (dead_keys) *dead_keys = (int32_t)dead;
+  if (dead_tiles) *dead_tiles = (int32_t)(dead / Z);
+  return TEMPO_OK;
+}
+
+int tempo_ring_blocks(int32_t window, int32_t Z, int32_t queries, int32_t* ring_blocks) {
+  if (!ring_blocks) return TEMPO_ERR_NULL;
+  if (window < 1 || Z < 1 || queries < 1) return TEMPO_ERR_RANGE;
+  // the union of the queries' ranges, at its worst alignment to the tiles
+  const int64_t span = (int64_t)window + queries - 1;
+  const int64_t tiles = span <= 1 ? 1 : (span - 2 + Z) / Z + 1;
+  if (tiles > (1 << 30)) return TEMPO_ERR_RANGE;
+  int32_t ring = 1;
+  while (ring < tiles) ring *= 2;
+  *ring_blocks = ring;
+  return TEMPO_OK;
+}
+
 int64_t tempo_kv_element_offset(const tempo_kv* kv, int32_t which, int32_t block, int32_t head,
                                 int32_t slot, int32_t d) {
   if (check_layout(kv) != TEMPO_OK) return -1;

@@ -83,6 +83,8 @@ _i32p = ctypes.POINTER(ctypes.c_int32)
 SIGNATURES = {
     "tempo_visible_range": (ctypes.c_int, [_i32, _i32, _i32] + [_i32p] * 6),
     "tempo_append_slot": (ctypes.c_int, [_i32, _i32, _i32p, _i32p]),
+    "tempo_kv_release": (ctypes.c_int, [_i32, _i32, _i32, _i32p, _i32p]),
+    "tempo_ring_blocks": (ctypes.c_int, [_i32, _i32, _i32, _i32p]),
     "tempo_kv_element_offset": (ctypes.c_int64, [_kvp, _i32, _i32, _i32, _i32, _i32]),
     "tempo_kv_pool_bytes": (ctypes.c_size_t, [_kvp]),
     "tempo_attn_plan": (ctypes.c_int, [_kvp, _i32, _i32, _i32, _i32, _i32, _planp]),
@@ -236,6 +238,18 @@ def tempo_append_slot(t: int, Z: int):
     tile, slot = ctypes.c_int32(0), ctypes.c_int32(0)
     _check(load().tempo_append_slot(t, Z, ctypes.byref(tile), ctypes.byref(slot)), "tempo_append_slot")
     return tile.value, slot.value
+
+
+def tempo_kv_release(t: int, window: int, Z: int):
+    keys, tiles = ctypes.c_int32(0), ctypes.c_int32(0)
+    _check(load().tempo_kv_release(t, window, Z, ctypes.byref(keys), ctypes.byref(tiles)), "tempo_kv_release")
+    return keys.value, tiles.value
+
+
+def tempo_ring_blocks(window: int, Z: int, queries: int = 1) -> int:
+    ring = ctypes.c_int32(0)
+    _check(load().tempo_ring_blocks(window, Z, queries, ctypes.byref(ring)), "tempo_ring_blocks")
+    return ring.value
 
 
 def tempo_kv_element_offset(kv: tempo_kv, which: int, block: int, head: int, slot: int, d: int) -> int:

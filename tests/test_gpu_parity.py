@@ -356,6 +356,9 @@ def test_fused_step_ragged(dtype):
 @pytest.mark.parametrize("fused", [False, True])
 def test_ring_store_windowed_decode(dtype, Z, R, window, fused):
     B, Hq, Hkv, D, steps = 2, 6, 2, 128, 700
+    # the ring is the size the library's own helper gives for this window; one more key needs twice as much
+    assert T.tempo_ring_blocks(window, Z) == R
+    assert T.tempo_ring_blocks((R - 1) * Z + 1, Z) == R and T.tempo_ring_blocks((R - 1) * Z + 2, Z) == 2 * R
     q, K, V = host_inputs(12, B, steps, Hq, Hkv, D, dtype)
     ring_table = torch.from_numpy(synth.permutation(12, 3, B * R).reshape(B, R).copy())
     ring = BlockStore(B, Hq, Hkv, D, Z, steps - 1, dtype, num_blocks=B * R, block_table=ring_table,
@@ -390,6 +393,50 @@ def test_ring_store_windowed_decode(dtype, Z, R, window, fused):
         ring.attend_window(qd[0], ring.new_out(), steps - 1, (R - 1) * Z + 2)
     with pytest.raises(T.TempoError):
         ring.attend_causal(qd[0], ring.new_out(), steps - 1)
+
+
+# ----------------------------------------------------------------------------
+# Inferred deallocation on a linear store: the host frees the blocks that
+# tempo_kv_release reports dead, poisons them, and hands them to the tiles opened
+# later (other sequences' included).  Windowed decode of any length then lives in
+# a pool of a few blocks per sequence, and never reads a released block.
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,Z,window", [(T.TEMPO_BF16, 32, 70), (T.TEMPO_F32, 8, 9), (T.TEMPO_BF16, 64, 64)])
+def test_linear_store_recycles_released_blocks(dtype, Z, window):
+    B, Hq, Hkv, D, steps = 3, 4, 2, 64, 400
+    q, K, V = host_inputs(14, B, steps, Hq, Hkv, D, dtype)
+    live_tiles = (window - 2 + Z) // Z + 1 if window > 1 else 1   # most tiles a range touches
+    nb = B * (live_tiles + 1)                                      # one spare per sequence for the tile being opened
+    st = BlockStore(B, Hq, Hkv, D, Z, steps - 1, dtype, num_blocks=nb,
+                    block_table=torch.zeros((B, (steps - 1) // Z + 1), dtype=torch.int32), fill="nan")
+    qd, Kd, Vd = dev(q, dtype), dev(K, dtype), dev(V, dtype)
+    K64, V64 = K.astype(np.float64), V.astype(np.float64)
+    free = list(range(nb))
+    owner = {}                                                     # (b, tile) -> physical block
+    released = 0
+    out = torch.empty((steps, B, Hq, D), dtype=TDT[dtype], device=DEV)
+    for t in range(steps):
+        if t % Z == 0:                                             # a new tile opens: take blocks off the free list
+            for b in range(B):
+                owner[(b, t // Z)] = free.pop(0)
+                st.block_table[b, t // Z] = owner[(b, t // Z)]
+        st.step_window(qd[t], Kd[:, t].contiguous(), Vd[:, t].contiguous(), out[t], t, window)
+        dead_keys, dead_tiles = T.tempo_kv_release(t, window, Z)
+        for n in range(released, dead_tiles):                      # newly dead tiles: poison, then free
+            for b in range(B):
+                blk = owner.pop((b, n))
+                st.k_pool[blk] = float("nan")
+                st.v_pool[blk] = float("nan")
+                st.block_table[b, n] = nb - 1 - b                  # a stale entry must not matter either
+                free.append(blk)
+        released = max(released, dead_tiles)
+        assert len(owner) <= B * (live_tiles + 1)
+    torch.cuda.synchronize()
+    assert released == (steps - 1 - window + 2) // Z > 0
+    got = np64(out)
+    for t in list(range(0, steps, 7)) + [steps - 1]:
+        ref = oracle.attend(q[t].astype(np.float64), K64, V64, t, window, 1.0 / np.sqrt(D))
+        assert_close(got[t], ref, dtype, f"recycled linear store t={t} window={window}")
 
 
 # ----------------------------------------------------------------------------

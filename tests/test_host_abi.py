@@ -48,6 +48,23 @@ def test_visible_range_and_slot_match_oracle_bit_exact():
         T.tempo_append_slot(3, 0)
 
 
+def test_release_and_ring_size_match_oracle_bit_exact():
+    for Z in (1, 2, 3, 8, 64, 256):
+        for w in (0, 1, 2, 3, 9, 64, 65, 512, 513, 514):
+            for t in list(range(0, 40)) + [255, 256, 511, 512, 513, 4095]:
+                assert T.tempo_kv_release(t, w, Z) == oracle.release(t, w, Z), (t, w, Z)
+            for queries in (1, 2, 5, 42):
+                if w >= 1:
+                    assert T.tempo_ring_blocks(w, Z, queries) == oracle.ring_blocks(w, Z, queries), (w, Z, queries)
+    assert T.tempo_kv_release(2 ** 31 - 2, 1, 1) == (2 ** 31 - 1, 2 ** 31 - 1)   # no overflow at the top
+    for bad in ((-1, 3, 4), (3, -1, 4), (3, 3, 0), (2 ** 31 - 1, 1, 1)):
+        with pytest.raises(T.TempoError):
+            T.tempo_kv_release(*bad)
+    for bad in ((0, 8, 1), (8, 0, 1), (8, 8, 0), (2 ** 31 - 1, 1, 2 ** 31 - 1)):
+        with pytest.raises(T.TempoError):
+            T.tempo_ring_blocks(*bad)
+
+
 def kv_desc(dtype, D=128, Z=64, Hkv=2, num_blocks=3, max_blocks=4, pools=(1 << 20, 1 << 21, 1 << 22), ring=0):
     return T.tempo_kv(pools[0], pools[1], pools[2], num_blocks, max_blocks, Z, Hkv, D, dtype, ring)
 

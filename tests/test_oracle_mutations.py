@@ -29,6 +29,9 @@ PIN_TESTS = [
     pins.test_p11_rope_closed_forms,
     pins.test_p11_rope_is_a_rotation_with_relative_positions,
     pins.test_p11_rope_table_matches_closed_forms_and_rope,
+    pins.test_p12_release_follows_the_printed_inverse_window,
+    pins.test_p12_release_closed_forms_and_safety,
+    pins.test_p12_ring_blocks_is_the_smallest_power_of_two_that_holds,
 ]
 
 # (name, text to find, replacement) -- each is a mistake someone could make.
@@ -66,6 +69,17 @@ MUTATIONS = [
      "cos_out[(size_t)t * half + i] = sin(angle);\n      sin_out[(size_t)t * half + i] = cos(angle);"),
     ("rope table exponent", "const double angle = (double)t * pow(theta, -2.0 * (double)i / (double)D);",
      "const double angle = (double)t * pow(theta, -(double)i / (double)D);"),
+    ("release counts the step just answered as a reader", "for (int later = t + 1; !seen_later && later <= t + window; ++later) {",
+     "for (int later = t; !seen_later && later <= t + window; ++later) {"),
+    ("release skips the next step", "for (int later = t + 1; !seen_later && later <= t + window; ++later) {",
+     "for (int later = t + 2; !seen_later && later <= t + window; ++later) {"),
+    ("release counts partial tiles", "for (int first = 0; first + Z <= dead; first += Z) ++tiles;",
+     "for (int first = 0; first < dead; first += Z) ++tiles;"),
+    ("release under a causal pattern", "if (window == 0) seen_later = 1;", "if (window == 0) seen_later = 0;"),
+    ("ring forgets the block of queries", "const int last = first + queries - 1;", "const int last = first;"),
+    ("ring measured from the newest key only", "if (visible(j, first, window)) { oldest = j; break; }",
+     "if (visible(j, first, window)) { oldest = first; break; }"),
+    ("ring not rounded to a power of two", "while (ring < most) ring *= 2;", "ring = most;"),
     ("append slot one late", "for (int j = 0; j < t; ++j) {\n    if (++s == Z)", "for (int j = 0; j <= t; ++j) {\n    if (++s == Z)"),
 ]
 

@@ -366,6 +366,70 @@ def test_p10_static_tiling_fixture():
 
 
 # ----------------------------------------------------------------------------
+# P12 releases (Section 5.2: a stored step is released after its last reader, found
+#     from the inverse dependence) and the size of a circular store (Section 6).
+# ----------------------------------------------------------------------------
+def test_p12_release_follows_the_printed_inverse_window():
+    rows = [l for l in open(os.path.join(GOLDEN, "inverse_window.txt")) if not l.startswith("#")]
+    fwd, inv, keys = [c.strip() for c in rows[0].split("|")]
+    assert inv == "j:min(j+4,T)" and keys == "4"
+    window, T = 4, 60                                            # key j is read by steps j .. min(j+4,T)-1
+    for Z in (1, 3, 8):
+        for t in range(T - 4):
+            dead = [j for j in range(t + 1) if min(j + 4, T) - 1 <= t]     # last reader has run
+            assert dead == list(range(len(dead)))                          # a prefix
+            got_keys, got_tiles = oracle.release(t, window, Z)
+            assert got_keys == len(dead)
+            assert got_tiles == len(dead) // Z
+
+
+def test_p12_release_closed_forms_and_safety():
+    for Z in (1, 2, 5, 8):
+        for t in range(0, 50):
+            assert oracle.release(t, 0, Z) == (0, 0)             # causal: every later step reads everything
+            for w in (1, 2, 3, 7, 8, 9, 30, 100):
+                keys, tiles = oracle.release(t, w, Z)
+                assert keys == min(t + 1, max(0, t - w + 2))
+                assert tiles == keys // Z
+                # safe: no later step reads a dead key; tight: the first live key is read by step t+1
+                for later in range(t + 1, t + w + 3):
+                    assert oracle.visible_range(later, w, Z)["lo"] >= keys
+                if keys <= t:
+                    assert oracle.visible_range(t + 1, w, Z)["lo"] == keys
+    with pytest.raises(ValueError):
+        oracle.release(-1, 3, 4)
+
+
+def _circular_store_holds(window, Z, queries, ring, steps):
+    """Simulate a circular store of `ring` blocks: step t goes to block (t div Z) mod ring.  Does every
+    call that answers `queries` steps (written first) find all keys of its ranges still stored?"""
+    holds = [None] * ring                                        # which tile a block holds
+    for first in range(0, steps):
+        for t in range(first, first + queries):                  # the call's steps, and all before them
+            holds[(t // Z) % ring] = t // Z
+        # (earlier steps were written by earlier iterations or are rewritten identically here)
+        lo = max(0, first - window + 1)
+        for j in range(lo, first + queries):
+            if holds[(j // Z) % ring] != j // Z:
+                return False
+    return True
+
+
+def test_p12_ring_blocks_is_the_smallest_power_of_two_that_holds():
+    for Z in (1, 2, 3, 8):
+        for window in (1, 2, 3, 7, 8, 9, 10, 17, 33):
+            for queries in (1, 2, 5, 9):
+                ring = oracle.ring_blocks(window, Z, queries)
+                assert ring >= 1 and ring & (ring - 1) == 0
+                steps = 6 * Z * ring + window
+                assert _circular_store_holds(window, Z, queries, ring, steps), (Z, window, queries, ring)
+                if ring > 1:
+                    assert not _circular_store_holds(window, Z, queries, ring // 2, steps), (Z, window, queries)
+    with pytest.raises(ValueError):
+        oracle.ring_blocks(0, 8, 1)
+
+
+# ----------------------------------------------------------------------------
 # The input generator is shared by both sides, so pin what it promises.
 # ----------------------------------------------------------------------------
 # ----------------------------------------------------------------------------
