@@ -397,6 +397,8 @@ template <int NW>
 hipError_t launch_prefill_nw(const AttnParams& p, int batch, int D, int grid_splits, hipStream_t stream) {
   const int QB = prefill_block_steps(p.G, NW);
   const int nblocks = (p.queries + QB - 1) / QB;
+  // the kernel renumbers its workgroups with 32-bit arithmetic on the linear index
+  if ((int64_t)nblocks * grid_splits * p.Hkv * batch > INT32_MAX) return hipErrorInvalidConfiguration;
   const dim3 grid(nblocks * grid_splits, p.Hkv, batch);
   const dim3 block(64 * NW);
   const size_t lds = 2 * (size_t)(2 * (D / 32) + D / 16) * 1024;
