@@ -312,3 +312,33 @@ def test_bad_arguments_are_refused_before_any_launch():
     assert lib.tempo_kv_gather(ctypes.byref(good), fake, fake, 2, 0, 4 * 64 + 1, None) == T.TEMPO_ERR_RANGE
     assert T.tempo_attn_workspace_bytes(kv_desc(T.TEMPO_BF16, D=96), 2, 6, 100) == 0
     assert "workspace" in T.tempo_strerror(T.TEMPO_ERR_WORKSPACE)
+
+
+# ----------------------------------------------------------------------------
+# The product path never reaches for the CPU oracle, and without the built library
+# it fails loudly instead of falling back to anything.
+# ----------------------------------------------------------------------------
+def test_product_path_does_not_touch_the_oracle_and_has_no_fallback(monkeypatch):
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    pkg = os.path.join(root, "paper_2501_05408_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text, f
+                assert "tempo_oracle" not in text, f
+    bench = open(os.path.join(root, "bench.py")).read()
+    assert bench.count("from oracle import") == 1
+    assert bench.index("if not args.no_cpu:") < bench.index("from oracle import")   # inside the CPU-baseline leg
+    # no library, and no way to build one: load() raises
+    from paper_2501_05408_amd import build as B
+    monkeypatch.setattr(T, "_lib", None)
+    monkeypatch.setattr(B, "LIB", os.path.join(root, "no_such_dir", "libtempo.so"))
+
+    def cannot_build(force=True):
+        raise RuntimeError("no compiler here")
+
+    monkeypatch.setattr(B, "build", cannot_build)
+    with pytest.raises((RuntimeError, OSError)):
+        T.load()
+
