@@ -498,10 +498,10 @@ def main() -> int:
 
     # --- CPU baseline: the oracle on this machine's host cores (the only leg that touches it);
     #     its output also serves as a parity spot check of the timed configuration --------
+    K0, V0 = keep_flat
     if not args.no_cpu:
         from oracle import tempo_oracle as oracle
 
-        K0, V0 = keep_flat
         Kc = K0.float().cpu().numpy().astype(np.float64)
         Vc = V0.float().cpu().numpy().astype(np.float64)
         qc = q.float().cpu().numpy().astype(np.float64)

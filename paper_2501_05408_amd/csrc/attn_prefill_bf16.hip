@@ -125,13 +125,17 @@ __host__ __device__ inline int prefill_block_steps(int G, int waves) { return (1
 // independent inside an iteration, so they overlap instead of alternating.  Keys
 // therefore run one group ahead of values through LDS: two key buffers (groups n + 1,
 // n + 2) and two value buffers (groups n, n + 1).
-template <int D, int NW, bool kRope>
+template <int D, int NW, bool kRope, bool kStream>
 __global__ __launch_bounds__(64 * NW, PROMPT_MIN_WAVES) void attn_prefill_bf16(AttnParams p) {
   constexpr int KS = D / 32;
   constexpr int DT = D / 16;
   constexpr int KU = 2 * KS;                  // 1 KiB units of one group's keys
   constexpr int UNITS = KU + DT;              // ... and of its keys and values together
   constexpr int PER_THREAD = (UNITS + NW - 1) / NW;  // units each wavefront copies per iteration (at most)
+  // A block in front of a long history reads every key/value once and no other workgroup reads
+  // them again: non-temporal copies (the cache-policy bit the decode kernel's loads carry) keep
+  // them from displacing anything.  The blocks of a prompt share keys/values through L2: cached.
+  constexpr int kCachePolicy = kStream ? 2 : 0;
   extern __shared__ u32x4 lds[];              // keys [2][KU][64] x 16 bytes, then values [2][DT][64] x 16 bytes
   u32x4* const lds_k = lds;
   u32x4* const lds_v = lds + 2 * KU * 64;
@@ -248,7 +252,7 @@ __global__ __launch_bounds__(64 * NW, PROMPT_MIN_WAVES) void attn_prefill_bf16(A
       const int u = wave + NW * i;  // wave-uniform
       if (u < KU)  // (wavefronts beyond the units copy nothing)
         __builtin_amdgcn_global_load_lds((global_ptr)(from + u * 1024 + lane * 16),
-                                         (lds_ptr)(lds_k + ((gk & 1) * KU + u) * 64), 16, 0, 0);
+                                         (lds_ptr)(lds_k + ((gk & 1) * KU + u) * 64), 16, 0, kCachePolicy);
     }
   };
   auto issue_values = [&](int gv, int64_t offset) {
@@ -259,7 +263,7 @@ __global__ __launch_bounds__(64 * NW, PROMPT_MIN_WAVES) void attn_prefill_bf16(A
       const int u = wave + NW * i - KU;
       if (u >= 0 && u < DT)
         __builtin_amdgcn_global_load_lds((global_ptr)(from + u * 1024 + lane * 16),
-                                         (lds_ptr)(lds_v + ((gv & 1) * DT + u) * 64), 16, 0, 0);
+                                         (lds_ptr)(lds_v + ((gv & 1) * DT + u) * 64), 16, 0, kCachePolicy);
     }
   };
   // Slots beyond the block's last step may be unwritten (NaN): the 0 mask under the
@@ -402,12 +406,21 @@ hipError_t launch_prefill_nw(const AttnParams& p, int batch, int D, int grid_spl
   const dim3 grid(nblocks * grid_splits, p.Hkv, batch);
   const dim3 block(64 * NW);
   const size_t lds = 2 * (size_t)(2 * (D / 32) + D / 16) * 1024;
+  const bool stream_once = !p.direct;  // split path: each workgroup's range is read by nobody else
   if (p.rope_cos) {
-    if (D == 128) return launch((attn_prefill_bf16<128, NW, true>), grid, block, lds, stream, p);
-    return launch((attn_prefill_bf16<64, NW, true>), grid, block, lds, stream, p);
+    if (D == 128) {
+      return stream_once ? launch((attn_prefill_bf16<128, NW, true, true>), grid, block, lds, stream, p)
+                         : launch((attn_prefill_bf16<128, NW, true, false>), grid, block, lds, stream, p);
+    }
+    return stream_once ? launch((attn_prefill_bf16<64, NW, true, true>), grid, block, lds, stream, p)
+                       : launch((attn_prefill_bf16<64, NW, true, false>), grid, block, lds, stream, p);
   }
-  if (D == 128) return launch((attn_prefill_bf16<128, NW, false>), grid, block, lds, stream, p);
-  return launch((attn_prefill_bf16<64, NW, false>), grid, block, lds, stream, p);
+  if (D == 128) {
+    return stream_once ? launch((attn_prefill_bf16<128, NW, false, true>), grid, block, lds, stream, p)
+                       : launch((attn_prefill_bf16<128, NW, false, false>), grid, block, lds, stream, p);
+  }
+  return stream_once ? launch((attn_prefill_bf16<64, NW, false, true>), grid, block, lds, stream, p)
+                     : launch((attn_prefill_bf16<64, NW, false, false>), grid, block, lds, stream, p);
 }
 }  // namespace
 

@@ -46,6 +46,11 @@ int check_store(const tempo_kv* kv) {
 // over the eight wavefronts of the LDS-staged kernel (the same limit for fp32).
 // A single step of a group of more than 16 query heads is such a block of one step.
 constexpr int kMaxColumns = 128;
+// Up to this many columns the single-step kernel (one 16-column tile) serves the call.
+#ifndef TEMPO_NARROW_COLUMNS
+#define TEMPO_NARROW_COLUMNS 16
+#endif
+constexpr int kNarrowColumns = TEMPO_NARROW_COLUMNS;
 
 int check_heads(const tempo_kv* kv, int32_t batch, int32_t Hq) {
   if (batch < 1 || batch > 65535) return TEMPO_ERR_SHAPE;
@@ -304,7 +309,7 @@ int check_attn(const tempo_kv* kv, int32_t batch, int32_t Hq, int32_t t, int32_t
   if (kv->dtype == TEMPO_BF16) {
     const int columns = queries * (Hq / kv->num_kv_heads);
     // more than 16 columns go to the LDS-staged kernel, whose launch shape is fixed
-    if (columns <= 16 && partial_bf16_lds_bytes(plan->waves, columns, kv->head_dim) > kMaxLds) return TEMPO_ERR_SHAPE;
+    if (columns <= kNarrowColumns && partial_bf16_lds_bytes(plan->waves, columns, kv->head_dim) > kMaxLds) return TEMPO_ERR_SHAPE;
   }
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return TEMPO_ERR_WORKSPACE;
   if (workspace_bytes < plan_bytes(kv, (int64_t)batch * queries * Hq, plan->num_splits)) return TEMPO_ERR_WORKSPACE;
@@ -328,7 +333,7 @@ int do_partial(const tempo_kv* kv, const void* q, const void* k_new, const void*
     p.rope_sin = rope->sin;
   }
   const int32_t gs = grid_splits(plan, t, t_per_seq, window, queries, pad_t);
-  if (kv->dtype == TEMPO_BF16 && queries * p.G > 16)  // a wide block: the LDS-staged kernel, key range split as planned
+  if (kv->dtype == TEMPO_BF16 && queries * p.G > kNarrowColumns)  // a wide block: the LDS-staged kernel, key range split as planned
     return launch_status(launch_prefill_bf16(p, batch, kv->head_dim, gs, stream), "attn_block_partial");
   const hipError_t e = kv->dtype == TEMPO_BF16
                            ? launch_partial_bf16(p, batch, kv->head_dim, gs, plan->waves, stream)
@@ -354,16 +359,19 @@ void make_block_plan(const tempo_kv* kv, int32_t batch, int32_t Hq, int32_t t, i
   make_plan(kv, batch, Hq, last_step(t, queries), union_window(window, queries), ragged, plan);
   if (kv->dtype != TEMPO_BF16) return;
   const int columns = queries * (Hq / kv->num_kv_heads);
-  if (columns > 16) {
+  if (columns > kNarrowColumns) {
     // The LDS-staged kernel: its workgroups do more arithmetic per key than the decode
     // kernel's, so two per compute unit are wanted (measured at batch 16 x 8 heads,
     // t = 4095: 4 splits of 1024 keys 62-79 us for 30-126 columns, 2 splits 80-82 us).
     // Longest split length of at least 256 keys that gives >= 512 workgroups, else 256.
+    // Up to 32 columns a workgroup has only two wavefronts: twice as many workgroups
+    // (measured there: 8 splits of 512 keys 52.8-53.8 us, 4 splits of 1024 keys 55.5-56.1 us).
     const int32_t t_eff = last_step(t, queries), w_eff = union_window(window, queries);
     const int64_t pairs = (int64_t)batch * kv->num_kv_heads;
+    const int64_t want = (columns <= 32 ? 4 : 2) * (int64_t)kComputeUnits;
     int k = 8;
     for (int cand = 30; cand >= 8; --cand) {
-      if (pairs * splits_bound(t_eff, w_eff, cand) >= 2 * kComputeUnits) { k = cand; break; }
+      if (pairs * splits_bound(t_eff, w_eff, cand) >= want) { k = cand; break; }
     }
     while (splits_bound(t_eff, w_eff, k) > kMaxSplits) ++k;
     if (ragged && k > 10 && splits_bound(t_eff, w_eff, 10) <= kMaxSplits) k = 10;  // as for single steps
@@ -401,7 +409,7 @@ int decode(const tempo_kv* kv, const void* q, const void* k_new, const void* v_n
   // A group of more than 16 query heads runs in the LDS-staged kernel, which reads the
   // store only: the write (rotating the key when tables are given) goes first there too,
   // and the kernel rotates the queries.
-  const bool wide = kv->dtype == TEMPO_BF16 && queries * (Hq / kv->num_kv_heads) > 16;
+  const bool wide = kv->dtype == TEMPO_BF16 && queries * (Hq / kv->num_kv_heads) > kNarrowColumns;
   if (k_new && kv->dtype == TEMPO_BF16 && (wide || (!rope && (int64_t)batch * kv->num_kv_heads > kComputeUnits))) {
     const StoreParams sp = store_params(kv, batch, t, t_per_seq);
     const hipError_t e = rope ? launch_rope_append(sp, rope->cos, rope->sin, k_new, v_new, kv->head_dim, kv->dtype, s)
@@ -874,7 +882,7 @@ int tempo_attn_decode_partial(const tempo_kv* kv, const void* q, const void* k_n
   if ((rc = check_scale(scale)) != TEMPO_OK) return rc;
   if ((rc = check_attn(kv, batch, num_q_heads, t, window, t_per_seq != nullptr, plan, workspace, workspace_bytes)) != TEMPO_OK) return rc;
   // the kernel that serves a group of more than 16 heads does not write the store
-  if (k_new && kv->dtype == TEMPO_BF16 && num_q_heads / kv->num_kv_heads > 16) return TEMPO_ERR_SHAPE;
+  if (k_new && kv->dtype == TEMPO_BF16 && num_q_heads / kv->num_kv_heads > kNarrowColumns) return TEMPO_ERR_SHAPE;
   return do_partial(kv, q, k_new, v_new, nullptr, batch, num_q_heads, t, t_per_seq, window, scale, plan,
                     workspace, static_cast<hipStream_t>(stream));
 }
