@@ -362,7 +362,8 @@ void make_block_plan(const tempo_kv* kv, int32_t batch, int32_t Hq, int32_t t, i
   if (columns > kNarrowColumns) {
     // The LDS-staged kernel: its workgroups do more arithmetic per key than the decode
     // kernel's, so two per compute unit are wanted (measured at batch 16 x 8 heads,
-    // t = 4095: 4 splits of 1024 keys 62-79 us for 30-126 columns, 2 splits 80-82 us).
+    // t = 4095: 4 splits of 1024 keys 59-68 us for 63-126 columns, 2 splits 82-83 us,
+    // 8 splits 68-81 us).
     // Longest split length of at least 256 keys that gives >= 512 workgroups, else 256.
     // Up to 32 columns a workgroup has only two wavefronts: twice as many workgroups
     // (measured there: 8 splits of 512 keys 52.8-53.8 us, 4 splits of 1024 keys 55.5-56.1 us).
