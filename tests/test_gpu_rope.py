@@ -238,6 +238,71 @@ def test_fused_rope_step_large_positions_ring_bf16():
 
 
 # ----------------------------------------------------------------------------
+# A serving loop end to end: prompts of different lengths in one call (rotary producer
+# fused in), then decode steps in which every sequence stands at its own position
+# (fused rotate + append + attend), some through a block of steps; every decode output
+# against the oracle on the rotated history.
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("window", [0, 45])
+def test_prompt_then_ragged_decode_end_to_end(window):
+    B, Hq, Hkv, D, Z, T_len = 5, 6, 2, 128, 32, 260
+    dtype = T.TEMPO_BF16
+    q, K, V = host_inputs(58, B, T_len, Hq, Hkv, D, dtype)       # q [T][B][Hq][D]
+    cos_t, sin_t = tables(T_len, D)
+    table, nb = random_table(58, B, (T_len - 1) // Z + 1)
+    st = BlockStore(B, Hq, Hkv, D, Z, T_len - 1, dtype, num_blocks=nb, block_table=table, fill="nan")
+    st.set_rope(cos_t, sin_t)
+    Kd, Vd = dev(K, dtype), dev(V, dtype)
+    qd = dev(np.ascontiguousarray(np.transpose(q, (1, 0, 2, 3))), dtype)   # [B][T][Hq][D]
+    prompt = [130, 1, 64, 97, 33]                                 # prompt lengths
+    P = max(prompt)
+    cps = torch.tensor(prompt, dtype=torch.int32, device=DEV)
+    op = torch.zeros((B, P, Hq, D), dtype=torch.bfloat16, device=DEV)
+    st.prefill_attend(qd[:, :P].contiguous(), Kd[:, :P].contiguous(), Vd[:, :P].contiguous(), op, 0, P, window,
+                      count_per_seq=cps, rope=True)
+    qr64, Kr64 = oracle_rotated_kv(q, K, dtype)
+    V64 = V.astype(np.float64)
+    scale = 1.0 / np.sqrt(D)
+    got = np64(op)
+    for b in range(B):                                            # the last prompt step of every sequence
+        t = prompt[b] - 1
+        ref = oracle.attend(qr64[t][b:b + 1], Kr64[b:b + 1], V64[b:b + 1], t, window, scale)
+        assert_close(got[b:b + 1, t], ref, dtype, f"prompt seq {b} step {t}")
+    # decode: 60 single steps, each sequence at its own position
+    pos = list(prompt)
+    ar = torch.arange(B, device=DEV)
+    for step in range(60):
+        tps = torch.tensor(pos, dtype=torch.int32, device=DEV)
+        qb = torch.stack([qd[b, pos[b]] for b in range(B)]).contiguous()
+        out = st.rope_step(qb, Kd[ar, tps.long()].contiguous(), Vd[ar, tps.long()].contiguous(), st.new_out(),
+                           max(pos), window, tps)
+        if step % 7 == 0 or step == 59:
+            qref = np.stack([qr64[pos[b], b] for b in range(B)])
+            ref = oracle.attend(qref, Kr64, V64, np.array(pos, dtype=np.int32), window, scale)
+            assert_close(out, ref, dtype, f"decode step {step} positions {pos}")
+        pos = [x + 1 for x in pos]
+    # then a block of 9 steps per sequence (keys rotated by the separate producer, queries likewise)
+    C = 9
+    tps = torch.tensor(pos, dtype=torch.int32, device=DEV)
+    for c in range(C):
+        tc = tps + c
+        st.rope_append(Kd[ar, tc.long()].contiguous(), Vd[ar, tc.long()].contiguous(), max(pos) + c, tc.to(torch.int32))
+    qblk = torch.empty((B, C, Hq, D), dtype=torch.bfloat16, device=DEV)
+    for c in range(C):
+        tc = (tps + c).to(torch.int32)
+        qc = torch.stack([qd[b, pos[b] + c] for b in range(B)]).contiguous()
+        qblk[:, c] = st.rope_rotate(qc, torch.empty_like(qc), max(pos) + c, tc)
+    oblk = torch.empty_like(qblk)
+    st.attend_block(qblk, oblk, max(pos), C, window, tps)
+    gotb = np64(oblk)
+    for c in range(C):
+        tt = np.array([x + c for x in pos], dtype=np.int32)
+        qref = np.stack([qr64[pos[b] + c, b] for b in range(B)])
+        ref = oracle.attend(qref, Kr64, V64, tt, window, scale)
+        assert_close(gotb[:, c], ref, dtype, f"block step {c}")
+
+
+# ----------------------------------------------------------------------------
 # A prompt with the rotary producer fused in: keys rotated on their way into the
 # store (the bits tempo_rope_kv_append stores), queries when the prompt kernel
 # loads them; every step against the oracle, per-sequence lengths included.
