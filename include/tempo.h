@@ -354,6 +354,22 @@ int tempo_attn_block_window(const tempo_kv* kv, const void* q, void* out, int32_
                             size_t workspace_bytes, void* stream);
 
 /*
+ * The block entry points with unrotated queries: query c of sequence b is turned to its
+ * own position t + c (t_per_seq[b] + c) when the kernel loads it, with the arithmetic of
+ * tempo_rope_rotate (same bits as rotating first).  The store must already hold the
+ * rotated keys of steps up to t + queries - 1 (tempo_rope_kv_append_block).  rope as in
+ * tempo_rope_decode_step_*; everything else as tempo_attn_block_*.
+ */
+int tempo_rope_attn_block_causal(const tempo_kv* kv, const tempo_rope* rope, const void* q_raw,
+                                 void* out, int32_t batch, int32_t num_q_heads, int32_t queries,
+                                 int32_t t, const int32_t* t_per_seq, float scale, void* workspace,
+                                 size_t workspace_bytes, void* stream);
+int tempo_rope_attn_block_window(const tempo_kv* kv, const tempo_rope* rope, const void* q_raw,
+                                 void* out, int32_t batch, int32_t num_q_heads, int32_t queries,
+                                 int32_t t, const int32_t* t_per_seq, int32_t window, float scale,
+                                 void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Prompt processing (Section 2: prompt tokens are processed before decoding
  * starts; Section 4.3: the temporal dimension evaluated in tiles): steps
  * t .. t+count-1 of every sequence in ONE call.  The keys/values of those steps are
@@ -445,6 +461,18 @@ size_t tempo_attn_block_workspace_bytes(const tempo_kv* kv, int32_t batch, int32
  */
 int tempo_kv_append_block(const tempo_kv* kv, const void* k_new, const void* v_new, int32_t batch,
                           int32_t t, const int32_t* t_per_seq, int32_t count, void* stream);
+
+/*
+ * The same write with the rotary producer fused in (Section 6, "in-place writes": the
+ * kernel that produces the keys writes them into the store): row c of k_raw arrives
+ * unrotated and is turned to its own position t + c (t_per_seq[b] + c) on the way in;
+ * the store then holds the bits tempo_rope_kv_append would have written step by step.
+ * bf16 stores only (TEMPO_ERR_DTYPE otherwise); rope as in tempo_rope_kv_append, its
+ * tables must reach position t + count - 1.  Other errors as tempo_kv_append_block.
+ */
+int tempo_rope_kv_append_block(const tempo_kv* kv, const tempo_rope* rope, const void* k_raw,
+                               const void* v_new, int32_t batch, int32_t t, const int32_t* t_per_seq,
+                               int32_t count, void* stream);
 
 /*
  * Partial attention and split combine as two separate launches, with an explicit

@@ -588,6 +588,26 @@ int tempo_kv_append_block(const tempo_kv* kv, const void* k_new, const void* v_n
   return launch_status(e, "kv_append_block");
 }
 
+int tempo_rope_kv_append_block(const tempo_kv* kv, const tempo_rope* rope, const void* k_raw, const void* v_new,
+                               int32_t batch, int32_t t, const int32_t* t_per_seq, int32_t count, void* stream) {
+  int rc = check_store(kv);
+  if (rc != TEMPO_OK) return rc;
+  if (!k_raw || !v_new) return TEMPO_ERR_NULL;
+  if (kv->dtype != TEMPO_BF16) return TEMPO_ERR_DTYPE;  // the block write rotates in the bf16 kernels only
+  if (batch < 1 || batch > 65535) return TEMPO_ERR_SHAPE;
+  if (count < 1 || count > 65536) return TEMPO_ERR_SHAPE;
+  if (t < 0 || t > INT32_MAX - count) return TEMPO_ERR_RANGE;
+  if ((rc = check_step(kv, t + count - 1)) != TEMPO_OK) return rc;
+  if ((rc = check_rope(rope, kv->head_dim, t + count - 1)) != TEMPO_OK) return rc;
+  if (kv->ring_blocks && (int64_t)count > (int64_t)kv->ring_blocks * kv->block_size) return TEMPO_ERR_RANGE;
+  if ((int64_t)batch * count * kv->num_kv_heads * kv->head_dim > INT32_MAX) return TEMPO_ERR_SHAPE;
+  StoreParams p = store_params(kv, batch, t, t_per_seq, count);
+  p.rope_cos = rope->cos;
+  p.rope_sin = rope->sin;
+  const hipError_t e = launch_append(p, k_raw, v_new, kv->head_dim, kv->dtype, static_cast<hipStream_t>(stream));
+  return launch_status(e, "kv_rope_append_block");
+}
+
 int tempo_kv_gather(const tempo_kv* kv, void* k_out, void* v_out, int32_t batch, int32_t j0,
                     int32_t count, void* stream) {
   int rc = check_store(kv);
@@ -870,6 +890,25 @@ int tempo_attn_block_window(const tempo_kv* kv, const void* q, void* out, int32_
   if (window < 1 || window > INT32_MAX - 64) return TEMPO_ERR_RANGE;
   return decode(kv, q, nullptr, nullptr, out, batch, num_q_heads, t, t_per_seq, window, scale, workspace,
                 workspace_bytes, stream, queries);
+}
+
+int tempo_rope_attn_block_causal(const tempo_kv* kv, const tempo_rope* rope, const void* q_raw, void* out,
+                                 int32_t batch, int32_t num_q_heads, int32_t queries, int32_t t,
+                                 const int32_t* t_per_seq, float scale, void* workspace, size_t workspace_bytes,
+                                 void* stream) {
+  if (!rope) return TEMPO_ERR_NULL;
+  return decode(kv, q_raw, nullptr, nullptr, out, batch, num_q_heads, t, t_per_seq, 0, scale, workspace,
+                workspace_bytes, stream, queries, rope);
+}
+
+int tempo_rope_attn_block_window(const tempo_kv* kv, const tempo_rope* rope, const void* q_raw, void* out,
+                                 int32_t batch, int32_t num_q_heads, int32_t queries, int32_t t,
+                                 const int32_t* t_per_seq, int32_t window, float scale, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+  if (!rope) return TEMPO_ERR_NULL;
+  if (window < 1 || window > INT32_MAX - 64) return TEMPO_ERR_RANGE;
+  return decode(kv, q_raw, nullptr, nullptr, out, batch, num_q_heads, t, t_per_seq, window, scale, workspace,
+                workspace_bytes, stream, queries, rope);
 }
 
 int tempo_attn_decode_partial(const tempo_kv* kv, const void* q, const void* k_new,

@@ -133,14 +133,25 @@ class BlockStore:
                                             t_per_seq, s, self.workspace, self.workspace_bytes)
         return out
 
-    def attend_block(self, q, out, t, queries, window=0, t_per_seq=None, scale=None):
-        """Steps t .. t+queries-1 in one call; q, out are [batch][queries][Hq][D]."""
+    def rope_append_block(self, k_raw, v_new, t, count, t_per_seq=None):
+        """Write steps t .. t+count-1 with the keys rotated to their own positions on the way in."""
+        T.tempo_rope_kv_append_block(self.kv, self.rope, k_raw, v_new, self.batch, t, t_per_seq, count)
+
+    def attend_block(self, q, out, t, queries, window=0, t_per_seq=None, scale=None, rope=False):
+        """Steps t .. t+queries-1 in one call; q, out are [batch][queries][Hq][D].  With rope=True the
+        queries arrive unrotated (set_rope tables)."""
         ws_t = self.ring_blocks * self.Z + 32 if self.ring_blocks else self.max_t
         nbytes = T.tempo_attn_block_workspace_bytes(self.kv, self.batch, self.Hq, queries, ws_t)
         if getattr(self, "_block_ws", None) is None or self._block_ws.numel() < nbytes:
             self._block_ws = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
         s = self.scale if scale is None else scale
-        if window:
+        if rope and window:
+            T.tempo_rope_attn_block_window(self.kv, self.rope, q, out, self.batch, self.Hq, queries, t, t_per_seq,
+                                           window, s, self._block_ws, nbytes)
+        elif rope:
+            T.tempo_rope_attn_block_causal(self.kv, self.rope, q, out, self.batch, self.Hq, queries, t, t_per_seq, s,
+                                           self._block_ws, nbytes)
+        elif window:
             T.tempo_attn_block_window(self.kv, q, out, self.batch, self.Hq, queries, t, t_per_seq, window, s,
                                       self._block_ws, nbytes)
         else:

@@ -127,6 +127,11 @@ SIGNATURES = {
     "tempo_attn_block_plan": (ctypes.c_int, [_kvp, _i32, _i32, _i32, _i32, _i32, _i32, _planp]),
     "tempo_attn_block_workspace_bytes": (ctypes.c_size_t, [_kvp, _i32, _i32, _i32, _i32]),
     "tempo_kv_append_block": (ctypes.c_int, [_kvp, _vp, _vp, _i32, _i32, _vp, _i32, _vp]),
+    "tempo_rope_kv_append_block": (ctypes.c_int, [_kvp, _ropep, _vp, _vp, _i32, _i32, _vp, _i32, _vp]),
+    "tempo_rope_attn_block_causal": (ctypes.c_int, [_kvp, _ropep, _vp, _vp, _i32, _i32, _i32, _i32, _vp,
+                                                    ctypes.c_float, _vp, ctypes.c_size_t, _vp]),
+    "tempo_rope_attn_block_window": (ctypes.c_int, [_kvp, _ropep, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _i32,
+                                                    ctypes.c_float, _vp, ctypes.c_size_t, _vp]),
     "tempo_attn_decode_partial": (ctypes.c_int, [_kvp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _i32,
                                                  ctypes.c_float, _planp, _vp, ctypes.c_size_t, _vp]),
     "tempo_attn_decode_combine": (ctypes.c_int, [_kvp, _vp, _i32, _i32, _i32, _vp, _i32, _planp, _vp,
@@ -432,6 +437,27 @@ def tempo_attn_block_workspace_bytes(kv: tempo_kv, batch: int, num_q_heads: int,
 def tempo_kv_append_block(kv, k_new, v_new, batch, t, t_per_seq, count, stream=None):
     _check(load().tempo_kv_append_block(ctypes.byref(kv), _ptr(k_new), _ptr(v_new), batch, t,
                                         _ptr(t_per_seq), count, _stream(stream)), "tempo_kv_append_block")
+
+
+def tempo_rope_kv_append_block(kv, rope, k_raw, v_new, batch, t, t_per_seq, count, stream=None):
+    _check(load().tempo_rope_kv_append_block(ctypes.byref(kv), ctypes.byref(rope), _ptr(k_raw), _ptr(v_new), batch,
+                                             t, _ptr(t_per_seq), count, _stream(stream)),
+           "tempo_rope_kv_append_block")
+
+
+def tempo_rope_attn_block_causal(kv, rope, q_raw, out, batch, num_q_heads, queries, t, t_per_seq, scale, workspace,
+                                 workspace_bytes, stream=None):
+    _check(load().tempo_rope_attn_block_causal(ctypes.byref(kv), ctypes.byref(rope), _ptr(q_raw), _ptr(out), batch,
+                                               num_q_heads, queries, t, _ptr(t_per_seq), scale, _ptr(workspace),
+                                               workspace_bytes, _stream(stream)), "tempo_rope_attn_block_causal")
+
+
+def tempo_rope_attn_block_window(kv, rope, q_raw, out, batch, num_q_heads, queries, t, t_per_seq, window, scale,
+                                 workspace, workspace_bytes, stream=None):
+    _check(load().tempo_rope_attn_block_window(ctypes.byref(kv), ctypes.byref(rope), _ptr(q_raw), _ptr(out), batch,
+                                               num_q_heads, queries, t, _ptr(t_per_seq), window, scale,
+                                               _ptr(workspace), workspace_bytes, _stream(stream)),
+           "tempo_rope_attn_block_window")
 
 
 def tempo_attn_decode_partial(kv, q, k_new, v_new, batch, num_q_heads, t, t_per_seq, window, scale, plan,

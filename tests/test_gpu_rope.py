@@ -238,6 +238,65 @@ def test_fused_rope_step_large_positions_ring_bf16():
 
 
 # ----------------------------------------------------------------------------
+# Blocks with the rotary producer fused in: the rotating block write stores the bits of
+# step-by-step rotating appends, and the block call with unrotated queries gives the bits
+# of rotating first; every step of the block against the oracle.  Column counts on both
+# kernels (up to 16: single-step kernel; more: LDS-staged kernel), per-sequence steps.
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("C", [1, 4, 5, 9, 42])
+@pytest.mark.parametrize("window,ragged", [(0, False), (37, False), (0, True), (60, True)])
+def test_rope_block_write_and_block_attention(C, window, ragged):
+    B, Hq, Hkv, D, Z, T_len = 4, 6, 2, 128, 32, 200
+    dtype = T.TEMPO_BF16
+    q, K, V = host_inputs(59 + C, B, T_len, Hq, Hkv, D, dtype)
+    cos_t, sin_t = tables(T_len, D)
+    st = BlockStore(B, Hq, Hkv, D, Z, T_len - 1, dtype, fill="nan")
+    one = BlockStore(B, Hq, Hkv, D, Z, T_len - 1, dtype, fill="nan")
+    st.set_rope(cos_t, sin_t)
+    one.set_rope(cos_t, sin_t)
+    Kd, Vd = dev(K, dtype), dev(V, dtype)
+    qd = dev(np.ascontiguousarray(np.transpose(q, (1, 0, 2, 3))), dtype)   # [B][T][Hq][D]
+    first = [101, 64, 33, 150 - C] if ragged else [120] * B       # first step of each sequence's block
+    hist = max(first)
+    # history: steps 0 .. first[b]-1 of every sequence, one rotating append per step
+    ar = torch.arange(B, device=DEV)
+    for t in range(hist):
+        tps = torch.tensor([min(t, f - 1) for f in first], dtype=torch.int32, device=DEV)
+        for store in (st, one):
+            store.rope_append(Kd[ar, tps.long()].contiguous(), Vd[ar, tps.long()].contiguous(), t, tps)
+    fps = torch.tensor(first, dtype=torch.int32, device=DEV)
+    kblk = torch.stack([Kd[b, first[b]:first[b] + C] for b in range(B)]).contiguous()
+    vblk = torch.stack([Vd[b, first[b]:first[b] + C] for b in range(B)]).contiguous()
+    qblk = torch.stack([qd[b, first[b]:first[b] + C] for b in range(B)]).contiguous()
+    tp = fps if ragged else None
+    st.rope_append_block(kblk, vblk, hist, C, tp)
+    qrot = torch.empty_like(qblk)
+    for c in range(C):                                            # the same, one step at a time
+        tc = (fps + c).to(torch.int32)
+        one.rope_append(kblk[:, c].contiguous(), vblk[:, c].contiguous(), hist + c, tc)
+        qrot[:, c] = one.rope_rotate(qblk[:, c].contiguous(), torch.empty_like(qblk[:, c]), hist + c, tc)
+    torch.cuda.synchronize()
+    assert torch.equal(st.k_pool.view(torch.uint8), one.k_pool.view(torch.uint8))
+    assert torch.equal(st.v_pool.view(torch.uint8), one.v_pool.view(torch.uint8))
+    o_fused = torch.empty_like(qblk)
+    o_plain = torch.empty_like(qblk)
+    st.attend_block(qblk, o_fused, hist, C, window, tp, rope=True)
+    one.attend_block(qrot, o_plain, hist, C, window, tp)
+    assert torch.equal(o_fused.view(torch.uint8), o_plain.view(torch.uint8))
+    qr64, Kr64 = oracle_rotated_kv(q, K, dtype)
+    V64 = V.astype(np.float64)
+    got = np64(o_fused)
+    for c in range(C):
+        tt = np.array([f + c for f in first], dtype=np.int32)
+        qref = np.stack([qr64[first[b] + c, b] for b in range(B)])
+        ref = oracle.attend(qref, Kr64, V64, tt, window, 1.0 / np.sqrt(D))
+        assert_close(got[:, c], ref, dtype, f"rope block C={C} step {c} window={window} ragged={ragged}")
+    with pytest.raises(T.TempoError):                             # tables too short for the block's last step
+        short = T.make_rope(cos_t[:hist + C - 1].contiguous(), sin_t[:hist + C - 1].contiguous(), D)
+        T.tempo_rope_kv_append_block(st.kv, short, kblk, vblk, B, hist, tp, C)
+
+
+# ----------------------------------------------------------------------------
 # A serving loop end to end: prompts of different lengths in one call (rotary producer
 # fused in), then decode steps in which every sequence stands at its own position
 # (fused rotate + append + attend), some through a block of steps; every decode output
@@ -281,19 +340,15 @@ def test_prompt_then_ragged_decode_end_to_end(window):
             ref = oracle.attend(qref, Kr64, V64, np.array(pos, dtype=np.int32), window, scale)
             assert_close(out, ref, dtype, f"decode step {step} positions {pos}")
         pos = [x + 1 for x in pos]
-    # then a block of 9 steps per sequence (keys rotated by the separate producer, queries likewise)
+    # then a block of 9 steps per sequence: one rotating block write, one call with unrotated queries
     C = 9
     tps = torch.tensor(pos, dtype=torch.int32, device=DEV)
-    for c in range(C):
-        tc = tps + c
-        st.rope_append(Kd[ar, tc.long()].contiguous(), Vd[ar, tc.long()].contiguous(), max(pos) + c, tc.to(torch.int32))
-    qblk = torch.empty((B, C, Hq, D), dtype=torch.bfloat16, device=DEV)
-    for c in range(C):
-        tc = (tps + c).to(torch.int32)
-        qc = torch.stack([qd[b, pos[b] + c] for b in range(B)]).contiguous()
-        qblk[:, c] = st.rope_rotate(qc, torch.empty_like(qc), max(pos) + c, tc)
+    kblk = torch.stack([Kd[b, pos[b]:pos[b] + C] for b in range(B)]).contiguous()
+    vblk = torch.stack([Vd[b, pos[b]:pos[b] + C] for b in range(B)]).contiguous()
+    qblk = torch.stack([qd[b, pos[b]:pos[b] + C] for b in range(B)]).contiguous()
+    st.rope_append_block(kblk, vblk, max(pos), C, tps)
     oblk = torch.empty_like(qblk)
-    st.attend_block(qblk, oblk, max(pos), C, window, tps)
+    st.attend_block(qblk, oblk, max(pos), C, window, tps, rope=True)
     gotb = np64(oblk)
     for c in range(C):
         tt = np.array([x + c for x in pos], dtype=np.int32)

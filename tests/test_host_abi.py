@@ -283,6 +283,32 @@ def test_bad_arguments_are_refused_before_any_launch():
     assert lib.tempo_rope_rotate(ctypes.byref(rope_desc(head_dim=7)), fake, fake, T.TEMPO_F32, 2, 6, 5, None, None) == T.TEMPO_ERR_SHAPE
     assert lib.tempo_rope_rotate(ctypes.byref(rope_desc()), fake, fake, T.TEMPO_F32, 2, 6, 100, None, None) == T.TEMPO_ERR_RANGE
 
+    # blocks with the rotary producer: the rotating block write and the block call with raw queries
+    def rope_append_block(kv, rope, count=3, t=5):
+        r = ctypes.byref(rope) if rope is not None else None
+        return lib.tempo_rope_kv_append_block(ctypes.byref(kv), r, fake, fake, 2, t, None, count, None)
+
+    assert rope_append_block(good, None) == T.TEMPO_ERR_NULL
+    assert rope_append_block(kv_desc(T.TEMPO_F32), rope_desc()) == T.TEMPO_ERR_DTYPE
+    assert rope_append_block(good, rope_desc(), count=0) == T.TEMPO_ERR_SHAPE
+    assert rope_append_block(good, rope_desc(positions=7)) == T.TEMPO_ERR_RANGE      # steps 5..7 need 8 rows
+    assert rope_append_block(good, rope_desc(), t=4 * 64 - 2) == T.TEMPO_ERR_RANGE  # runs past the last block
+
+    def rope_block(rope, queries=3, t=5, w=None):
+        r = ctypes.byref(rope) if rope is not None else None
+        if w is None:
+            return lib.tempo_rope_attn_block_causal(ctypes.byref(good), r, fake, fake, 2, 6, queries, t, None, 0.1,
+                                                    None, 0, None)
+        return lib.tempo_rope_attn_block_window(ctypes.byref(good), r, fake, fake, 2, 6, queries, t, None, w, 0.1,
+                                                None, 0, None)
+
+    assert rope_block(None) == T.TEMPO_ERR_NULL
+    assert rope_block(rope_desc(positions=7)) == T.TEMPO_ERR_RANGE          # the last query stands at step 7
+    assert rope_block(rope_desc(), queries=0) == T.TEMPO_ERR_SHAPE
+    assert rope_block(rope_desc()) == T.TEMPO_ERR_WORKSPACE                  # everything else is fine
+    assert rope_block(rope_desc(), w=0) == T.TEMPO_ERR_RANGE
+    assert rope_block(rope_desc(), w=9) == T.TEMPO_ERR_WORKSPACE
+
     def prefill(kv, t=0, count=10, w=None, k=fake):
         if w is None:
             return lib.tempo_prefill_causal(ctypes.byref(kv), fake, k, fake, fake, 2, 6, t, count, None, 0.1, None, 0,
