@@ -153,6 +153,22 @@ def other_workloads(torch, T, BlockStore, synth, dev, kv_bytes_per_token):
                                   "kv_gbs": round(16 * 4096 * kv_bytes_per_token / dt / 1e9, 1),
                                   "separate_launches_us": round(dt3 * 1e6, 2),
                                   "note": "fused: rotate q,k + append + attend in 2 launches; separate: 4 launches"}
+    # the same for a block of 21 steps: one rotating block write + one block call with raw queries
+    C = 21
+    qc = synth.device_normal((16, C, Hq, D), 277, torch.bfloat16, dev)
+    kc = synth.device_normal((16, C, Hkv, D), 278, torch.bfloat16, dev)
+    vc = synth.device_normal((16, C, Hkv, D), 279, torch.bfloat16, dev)
+    oc = torch.empty_like(qc)
+
+    def rope_block(i):
+        sts[i % 8].rope_append_block(kc, vc, 4096 - C, C)
+        sts[i % 8].attend_block(qc, oc, 4096 - C, C, rope=True)
+
+    dt = _timed(torch, rope_block, 200, 20)
+    out[f"rope_block{C}_b16_t{4096 - C}"] = {"us_per_call": round(dt * 1e6, 2),
+                                             "us_per_query_step": round(dt * 1e6 / C, 2),
+                                             "note": "rotating block write + block attention with unrotated queries"}
+    del qc, kc, vc, oc
     del sts
     torch.cuda.empty_cache()
 
