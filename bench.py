@@ -271,6 +271,35 @@ def prompt_only(torch, T, BlockStore, synth, dev, repeats):
                          "peak": 2500.0, "unit": "TFLOP/s", "frac": round(flops / dt / 1e12 / 2500.0, 4)}}
 
 
+def block_only(torch, T, BlockStore, synth, dev, C, repeats):
+    """One block workload alone (for profiling the split path of the LDS-staged kernel): C query
+    steps of 16 sequences of the headline shape in front of 4096 - C stored steps, one block-store
+    write and one tempo_attn_block_causal call per repeat, 8 layer pools rotated."""
+    B, Hq, Hkv, D, Z = 16, 24, 8, 128, 256
+    sts = []
+    for layer in range(8):
+        st = BlockStore(B, Hq, Hkv, D, Z, 4095, T.TEMPO_BF16, device=dev)
+        st.k_pool.normal_()
+        st.v_pool.normal_()
+        sts.append(st)
+    q = synth.device_normal((B, C, Hq, D), 177, torch.bfloat16, dev)
+    k = synth.device_normal((B, C, Hkv, D), 178, torch.bfloat16, dev)
+    v = synth.device_normal((B, C, Hkv, D), 179, torch.bfloat16, dev)
+    o = torch.empty_like(q)
+
+    def step(i):
+        sts[i % 8].append_block(k, v, 4096 - C, C)
+        sts[i % 8].attend_block(q, o, 4096 - C, C)
+
+    dt = _timed(torch, step, repeats, 10)
+    plan = T.tempo_attn_block_plan(sts[0].kv, B, Hq, C, 4096 - C, 0)
+    nbytes = B * 4096 * 2 * Hkv * D * 2
+    return {"workload": f"block of {C} query steps x 16 sequences at t0={4096 - C}, llama-3.2-3b attention shape",
+            "us_per_call": round(dt * 1e6, 2), "kv_gbs": round(nbytes / dt / 1e9, 1),
+            "algorithmic_bytes_per_call": nbytes, "splits": plan.num_splits,
+            "tokens_per_split": plan.tokens_per_split}
+
+
 def tile_sweep(torch, T, BlockStore, synth, dev):
     """Tile-size sweep and padded baseline at T = 16384 (the shape of the paper's block-size
     figure, Section 7.2): for batch 4 and 16 and tile sizes Z = 32 .. 8192, the mean time of a
@@ -322,6 +351,9 @@ def main() -> int:
                     help="short run to put under rocprofv3 --pmc: pools filled directly with N(0,1), "
                          "W+K decode steps, then 4 copy launches of 256 MiB (the known-size kernel the "
                          "traffic counters are scaled by); no timing, no oracle")
+    ap.add_argument("--block-only", type=int, default=0, metavar="C",
+                    help="instead of the headline run: a block of C query steps at t0 = 4096 - C alone, "
+                         "--steps times, printed as one JSON line")
     ap.add_argument("--prompt-only", action="store_true",
                     help="instead of the headline run: the prompt-processing workload alone, --steps times "
                          "(use a small --steps), printed as one JSON line")
@@ -347,6 +379,10 @@ def main() -> int:
     T.load()
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.block_only:
+        print(json.dumps({"block_of_queries": block_only(torch, T, BlockStore, synth, dev, args.block_only,
+                                                         min(args.steps, 400))}))
+        return 0
     if args.prompt_only:
         print(json.dumps({"prompt_processing": prompt_only(torch, T, BlockStore, synth, dev, min(args.steps, 50))}))
         return 0
