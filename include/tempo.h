@@ -263,9 +263,10 @@ int tempo_decode_step_window(const tempo_kv* kv, const void* q, const void* k_ne
  * it).  Same result as tempo_attn_decode_causal at step t, but the kernel reads and
  * multiplies keys/values 0 .. t_pad of every sequence and masks those beyond the
  * step by index (their contents never matter).  For measurement: its time is that
- * of step t_pad whatever t is.  bf16 stores only (TEMPO_ERR_DTYPE otherwise);
- * t <= t_pad, and step t_pad must fit the store (TEMPO_ERR_RANGE).  workspace as
- * for step t_pad.
+ * of step t_pad whatever t is.  bf16 stores only (TEMPO_ERR_DTYPE otherwise) and
+ * groups of at most 16 query heads per key/value head (TEMPO_ERR_SHAPE otherwise:
+ * the kernel that serves larger groups has no padded form); t <= t_pad, and step
+ * t_pad must fit the store (TEMPO_ERR_RANGE).  workspace as for step t_pad.
  */
 int tempo_attn_decode_padded_causal(const tempo_kv* kv, const void* q, void* out, int32_t batch,
                                     int32_t num_q_heads, int32_t t, const int32_t* t_per_seq,

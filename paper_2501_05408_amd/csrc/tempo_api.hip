@@ -664,6 +664,9 @@ int tempo_attn_decode_padded_causal(const tempo_kv* kv, const void* q, void* out
                                     int32_t t_pad, float scale, void* workspace, size_t workspace_bytes,
                                     void* stream) {
   if (kv && kv->dtype == TEMPO_F32) return TEMPO_ERR_DTYPE;  // the baseline exists for the bf16 kernel only
+  // ... and in the single-step kernel only: the LDS-staged kernel that serves larger query
+  // groups walks the step's own range and knows no padding bound
+  if (kv && kv->num_kv_heads > 0 && num_q_heads / kv->num_kv_heads > kNarrowColumns) return TEMPO_ERR_SHAPE;
   if (t_pad < t) return TEMPO_ERR_RANGE;
   return decode(kv, q, nullptr, nullptr, out, batch, num_q_heads, t, t_per_seq, 0, scale, workspace,
                 workspace_bytes, stream, 1, nullptr, t_pad);

@@ -478,6 +478,35 @@ def test_llama_shape_causal_bf16_full_size():
         assert_close(out, ref, dtype, f"llama causal t={t}")
 
 
+def test_llama_shape_causal_bf16_full_size_every_step_appended():
+    # The whole causal workload the way a decoder runs it: t = 0 .. 4095, each step through the fused
+    # entry point (block-store write of step t + attention over 0..t in one call), no prefill.
+    B, Hq, Hkv, D, Z, T_len = 16, 24, 8, 128, 256, 4096
+    dtype = T.TEMPO_BF16
+    K, V = flat_kv(25, B, T_len, Hkv, D)
+    table, nb = random_table(25, B, T_len // Z, extra=0)
+    st = BlockStore(B, Hq, Hkv, D, Z, T_len - 1, dtype, num_blocks=nb, block_table=table, fill="nan")
+    Q = synth.device_normal((T_len, B, Hq, D), 2500, torch.bfloat16, DEV)
+    Kt, Vt = K.transpose(0, 1).contiguous(), V.transpose(0, 1).contiguous()      # [T][B][Hkv][D]
+    outs = torch.empty_like(Q)
+    for t in range(T_len):
+        st.step_causal(Q[t], Kt[t], Vt[t], outs[t], t)
+    torch.cuda.synchronize()
+    # the store now holds exactly the flat keys/values, bit for bit
+    kg, vg = st.gather(0, T_len)
+    assert torch.equal(kg, K) and torch.equal(vg, V)
+    del kg, vg, Kt, Vt
+    assert torch.isfinite(outs.float()).all()
+    # every step with t mod 256 in {0, 1, 254, 255}, every 16th step, and a few more
+    steps = sorted({t for t in range(T_len) if t % 256 in (0, 1, 254, 255)} | set(range(0, T_len, 16)) |
+                   {31, 32, 257, 1000, 2047, 2048, 3000, 4094, 4095})
+    K64, V64 = np64(K), np64(V)
+    Q64, got = np64(Q[steps]), np64(outs[steps])
+    for i, t in enumerate(steps):
+        ref = oracle.attend(Q64[i], K64, V64, t, 0, 1.0 / np.sqrt(D))             # reads keys 0..t only
+        assert_close(got[i], ref, dtype, f"llama causal, appended step by step, t={t}")
+
+
 def test_llama_shape_window_bf16_full_size():
     B, Hq, Hkv, D, Z, T_len, w = 16, 24, 8, 128, 256, 16384, 512
     dtype = T.TEMPO_BF16
@@ -496,6 +525,40 @@ def test_llama_shape_window_bf16_full_size():
         out = st.attend_window(q, st.new_out(), t, w)
         ref = oracle.attend(np64(q), K64, V64, t, w, 1.0 / np.sqrt(D))    # reads its window only
         assert_close(out, ref, dtype, f"llama window t={t}")
+
+
+def test_llama_shape_window_bf16_full_size_ring_store_every_step_appended():
+    # The window workload on the window store: a ring of tempo_ring_blocks(512, 256) blocks per
+    # sequence (constant memory), t = 0 .. 16383, each step through the fused entry point.
+    B, Hq, Hkv, D, Z, T_len, w = 16, 24, 8, 128, 256, 16384, 512
+    dtype = T.TEMPO_BF16
+    R = T.tempo_ring_blocks(w, Z)
+    need = oracle.ring_blocks(w, Z)
+    assert R >= need and R & (R - 1) == 0 and R // 2 < need        # the oracle's count, rounded up by the library
+    K, V = flat_kv(26, B, T_len, Hkv, D)
+    ring_table = torch.from_numpy(synth.permutation(26, 3, B * R).reshape(B, R).copy())
+    st = BlockStore(B, Hq, Hkv, D, Z, T_len - 1, dtype, num_blocks=B * R, block_table=ring_table,
+                    fill="nan", ring_blocks=R)
+    assert st.k_pool.numel() == B * R * Hkv * Z * D                 # R blocks per sequence, whatever T is
+    Q = synth.device_normal((T_len, B, Hq, D), 2600, torch.bfloat16, DEV)
+    Kt, Vt = K.transpose(0, 1).contiguous(), V.transpose(0, 1).contiguous()
+    outs = torch.empty_like(Q)
+    for t in range(T_len):
+        st.step_window(Q[t], Kt[t], Vt[t], outs[t], t, w)
+    torch.cuda.synchronize()
+    kg, vg = st.gather(T_len - w, w)                                 # the last window reads back exactly
+    assert torch.equal(kg, K[:, T_len - w:]) and torch.equal(vg, V[:, T_len - w:])
+    del kg, vg, Kt, Vt
+    assert torch.isfinite(outs.float()).all()
+    # every step below 1100, every block boundary and its neighbours, a seeded sample of 256 steps
+    steps = set(range(1100)) | {t for k in range(1, T_len // Z) for t in (k * Z - 1, k * Z, k * Z + 1)}
+    steps |= {int(x) for x in synth.integers(26, 5, 256, 0, T_len - 1)} | {5000, 8191, 8192, T_len - 1}
+    steps = sorted(steps)
+    K64, V64 = np64(K), np64(V)
+    Q64, got = np64(Q[steps]), np64(outs[steps])
+    for i, t in enumerate(steps):
+        ref = oracle.attend(Q64[i], K64, V64, t, w, 1.0 / np.sqrt(D))             # reads its window only
+        assert_close(got[i], ref, dtype, f"llama window on a ring, appended step by step, t={t}")
 
 
 def test_long_single_sequence_bf16_full_size():
@@ -518,41 +581,75 @@ def test_long_single_sequence_bf16_full_size():
         assert_close(out, ref, dtype, f"long t={t} 256-way plan")
 
 
+@pytest.mark.timeout(900)
 def test_ragged_multi_layer_shared_pool_bf16():
-    # The ragged multi-layer workload at its real per-layer shape (batch 64, lengths
-    # uniform in [1, 8192], one shared pool, a random block table per layer); 4 of
-    # the 28 layers, since layers are independent calls of identical geometry.
-    layers, B, Hq, Hkv, D, Z, T_max = 4, 64, 24, 8, 128, 256, 8192
+    # The ragged multi-layer workload at its real shape: 28 layers, batch 64, lengths uniform in
+    # [1, 8192], ONE shared pool that holds exactly the blocks the sequences need (about 30 GiB), a
+    # random block table per layer.  One decode step = per layer, the fused ragged step (append
+    # step L-1, attend over 0..L-1).  Every layer and every sequence is compared with the oracle.
+    layers, B, Hq, Hkv, D, Z, T_max = 28, 64, 24, 8, 128, 256, 8192
     dtype = T.TEMPO_BF16
     lengths = synth.integers(24, 1, B, 1, T_max)
     lengths[0], lengths[1] = 1, T_max                    # both extremes are present
-    blocks_per_seq = T_max // Z
-    perm = synth.permutation(24, 2, layers * B * blocks_per_seq)
-    tables = torch.from_numpy(perm.reshape(layers, B, blocks_per_seq).copy())
-    nb = layers * B * blocks_per_seq
+    need = (lengths.astype(np.int64) + Z - 1) // Z       # blocks per sequence
+    per_layer = int(need.sum())
+    nb = layers * per_layer
+    perm = synth.permutation(24, 2, nb)
     shape = (nb, Hkv, Z * D)
     k_pool = torch.full(shape, float("nan"), dtype=torch.bfloat16, device=DEV)
     v_pool = torch.full(shape, float("nan"), dtype=torch.bfloat16, device=DEV)
     len_d = torch.from_numpy(lengths).to(DEV)
     tps = (len_d - 1).to(torch.int32)
-    sample = [0, 1] + [int(i) for i in np.argsort(lengths)[[5, 20, 40, 60]]]
+    ar = torch.arange(B, device=DEV)
+    # the oracle's fp64 inputs travel through two reused pinned host buffers
+    pin_k = torch.empty((B, T_max, Hkv, D), dtype=torch.float64, pin_memory=True)
+    pin_v = torch.empty_like(pin_k, pin_memory=True)
+    stores, flats, outs = [], [], []
     for layer in range(layers):
-        K, V = flat_kv(240 + layer, B, T_max, Hkv, D)
-        st = BlockStore(B, Hq, Hkv, D, Z, T_max - 1, dtype, num_blocks=nb, block_table=tables[layer],
+        table = np.full((B, T_max // Z), -1, dtype=np.int32)        # entries beyond a sequence's blocks are never read
+        ids = perm[layer * per_layer:(layer + 1) * per_layer]
+        pos = 0
+        for b in range(B):
+            table[b, :need[b]] = ids[pos:pos + need[b]]
+            pos += int(need[b])
+        st = BlockStore(B, Hq, Hkv, D, Z, T_max - 1, dtype, num_blocks=nb, block_table=torch.from_numpy(table),
                         pools=(k_pool, v_pool))
-        # every sequence holds its steps 0..L-2; the fused ragged step appends step L-1 and attends
-        st.prefill(K, V, T_max - 2, lengths=torch.clamp(len_d - 1, min=1))
-        ar = torch.arange(B, device=DEV)
-        q = synth.device_normal((B, Hq, D), 2400 + layer, torch.bfloat16, DEV)
-        out = st.step_causal(q, K[ar, tps.long()].contiguous(), V[ar, tps.long()].contiguous(),
-                             st.new_out(), T_max - 1, t_per_seq=tps)
-        for b in sample:
+        K, V = flat_kv(240 + layer, B, T_max, Hkv, D)
+        # every sequence holds its steps 0..L-2 (one block-store write per sequence through a
+        # one-sequence view of the same store); the step itself appends step L-1
+        for b in range(B):
             L = int(lengths[b])
-            ref = oracle.attend(np64(q[b:b + 1]), np64(K[b:b + 1, :L]), np64(V[b:b + 1, :L]), L - 1, 0,
-                                1.0 / np.sqrt(D))
-            assert_close(out[b:b + 1], ref, dtype, f"layer {layer} seq {b} len {L}")
-        assert torch.isfinite(out.float()).all()
+            if L > 1:
+                one = T.make_kv(k_pool, v_pool, st.block_table[b:b + 1], nb, st.max_blocks_per_seq, Z, Hkv, D, dtype)
+                T.tempo_kv_append_block(one, K[b:b + 1, :L - 1].contiguous(), V[b:b + 1, :L - 1].contiguous(), 1, 0,
+                                        None, L - 1)
+        stores.append(st)
+        flats.append((K, V))
+    # the step: all 28 layers, one fused call each
+    qs = [synth.device_normal((B, Hq, D), 2400 + layer, torch.bfloat16, DEV) for layer in range(layers)]
+    for layer, st in enumerate(stores):
+        K, V = flats[layer]
+        outs.append(st.step_causal(qs[layer], K[ar, tps.long()].contiguous(), V[ar, tps.long()].contiguous(),
+                                   st.new_out(), T_max - 1, t_per_seq=tps))
+    torch.cuda.synchronize()
+    for layer, st in enumerate(stores):
+        K, V = flats[layer]
+        pin_k.copy_(K.double())
+        pin_v.copy_(V.double())
+        torch.cuda.synchronize()
+        ref = oracle.attend(np64(qs[layer]), pin_k.numpy(), pin_v.numpy(), lengths - 1, 0, 1.0 / np.sqrt(D))
+        assert_close(outs[layer], ref, dtype, f"ragged step, layer {layer}, all {B} sequences")
+        # the appended step is in the store (a short, a median and the longest sequence)
+        for b in (0, 1, int(np.argsort(lengths)[B // 2])):
+            L = int(lengths[b])
+            one = T.make_kv(k_pool, v_pool, st.block_table[b:b + 1], nb, st.max_blocks_per_seq, Z, Hkv, D, dtype)
+            kg = torch.empty((1, 1, Hkv, D), dtype=torch.bfloat16, device=DEV)
+            vg = torch.empty_like(kg)
+            T.tempo_kv_gather(one, kg, vg, 1, L - 1, 1)
+            assert torch.equal(kg[0, 0], K[b, L - 1]) and torch.equal(vg[0, 0], V[b, L - 1])
+        flats[layer] = None
         del K, V
+        print(f"ragged multi-layer: layer {layer} matches the oracle", flush=True)
 
 
 # ----------------------------------------------------------------------------

@@ -230,6 +230,17 @@ def test_bad_arguments_are_refused_before_any_launch():
     assert ring_causal(255) == T.TEMPO_ERR_WORKSPACE
     assert ring_causal(256) == T.TEMPO_ERR_RANGE
 
+    # the padded + masked baseline lives in the single-step kernel: bf16, groups of at most 16 heads
+    def padded(kv, Hq=6, t=5, t_pad=100):
+        return lib.tempo_attn_decode_padded_causal(ctypes.byref(kv), fake, fake, 2, Hq, t, None, t_pad, 0.1, None, 0,
+                                                   None)
+
+    assert padded(good) == T.TEMPO_ERR_WORKSPACE                 # everything else is fine
+    assert padded(good, Hq=2 * 16) == T.TEMPO_ERR_WORKSPACE
+    assert padded(good, Hq=2 * 17) == T.TEMPO_ERR_SHAPE          # served by a kernel with no padded form
+    assert padded(good, t=101) == T.TEMPO_ERR_RANGE
+    assert padded(kv_desc(T.TEMPO_F32)) == T.TEMPO_ERR_DTYPE
+
     def block(kv, queries, t=5, Hq=6, w=None):
         if w is None:
             return lib.tempo_attn_block_causal(ctypes.byref(kv), fake, fake, 2, Hq, queries, t, None, 0.1, None, 0, None)
