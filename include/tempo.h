@@ -25,8 +25,9 @@
  *  - Pointers marked "device" are HIP device pointers; `stream` is a
  *    hipStream_t passed as void* (NULL = the default stream).  Everything else
  *    is host memory.  The caller owns every buffer.  The library allocates
- *    nothing, never synchronises, keeps no state between calls, and every
- *    launch is asynchronous on `stream`; calls may be captured in a HIP graph.
+ *    nothing, never synchronises, keeps no state between calls (one exception:
+ *    tempo_decode_step_causal_noalloc, see there), and every launch is
+ *    asynchronous on `stream`; calls may be captured in a HIP graph.
  *  - `out` must not alias q, the pools or the workspace.
  *  - Results are deterministic: same inputs and same arguments, same bits.
  *  - Every entry point validates its arguments on the host and returns a
@@ -256,6 +257,30 @@ int tempo_decode_step_window(const tempo_kv* kv, const void* q, const void* k_ne
                              const void* v_new, void* out, int32_t batch, int32_t num_q_heads,
                              int32_t t, const int32_t* t_per_seq, int32_t window, float scale,
                              void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * tempo_decode_step_causal for callers that cannot allocate device memory at all, not
+ * even a workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, launches and results (bit for bit) as
+ * tempo_decode_step_causal, but the split partials live in an 8 MiB array that is part
+ * of the library's device code (one copy per GPU, held until the process ends) instead
+ * of a caller's workspace.  The call allocates and frees nothing.
+ *   - A step whose partials (tempo_attn_plan_workspace_bytes of the plan tempo_attn_plan
+ *     returns for it) exceed 8 MiB is refused with TEMPO_ERR_WORKSPACE and a message on
+ *     stderr; nothing is launched.  (The headline shape needs 0.4 MiB, a single sequence
+ *     at t = 65535 3.2 MiB, a ragged batch of 64 at t <= 8191 6.4 MiB.)
+ *   - The device that `stream` belongs to must be the current device.  The first call on
+ *     a device looks the array's address up (hipGetSymbolAddress) and keeps it: this is
+ *     the one piece of state the library holds.  Make that first call outside stream
+ *     capture.
+ *   - Every call on a GPU uses that GPU's one array, so calls that overlap in time on one
+ *     GPU (different streams, or threads) race; calls on one stream are ordered and safe.
+ *     The array's contents need no initialisation and mean nothing between calls.
+ */
+int tempo_decode_step_causal_noalloc(const tempo_kv* kv, const void* q, const void* k_new,
+                                     const void* v_new, void* out, int32_t batch,
+                                     int32_t num_q_heads, int32_t t, const int32_t* t_per_seq,
+                                     float scale, void* stream);
 
 /*
  * Padded + masked baseline (Section 2.1, workaround (c): pad the dynamic dimension

@@ -4,6 +4,8 @@
 #include <limits.h>
 #include <stdio.h>
 
+#include <mutex>
+
 #include "tempo_internal.h"
 
 namespace {
@@ -212,6 +214,41 @@ int launch_status(hipError_t e, const char* what) {
 }
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ---- statically allocated partials for callers that cannot allocate -----------------
+// tempo_decode_step_causal_noalloc keeps the split partials here instead of in a caller's
+// workspace.  Each GPU holds its own copy of the array, at its own address, until the
+// process ends.  In host code the array's name is only a handle for hipGetSymbolAddress:
+// the address kernels are given is the one that call returned for the current device.
+constexpr size_t kScratchBytes = (size_t)8 << 20;
+__attribute__((used)) static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device, resolved once per device.
+int scratch_on_current_device(void** ptr) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    fprintf(stderr, "libtempo: no current device for the static scratch array: %s\n", hipGetErrorString(e));
+    return TEMPO_ERR_LAUNCH;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) {
+      fprintf(stderr, "libtempo: hipGetSymbolAddress(scratch) failed on device %d: %s\n", dev, hipGetErrorString(e));
+      return TEMPO_ERR_LAUNCH;
+    }
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return TEMPO_OK;
+}
+
 
 // Workspace = [m,l: rows*S*2 f32] [acc: rows*S*D f32], each part padded to 256 bytes;
 // rows = batch * queries * Hq.
@@ -657,6 +694,29 @@ int tempo_decode_step_window(const tempo_kv* kv, const void* q, const void* k_ne
   if (window < 1) return TEMPO_ERR_RANGE;
   return decode(kv, q, k_new, v_new, out, batch, num_q_heads, t, t_per_seq, window, scale, workspace,
                 workspace_bytes, stream);
+}
+
+int tempo_decode_step_causal_noalloc(const tempo_kv* kv, const void* q, const void* k_new, const void* v_new,
+                                     void* out, int32_t batch, int32_t num_q_heads, int32_t t,
+                                     const int32_t* t_per_seq, float scale, void* stream) {
+  if (!k_new || !v_new) return TEMPO_ERR_NULL;
+  int rc = check_layout(kv);
+  if (rc != TEMPO_OK) return rc;
+  if (!q || !out) return TEMPO_ERR_NULL;
+  if ((rc = check_heads(kv, batch, num_q_heads)) != TEMPO_OK) return rc;
+  if (t < 0 || t > INT32_MAX - 64) return TEMPO_ERR_RANGE;
+  // the partials of this call's own plan must fit the static array
+  tempo_plan plan;
+  make_block_plan(kv, batch, num_q_heads, t, 0, t_per_seq != nullptr, 1, &plan);
+  const size_t need = plan_bytes(kv, (int64_t)batch * num_q_heads, plan.num_splits);
+  if (need > kScratchBytes) {
+    fprintf(stderr, "libtempo: tempo_decode_step_causal_noalloc: this step needs %zu bytes of split partials, "
+                    "the static array holds %zu; use tempo_decode_step_causal with a workspace\n", need, kScratchBytes);
+    return TEMPO_ERR_WORKSPACE;
+  }
+  void* ws = nullptr;
+  if ((rc = scratch_on_current_device(&ws)) != TEMPO_OK) return rc;
+  return decode(kv, q, k_new, v_new, out, batch, num_q_heads, t, t_per_seq, 0, scale, ws, kScratchBytes, stream);
 }
 
 int tempo_attn_decode_padded_causal(const tempo_kv* kv, const void* q, void* out, int32_t batch,

@@ -103,6 +103,12 @@ class BlockStore:
                                    self.workspace_bytes)
         return out
 
+    def step_causal_noalloc(self, q, k_new, v_new, out, t, t_per_seq=None, scale=None):
+        """step_causal with the split partials in the library's static device array (no workspace)."""
+        T.tempo_decode_step_causal_noalloc(self.kv, q, k_new, v_new, out, self.batch, self.Hq, t, t_per_seq,
+                                           self.scale if scale is None else scale)
+        return out
+
     def step_window(self, q, k_new, v_new, out, t, window, t_per_seq=None, scale=None):
         T.tempo_decode_step_window(self.kv, q, k_new, v_new, out, self.batch, self.Hq, t, t_per_seq, window,
                                    self.scale if scale is None else scale, self.workspace,

@@ -100,6 +100,8 @@ SIGNATURES = {
                                                 ctypes.c_float, _vp, ctypes.c_size_t, _vp]),
     "tempo_decode_step_window": (ctypes.c_int, [_kvp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _i32,
                                                 ctypes.c_float, _vp, ctypes.c_size_t, _vp]),
+    "tempo_decode_step_causal_noalloc": (ctypes.c_int, [_kvp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp,
+                                                        ctypes.c_float, _vp]),
     "tempo_attn_decode_padded_causal": (ctypes.c_int, [_kvp, _vp, _vp, _i32, _i32, _i32, _vp, _i32, ctypes.c_float,
                                                        _vp, ctypes.c_size_t, _vp]),
     "tempo_rope_rotate": (ctypes.c_int, [_ropep, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp]),
@@ -324,6 +326,14 @@ def tempo_decode_step_window(kv, q, k_new, v_new, out, batch, num_q_heads, t, t_
                                            batch, num_q_heads, t, _ptr(t_per_seq), window, scale,
                                            _ptr(workspace), workspace_bytes, _stream(stream)),
            "tempo_decode_step_window")
+
+
+def tempo_decode_step_causal_noalloc(kv, q, k_new, v_new, out, batch, num_q_heads, t, t_per_seq, scale,
+                                     stream=None):
+    _check(load().tempo_decode_step_causal_noalloc(ctypes.byref(kv), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out),
+                                                   batch, num_q_heads, t, _ptr(t_per_seq), scale,
+                                                   _stream(stream)),
+           "tempo_decode_step_causal_noalloc")
 
 
 def tempo_attn_decode_padded_causal(kv, q, out, batch, num_q_heads, t, t_per_seq, t_pad, scale, workspace,
