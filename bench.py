@@ -444,6 +444,50 @@ def step_only(torch, T, BlockStore, synth, dev, name, repeats):
             "kv_bytes_per_step": nbytes, "kv_gbs": round(nbytes / r["median"] / 1e9, 1)}
 
 
+def plan_sweep(torch, T, BlockStore, synth, dev):
+    """Every explicit split plan against the library's own choice: causal decode of the Llama head
+    shape at batch 4, 16 and 64 and several steps; one attention call per step (the store already
+    holds step t) through tempo_attn_block_with_plan, 8 rotated layer pools, median over chunks."""
+    Hq, Hkv, D, Z = 24, 8, 128, 256
+    out = {}
+    for batch in (4, 16, 64):
+        sts = []
+        for layer in range(8):
+            st = BlockStore(batch, Hq, Hkv, D, Z, 8191, T.TEMPO_BF16, device=dev)
+            st.k_pool.normal_()
+            st.v_pool.normal_()
+            sts.append(st)
+        q = synth.device_normal((batch, Hq, D), 61, torch.bfloat16, dev)
+        o = sts[0].new_out()
+        for t in (255, 1023, 2047, 4095, 8191):
+            lib = T.tempo_attn_plan(sts[0].kv, batch, Hq, t, 0)
+            rows = {}
+            for k in range(7, 14):                                        # 128 .. 8192 keys per split
+                tps = 1 << k
+                splits = t // tps + 1
+                if splits > 1024 or (splits == 1 and tps >= 2 * (t + 1)):
+                    continue                                              # longer single splits are the same plan
+                for waves in (4, 8):
+                    if tps // 32 < waves:
+                        continue
+                    plan = T.tempo_plan(tps, splits, waves)
+                    nbytes = T.tempo_attn_plan_workspace_bytes(sts[0].kv, batch, Hq, plan)
+                    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+
+                    def call(i):
+                        T.tempo_attn_block_with_plan(sts[i % 8].kv, q, o, batch, Hq, 1, t, None, 0, sts[0].scale, plan,
+                                                     ws, nbytes)
+
+                    rows[f"{tps}x{waves}"] = us(gpu_timed(torch, call, 100, 10)["median"])
+            lib_us = us(gpu_timed(torch, lambda i: sts[i % 8].attend_causal(q, o, t), 100, 10)["median"])
+            out[f"b{batch}_t{t}"] = {"plans_us": rows, "library_plan": f"{lib.tokens_per_split}x{lib.waves}",
+                                     "library_splits": lib.num_splits, "library_us": lib_us,
+                                     "best_us": min(rows.values())}
+        del sts
+        torch.cuda.empty_cache()
+    return out
+
+
 def tile_sweep(torch, T, BlockStore, synth, dev):
     """Tile-size sweep and padded baseline at T = 16384 (the shape of the paper's block-size
     figure, Section 7.2): for batch 4 and 16 and tile sizes Z = 32 .. 8192, the mean time of a
@@ -583,6 +627,9 @@ def main() -> int:
     ap.add_argument("--step-only", default="", metavar="NAME",
                     help="instead of the headline run: one launch-bound step alone, --steps times "
                          "(window512, long8191 or t255), printed as one JSON line")
+    ap.add_argument("--plan-sweep", action="store_true",
+                    help="instead of the headline run: every explicit split plan against the library's choice at "
+                         "batch 4, 16, 64, printed as one JSON line")
     ap.add_argument("--tile-sweep", action="store_true",
                     help="instead of the headline run: tile-size sweep and padded baseline at T=16384, "
                          "printed as one JSON line")
@@ -615,6 +662,9 @@ def main() -> int:
     if args.step_only:
         print(json.dumps({"launch_bound_step": step_only(torch, T, BlockStore, synth, dev, args.step_only,
                                                          min(args.steps, 2000))}))
+        return 0
+    if args.plan_sweep:
+        print(json.dumps({"plan_sweep": plan_sweep(torch, T, BlockStore, synth, dev)}))
         return 0
     if args.tile_sweep:
         print(json.dumps({"tile_size_sweep": tile_sweep(torch, T, BlockStore, synth, dev)}))

@@ -246,7 +246,7 @@ __global__ __launch_bounds__(512) void attn_partial_bf16(AttnParams p) {
     logits_of_group<D>(p, qreg, g, x);
     if (more) load_keys<D>(p, base_nxt, lane, g);  // the key registers are free again
 
-    uint32_t keep[4];
+    uint32_t keep[4] = {~0u, ~0u, ~0u, ~0u};
     const bool cut = (grp << 5) < all_lo || (grp << 5) + 31 > all_hi;  // wave-uniform
     if (cut) {
       mask_logits(grp, lo_col, hi_col, lane, x);
@@ -255,15 +255,15 @@ __global__ __launch_bounds__(512) void attn_partial_bf16(AttnParams p) {
     const bf16x8 pa = softmax_update<D>(x, lane, st);
 
     if (grp == grp_new) append_values<D>(p, base, t_b, lane, stage, g);
-    if (cut) {  // 0 mask under the sums: unwritten slots may hold NaN, and 0 * NaN is NaN
+    // 0 mask under the sums: unwritten slots may hold NaN, and 0 * NaN is NaN.  The mask (all
+    // ones for a group no range cuts) is applied to a copy that feeds the product, never to
+    // the group's registers themselves.
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt) {
-        g.v[dt].x &= keep[0]; g.v[dt].y &= keep[1]; g.v[dt].z &= keep[2]; g.v[dt].w &= keep[3];
-      }
+    for (int dt = 0; dt < DT; ++dt) {
+      u32x4 vv = g.v[dt];
+      vv.x &= keep[0]; vv.y &= keep[1]; vv.z &= keep[2]; vv.w &= keep[3];
+      st.acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, as_bf16x8(vv), st.acc[dt], 0, 0, 0);
     }
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-      st.acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, as_bf16x8(g.v[dt]), st.acc[dt], 0, 0, 0);
     if (more) load_values<D>(p, base_nxt, lane, g);  // the value registers are free again
 
     grp = nxt;

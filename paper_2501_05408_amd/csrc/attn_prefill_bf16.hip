@@ -30,13 +30,6 @@
 // blocks that follow find it in that die's L2; the longest blocks come first.
 #include "attn_bf16_common.h"
 
-// The instantiation that is built for prompts: wavefronts per workgroup (each with one
-// tile of 16 columns) and the occupancy (wavefronts per SIMD) the register allocation
-// must allow.
-#ifndef PROMPT_NW
-#define PROMPT_NW 8
-#define PROMPT_MIN_WAVES 1
-#endif
 
 namespace tempo {
 namespace {
@@ -126,7 +119,7 @@ __host__ __device__ inline int prefill_block_steps(int G, int waves) { return (1
 // therefore run one group ahead of values through LDS: two key buffers (groups n + 1,
 // n + 2) and two value buffers (groups n, n + 1).
 template <int D, int NW, bool kRope, bool kStream>
-__global__ __launch_bounds__(64 * NW, PROMPT_MIN_WAVES) void attn_prefill_bf16(AttnParams p) {
+__global__ __launch_bounds__(64 * NW) void attn_prefill_bf16(AttnParams p) {
   constexpr int KS = D / 32;
   constexpr int DT = D / 16;
   constexpr int KU = 2 * KS;                  // 1 KiB units of one group's keys
@@ -392,7 +385,7 @@ __global__ __launch_bounds__(64 * NW, PROMPT_MIN_WAVES) void attn_prefill_bf16(A
 // The prompt path uses kPromptWaves wavefronts; a single block of fewer columns gets a
 // workgroup of just enough wavefronts (2, 4 or 8), so that several workgroups share a
 // compute unit and the kernel stays bound by HBM.
-constexpr int kPromptWaves = PROMPT_NW;
+constexpr int kPromptWaves = 8;
 
 int prefill_bf16_block_steps(int G) { return prefill_block_steps(G, kPromptWaves); }
 

@@ -49,10 +49,7 @@ int check_store(const tempo_kv* kv) {
 // A single step of a group of more than 16 query heads is such a block of one step.
 constexpr int kMaxColumns = 128;
 // Up to this many columns the single-step kernel (one 16-column tile) serves the call.
-#ifndef TEMPO_NARROW_COLUMNS
-#define TEMPO_NARROW_COLUMNS 16
-#endif
-constexpr int kNarrowColumns = TEMPO_NARROW_COLUMNS;
+constexpr int kNarrowColumns = 16;
 
 int check_heads(const tempo_kv* kv, int32_t batch, int32_t Hq) {
   if (batch < 1 || batch > 65535) return TEMPO_ERR_SHAPE;
@@ -184,10 +181,11 @@ void make_plan(const tempo_kv* kv, int32_t batch, int32_t Hq, int32_t t_max, int
   plan->num_splits = splits_bound(t_max, window, best_k);
   // About 8 wavefronts per compute unit keep the memory pipe full: 4 per workgroup
   // when a unit gets two or more workgroups, 8 when it gets at most one (measured:
-  // 256 workgroups x 8 waves 42.4 us, x 4 waves 43.4 us; 512 x 4 waves 42.7 us).
+  // 256 workgroups x 8 waves 42.4 us, x 4 waves 43.4 us; 512 x 4 waves 42.7 us), down
+  // to one 32-slot group per wavefront (256 keys at batch 16: 7.7 us with 8, 8.2 with 4).
   const int groups = plan->tokens_per_split / 32;
   const int64_t workgroups = pairs * plan->num_splits;
-  if (workgroups <= kComputeUnits && groups >= 16) plan->waves = 8;
+  if (workgroups <= kComputeUnits && groups >= 8) plan->waves = 8;
   else plan->waves = groups >= 4 ? 4 : groups;
 }
 

@@ -384,3 +384,27 @@ def test_product_path_does_not_touch_the_oracle_and_has_no_fallback(monkeypatch)
     with pytest.raises((RuntimeError, OSError)):
         T.load()
 
+
+def test_planner_choice_is_near_the_best_measured_plan():
+    """The split planner against a sweep of explicit plans measured on an MI355X and kept in
+    profiles/ (batch 4, 16 and 64; the planner's time model was fitted at batch 16): the plan the
+    library picks must have been measured within 5% of the fastest plan of its case."""
+    path = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "profiles",
+                        "attn_partial_bf16_plan_sweep.txt")
+    cases = {}
+    for line in open(path):
+        parts = line.split()
+        if len(parts) == 3 and parts[0].startswith("b") and "_t" in parts[0] and "x" in parts[1]:
+            cases.setdefault(parts[0], {})[parts[1]] = float(parts[2])
+    assert len(cases) >= 15
+    for case, plans in cases.items():
+        batch, t = int(case[1:case.index("_t")]), int(case[case.index("_t") + 2:])
+        kv = kv_desc(T.TEMPO_BF16, D=128, Z=256, Hkv=8, num_blocks=batch * 32, max_blocks=32)
+        plan = T.tempo_attn_plan(kv, batch, 24, t, 0)
+        tps = plan.tokens_per_split
+        if plan.num_splits == 1:                       # every single split that covers the range is the same plan
+            tps = 1 << (t + 1 - 1).bit_length() if t > 0 else 32
+            tps = max(tps, 32)
+        key = f"{tps}x{plan.waves}"
+        assert key in plans, f"{case}: the library's plan {key} was not part of the sweep"
+        assert plans[key] <= 1.05 * min(plans.values()), (case, key, plans[key], min(plans.values()))
