@@ -149,6 +149,54 @@ __device__ inline u32x4 rotate_fetched_key(const AttnParams& p, int pos, int lan
   return fetched;
 }
 
+// ---- merge of the workgroup's wavefronts -----------------------------------------------
+// Every wavefront has left its (m, l) per column at smem[w][16] / smem[NW][w][16] and its
+// accumulators at smem[2*NW*16 ...][w][ncols][D].  Thread idx owns element (column j, dim d):
+// all NW wavefronts' values of that element are requested at once, so the merge costs one trip
+// to LDS, not one per wavefront.  NW is a template parameter so that no wave-count predicate
+// sits between the barrier and the stores.
+template <int D, int NW>
+__device__ __forceinline__ void merge_waves(const AttnParams& p, const float* smem, int ncols, int b, int hkv, int split) {
+  const float* sm_m = smem;
+  const float* sm_l = smem + NW * 16;
+  const float* sm_acc = smem + NW * 32;
+  for (int idx = threadIdx.x; idx < ncols * D; idx += 64 * NW) {
+    const int j = idx / D, d = idx - j * D;
+    float mw[NW], lw[NW], aw[NW];
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      mw[w] = sm_m[w * 16 + j];
+      lw[w] = sm_l[w * 16 + j];
+      aw[w] = sm_acc[(w * ncols + j) * D + d];
+    }
+    float M = mw[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) M = fmaxf(M, mw[w]);
+    float num = 0.f, den = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      // a wavefront that saw no key of this column contributes nothing, whatever it holds
+      const bool seen = mw[w] != -INFINITY;
+      const float wgt = fast_exp2(mw[w] - M);
+      num += seen ? wgt * aw[w] : 0.f;
+      den += seen ? wgt * lw[w] : 0.f;
+    }
+    const int jc = p.queries == 1 ? 0 : j / p.G, jg = j - jc * p.G;
+    if (p.direct) {
+      const int64_t orow = ((int64_t)b * p.io_steps + jc) * p.Hq + (int64_t)hkv * p.G + jg;
+      static_cast<__bf16*>(p.out)[orow * D + d] = (__bf16)(num / den);
+    } else {
+      const int64_t row = ((int64_t)b * p.queries + jc) * p.Hq + (int64_t)hkv * p.G + jg;
+      const int64_t part = row * p.num_splits + split;
+      p.ws_acc[part * D + d] = num;
+      if (d == 0) {
+        p.ws_ml[part * 2] = M;
+        p.ws_ml[part * 2 + 1] = den;
+      }
+    }
+  }
+}
+
 template <int D, bool kRope>
 __global__ __launch_bounds__(512) void attn_partial_bf16(AttnParams p) {
   constexpr int KS = D / 32;
@@ -295,32 +343,10 @@ __global__ __launch_bounds__(512) void attn_partial_bf16(AttnParams p) {
 
   // Merge the wavefronts of the workgroup (same rule the split combine uses).  A
   // column that saw no key in this split leaves (m, l, acc) = (-inf, 0, 0).
-  for (int idx = threadIdx.x; idx < ncols * D; idx += blockDim.x) {
-    const int j = idx / D, d = idx - j * D;
-    float M = -INFINITY;
-    for (int w = 0; w < nwaves; ++w) M = fmaxf(M, sm_m[w * 16 + j]);
-    float num = 0.f, den = 0.f;
-    for (int w = 0; w < nwaves; ++w) {
-      const float mw = sm_m[w * 16 + j];
-      if (mw == -INFINITY) continue;  // a wavefront that saw no key of this column
-      const float wgt = fast_exp2(mw - M);
-      num += wgt * sm_acc[(w * ncols + j) * D + d];
-      den += wgt * sm_l[w * 16 + j];
-    }
-    const int jc = j / p.G, jg = j - jc * p.G;
-    const int64_t row = ((int64_t)b * p.queries + jc) * p.Hq + (int64_t)hkv * p.G + jg;
-    if (p.direct) {
-      const int64_t orow = ((int64_t)b * p.io_steps + jc) * p.Hq + (int64_t)hkv * p.G + jg;
-      static_cast<__bf16*>(p.out)[orow * D + d] = (__bf16)(num / den);
-    } else {
-      const int64_t part = row * p.num_splits + split;
-      p.ws_acc[part * D + d] = num;
-      if (d == 0) {
-        p.ws_ml[part * 2] = M;
-        p.ws_ml[part * 2 + 1] = den;
-      }
-    }
-  }
+  if (nwaves == 8) merge_waves<D, 8>(p, smem, ncols, b, hkv, split);
+  else if (nwaves == 4) merge_waves<D, 4>(p, smem, ncols, b, hkv, split);
+  else if (nwaves == 2) merge_waves<D, 2>(p, smem, ncols, b, hkv, split);
+  else merge_waves<D, 1>(p, smem, ncols, b, hkv, split);
 }
 
 }  // namespace

@@ -218,23 +218,29 @@ def test_fused_rope_step_ragged(dtype):
 # Large positions on a ring store (angles of ~1e5 radians), and the headline shape.
 # ----------------------------------------------------------------------------
 def test_fused_rope_step_large_positions_ring_bf16():
+    # A ring store at positions around 1e5: the window's worth of history before the first answered
+    # step is written with rotating appends, then every step goes through the fused rotary step.
     B, Hq, Hkv, D, Z, R, window, t0, n = 2, 6, 2, 128, 32, 4, 70, 100000, 120
     dtype = T.TEMPO_BF16
-    q, K, V = host_inputs(54, B, n, Hq, Hkv, D, dtype)
+    hist = window - 1                                   # steps t0-hist .. t0-1 are history
+    q, K, V = host_inputs(54, B, hist + n, Hq, Hkv, D, dtype)
     c, s = oracle.rope_table(t0 + n, D, THETA)
     cos_t = torch.from_numpy(c.astype(np.float32)).to(DEV)
     sin_t = torch.from_numpy(s.astype(np.float32)).to(DEV)
     st = BlockStore(B, Hq, Hkv, D, Z, 2 ** 30, dtype, ring_blocks=R, fill="nan")
     st.set_rope(cos_t, sin_t)
     qd, Kd, Vd = dev(q, dtype), dev(K, dtype), dev(V, dtype)
-    Kr = np.stack([oracle.rope(K[:, i].astype(np.float64), t0 + i, THETA) for i in range(n)], axis=1)
+    first = t0 - hist                                   # position of row 0 of K, V
+    Kr = np.stack([oracle.rope(K[:, i].astype(np.float64), first + i, THETA) for i in range(hist + n)], axis=1)
     Kr = synth.round_to_bf16(Kr.astype(np.float32)).astype(np.float64)
     V64 = V.astype(np.float64)
-    for i in range(n):
-        out = st.rope_step(qd[i], Kd[:, i].contiguous(), Vd[:, i].contiguous(), st.new_out(), t0 + i, window)
-        qr = synth.round_to_bf16(oracle.rope(q[i].astype(np.float64), t0 + i, THETA).astype(np.float32)).astype(np.float64)
+    for i in range(hist):
+        st.rope_append(Kd[:, i].contiguous(), Vd[:, i].contiguous(), first + i)
+    for i in range(hist, hist + n):
+        out = st.rope_step(qd[i], Kd[:, i].contiguous(), Vd[:, i].contiguous(), st.new_out(), first + i, window)
+        qr = synth.round_to_bf16(oracle.rope(q[i].astype(np.float64), first + i, THETA).astype(np.float32)).astype(np.float64)
         ref = oracle.attend(qr, Kr[:, :i + 1], V64[:, :i + 1], i, window, 1.0 / np.sqrt(D))
-        assert_close(out, ref, dtype, f"ring rope step t={t0 + i}")
+        assert_close(out, ref, dtype, f"ring rope step t={first + i}")
 
 
 # ----------------------------------------------------------------------------
