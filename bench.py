@@ -321,9 +321,16 @@ def other_workloads(torch, T, BlockStore, synth, dev, kv_bytes_per_token):
     del sts
     torch.cuda.empty_cache()
 
-    # ragged multi-layer: 28 layers, batch 64, lengths uniform in [1, 8192], one shared pool with
-    # exactly the blocks the sequences need, a random block table per layer
+    out["ragged_28layers_b64"] = ragged_step_bench(torch, T, BlockStore, synth, dev, kv_bytes_per_token)
+    return out
+
+
+def ragged_step_bench(torch, T, BlockStore, synth, dev, kv_bytes_per_token, repeats=10):
+    """Ragged multi-layer decode step: 28 layers, batch 64, lengths uniform in [1, 8192], one shared
+    pool with exactly the blocks the sequences need, a random block table per layer; one step = per
+    layer one fused call (block-store write + attention over each sequence's own range)."""
     import numpy as np
+    Hq, Hkv, D, Z = 24, 8, 128, 256
     n_layers, B = 28, 64
     lengths = synth.integers(24, 1, B, 1, 8192)
     need = (lengths.astype(np.int64) + Z - 1) // Z                       # blocks per sequence
@@ -352,19 +359,28 @@ def other_workloads(torch, T, BlockStore, synth, dev, kv_bytes_per_token):
         for st in sts:
             st.step_causal(q64, k64, v64, o, 8191, t_per_seq=tps)
 
-    dt = gpu_timed(torch, ragged_step, 10, 2, chunk=1)["median"]
-    gdt = graph_timed(torch, ragged_step, 1, 10)["median"]
+    def ragged_step_listed(_):
+        # the work list depends on the steps only: built once per decode step, used by all 28 layers
+        worklist = sts[0].build_worklist(8191, tps)
+        for st in sts:
+            st.step_ragged(q64, k64, v64, o, 8191, tps, worklist)
+
+    dense = gpu_timed(torch, ragged_step, repeats, 2, chunk=1)["median"]
+    listed = gpu_timed(torch, ragged_step_listed, repeats, 2, chunk=1)["median"]
+    dt = min(dense, listed)
+    gdt = graph_timed(torch, ragged_step, 1, repeats)["median"]
     step_bytes = n_layers * int(lengths.astype(np.int64).sum()) * kv_bytes_per_token
     plan = T.tempo_attn_plan(sts[0].kv, B, Hq, 8191, 0, True)
-    out["ragged_28layers_b64"] = {"ms_per_step": round(dt * 1e3, 3), "graph_ms_per_step": round(gdt * 1e3, 3),
-                                  "kv_gbs": round(step_bytes / dt / 1e9, 1),
-                                  "kv_bytes_per_step": step_bytes, "pool_gib": round(2 * k_pool.numel() * 2 / 2**30, 1),
-                                  "splits": plan.num_splits, "tokens_per_split": plan.tokens_per_split,
-                                  "roofline": hbm_roofline("attn_partial_bf16<128, false>", step_bytes, min(dt, gdt),
-                                                           "all 28 layers (block-store write, attention, combine each); "
-                                                           "the faster of eager and one graph of the 28 layers"),
-                                  "lengths": [int(x) for x in lengths]}
-    return out
+    return {"ms_per_step": round(dt * 1e3, 3), "ms_per_step_work_list": round(listed * 1e3, 3),
+            "ms_per_step_dense_grid": round(dense * 1e3, 3), "graph_ms_per_step": round(gdt * 1e3, 3),
+            "kv_gbs": round(step_bytes / dt / 1e9, 1), "kv_bytes_per_step": step_bytes,
+            "pool_gib": round(2 * k_pool.numel() * 2 / 2**30, 1),
+            "splits": plan.num_splits, "tokens_per_split": plan.tokens_per_split, "waves": plan.waves,
+            "roofline": hbm_roofline("attn_partial_bf16<128, false>", step_bytes, min(dt, gdt),
+                                     "all 28 layers (block-store write, attention, combine each, plus one work-list "
+                                     "launch per step when listed); the fastest of dense grid, work list and one "
+                                     "graph of the 28 dense layers"),
+            "lengths": [int(x) for x in lengths]}
 
 
 def prompt_only(torch, T, BlockStore, synth, dev, repeats):
@@ -626,7 +642,7 @@ def main() -> int:
                          "(use a small --steps), printed as one JSON line")
     ap.add_argument("--step-only", default="", metavar="NAME",
                     help="instead of the headline run: one launch-bound step alone, --steps times "
-                         "(window512, long8191 or t255), printed as one JSON line")
+                         "(window512, long8191, t255, or ragged = the 28-layer ragged step), printed as one JSON line")
     ap.add_argument("--plan-sweep", action="store_true",
                     help="instead of the headline run: every explicit split plan against the library's choice at "
                          "batch 4, 16, 64, printed as one JSON line")
@@ -658,6 +674,10 @@ def main() -> int:
         return 0
     if args.prompt_only:
         print(json.dumps({"prompt_processing": prompt_only(torch, T, BlockStore, synth, dev, min(args.steps, 50))}))
+        return 0
+    if args.step_only == "ragged":
+        print(json.dumps({"ragged_step": ragged_step_bench(torch, T, BlockStore, synth, dev, 2 * 8 * 128 * 2,
+                                                           min(args.steps, 100))}))
         return 0
     if args.step_only:
         print(json.dumps({"launch_bound_step": step_only(torch, T, BlockStore, synth, dev, args.step_only,

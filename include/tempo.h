@@ -259,6 +259,43 @@ int tempo_decode_step_window(const tempo_kv* kv, const void* q, const void* k_ne
                              void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Ragged decode steps with a work list.  Static tiling (Section 4.3) trades a dynamic range
+ * for a dynamic NUMBER of static tiles; when every sequence of a batch is at its own step
+ * (t_per_seq), that number differs per sequence.  tempo_decode_step_causal / _window then
+ * launch a dense grid over (sequence, largest split count) whose surplus workgroups exit at
+ * once.  The work list names only the (sequence, split) items that exist, longest first (all
+ * full splits, then each sequence's newest split by size), so the launch holds no empty
+ * workgroups and ends on its smallest items.  The list depends on the steps only, not on the
+ * pools or the block table: build it once per decode step and pass it to every layer's call.
+ *
+ * tempo_attn_worklist_bytes   bytes of a list for steps up to t_max (host only; 0 on
+ *                             unsupported arguments).
+ * tempo_attn_worklist_build   one small launch that writes the list (device, 4-byte aligned,
+ *                             at least tempo_attn_worklist_bytes bytes) from t_per_seq (device,
+ *                             [batch]; each clamped to [0, t_max]).  window = 0: causal.
+ * tempo_decode_step_ragged    tempo_decode_step_causal (window = 0) or _window at per-sequence
+ *                             steps, its partial-attention launch driven by the list; k_new
+ *                             and v_new may both be NULL (the store already holds the steps).
+ *                             Same results, bit for bit, as the entry points without a list.
+ * The list is valid for exactly the batch, head counts, t_max, window and t_per_seq VALUES it
+ * was built from; a stale list gives wrong results (never a fault: an item outside a
+ * sequence's range is skipped).  bf16 stores with at most 16 query heads per key/value head
+ * (TEMPO_ERR_DTYPE / TEMPO_ERR_SHAPE otherwise), batch * splits <= 65535 (TEMPO_ERR_SHAPE).
+ */
+size_t tempo_attn_worklist_bytes(const tempo_kv* kv, int32_t batch, int32_t num_q_heads,
+                                 int32_t t_max, int32_t window);
+
+int tempo_attn_worklist_build(const tempo_kv* kv, int32_t batch, int32_t num_q_heads, int32_t t_max,
+                              const int32_t* t_per_seq, int32_t window, void* worklist,
+                              size_t worklist_bytes, void* stream);
+
+int tempo_decode_step_ragged(const tempo_kv* kv, const void* q, const void* k_new, const void* v_new,
+                             void* out, int32_t batch, int32_t num_q_heads, int32_t t_max,
+                             const int32_t* t_per_seq, int32_t window, float scale,
+                             const void* worklist, void* workspace, size_t workspace_bytes,
+                             void* stream);
+
+/*
  * tempo_decode_step_causal for callers that cannot allocate device memory at all, not
  * even a workspace: code under HIP graph capture, tight serving loops, harnesses that
  * forbid hipMalloc.  Same arguments, launches and results (bit for bit) as

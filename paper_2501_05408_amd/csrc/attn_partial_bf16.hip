@@ -205,16 +205,27 @@ __global__ __launch_bounds__(512) void attn_partial_bf16(AttnParams p) {
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nwaves = blockDim.x >> 6;
-  const int hkv = blockIdx.x, b = blockIdx.y;
+  const int hkv = blockIdx.x;
+  // Which (sequence, split) this workgroup takes: its grid position, or, for a ragged batch
+  // with a work list, the list's item (non-empty items only, longest first).
+  int b = blockIdx.y, zsplit = blockIdx.z;
+  if (p.worklist) {
+    const_i32_ptr list = (const_i32_ptr)p.worklist;
+    if ((int)blockIdx.y >= list[0]) return;  // uniform over the workgroup
+    const int item = list[1 + blockIdx.y];
+    b = item & 0xFFFF;
+    zsplit = (int)((unsigned)item >> 16);
+  }
   int t_b = p.t_per_seq ? ((const_i32_ptr)p.t_per_seq)[b] : p.t;
   t_b = t_b > p.t ? p.t : (t_b < 0 ? 0 : t_b);
   const SeqRange rg = seq_range(t_b, p.window, p.tps_log2, p.queries, p.pad_t);
-  if ((int)blockIdx.z >= rg.nchunks) return;  // uniform over the workgroup
+  if (zsplit >= rg.nchunks) return;  // uniform over the workgroup
   // Dispatch order: the split index is the slowest grid dimension and runs from
   // the newest split to the oldest.  The newest split of every (sequence, head)
   // is the one a fused append lands in and the one t may cut short; launching
   // all of those first keeps their longer path out of the launch's last round.
-  const int split = rg.nchunks - 1 - (int)blockIdx.z;
+  // (A work list names the split itself.)
+  const int split = p.worklist ? zsplit : rg.nchunks - 1 - zsplit;
   const int chunk = rg.chunk0 + split;
   const int cs = chunk << p.tps_log2, ce = ((chunk + 1) << p.tps_log2) - 1;
   const int start = rg.lo > cs ? rg.lo : cs;
@@ -360,7 +371,9 @@ size_t partial_bf16_lds_bytes(int waves, int columns, int D) {
 hipError_t launch_partial_bf16(const AttnParams& p, int batch, int D, int grid_splits, int waves,
                                hipStream_t stream) {
   if (p.queries * p.G > 16) return hipErrorInvalidConfiguration;
-  const dim3 grid(p.Hkv, batch, grid_splits);
+  // with a work list: one grid row per possible item, the rows beyond the list's count exit at once
+  const dim3 grid = p.worklist ? dim3(p.Hkv, (unsigned)((int64_t)batch * grid_splits), 1) : dim3(p.Hkv, batch, grid_splits);
+  if (grid.y > 65535u) return hipErrorInvalidConfiguration;
   const dim3 block(64 * waves);
   const size_t lds = partial_bf16_lds_bytes(waves, p.queries * p.G, D);
   if (p.rope_cos) {

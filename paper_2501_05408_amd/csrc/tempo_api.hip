@@ -273,6 +273,7 @@ AttnParams attn_params(const tempo_kv* kv, const void* q, void* out, int32_t Hq,
   p.count_per_seq = nullptr;
   p.rope_cos = nullptr;
   p.rope_sin = nullptr;
+  p.worklist = nullptr;
   char* ws = static_cast<char*>(workspace);
   p.ws_ml = reinterpret_cast<float*>(ws);
   p.ws_acc = reinterpret_cast<float*>(ws + ml_bytes((int64_t)batch * queries * Hq, plan->num_splits));
@@ -357,9 +358,11 @@ int check_attn(const tempo_kv* kv, int32_t batch, int32_t Hq, int32_t t, int32_t
 int do_partial(const tempo_kv* kv, const void* q, const void* k_new, const void* v_new, void* out,
                int32_t batch, int32_t Hq, int32_t t, const int32_t* t_per_seq, int32_t window,
                float scale, const tempo_plan* plan, void* workspace, hipStream_t stream,
-               int32_t queries = 1, const tempo_rope* rope = nullptr, int32_t pad_t = 0, int32_t io_steps = 0) {
+               int32_t queries = 1, const tempo_rope* rope = nullptr, int32_t pad_t = 0, int32_t io_steps = 0,
+               const int32_t* worklist = nullptr) {
   AttnParams p = attn_params(kv, q, out, Hq, t, t_per_seq, window, scale, plan, workspace, batch, queries, pad_t);
   if (io_steps > 0) p.io_steps = io_steps;
+  p.worklist = worklist;
   p.direct = (out != nullptr && plan->num_splits == 1) ? 1 : 0;
   p.k_new = k_new;
   p.v_new = v_new;
@@ -422,7 +425,7 @@ void make_block_plan(const tempo_kv* kv, int32_t batch, int32_t Hq, int32_t t, i
 int decode(const tempo_kv* kv, const void* q, const void* k_new, const void* v_new, void* out,
            int32_t batch, int32_t Hq, int32_t t, const int32_t* t_per_seq, int32_t window, float scale,
            void* workspace, size_t workspace_bytes, void* stream, int32_t queries = 1,
-           const tempo_rope* rope = nullptr, int32_t pad_t = 0) {
+           const tempo_rope* rope = nullptr, int32_t pad_t = 0, const int32_t* worklist = nullptr) {
   int rc = check_layout(kv);
   if (rc != TEMPO_OK) return rc;
   if (!q || !out) return TEMPO_ERR_NULL;
@@ -454,7 +457,7 @@ int decode(const tempo_kv* kv, const void* q, const void* k_new, const void* v_n
     k_new = v_new = nullptr;
   }
   rc = do_partial(kv, q, k_new, v_new, out, batch, Hq, t, t_per_seq, window, scale, &plan, workspace, s, queries,
-                  rope, pad_t);
+                  rope, pad_t, 0, worklist);
   if (rc != TEMPO_OK || plan.num_splits == 1) return rc;  // a single split wrote `out` itself
   return do_combine(kv, out, batch, Hq, t, t_per_seq, window, &plan, workspace, s, queries, pad_t);
 }
@@ -715,6 +718,56 @@ int tempo_decode_step_causal_noalloc(const tempo_kv* kv, const void* q, const vo
   void* ws = nullptr;
   if ((rc = scratch_on_current_device(&ws)) != TEMPO_OK) return rc;
   return decode(kv, q, k_new, v_new, out, batch, num_q_heads, t, t_per_seq, 0, scale, ws, kScratchBytes, stream);
+}
+
+// The work list of a ragged step is tied to the plan the step will use: both come from
+// make_block_plan with the same arguments.
+static int worklist_plan(const tempo_kv* kv, int32_t batch, int32_t Hq, int32_t t_max, int32_t window, tempo_plan* plan) {
+  int rc = check_layout(kv);
+  if (rc != TEMPO_OK) return rc;
+  if ((rc = check_heads(kv, batch, Hq)) != TEMPO_OK) return rc;
+  if (t_max < 0 || t_max > INT32_MAX - 64 || window < 0) return TEMPO_ERR_RANGE;
+  // the list is read by the single-step bf16 kernel only
+  if (kv->dtype != TEMPO_BF16) return TEMPO_ERR_DTYPE;
+  if (Hq / kv->num_kv_heads > kNarrowColumns) return TEMPO_ERR_SHAPE;
+  make_block_plan(kv, batch, Hq, t_max, window, true, 1, plan);
+  if ((int64_t)batch * plan->num_splits > 65535) return TEMPO_ERR_SHAPE;  // one grid row per possible item
+  return TEMPO_OK;
+}
+
+size_t tempo_attn_worklist_bytes(const tempo_kv* kv, int32_t batch, int32_t num_q_heads, int32_t t_max,
+                                 int32_t window) {
+  tempo_plan plan;
+  if (worklist_plan(kv, batch, num_q_heads, t_max, window, &plan) != TEMPO_OK) return 0;
+  return align_up(sizeof(int32_t) * (1 + (size_t)batch * plan.num_splits), 256);
+}
+
+int tempo_attn_worklist_build(const tempo_kv* kv, int32_t batch, int32_t num_q_heads, int32_t t_max,
+                              const int32_t* t_per_seq, int32_t window, void* worklist, size_t worklist_bytes,
+                              void* stream) {
+  tempo_plan plan;
+  const int rc = worklist_plan(kv, batch, num_q_heads, t_max, window, &plan);
+  if (rc != TEMPO_OK) return rc;
+  if (!t_per_seq || !worklist) return TEMPO_ERR_NULL;
+  if ((reinterpret_cast<uintptr_t>(worklist) & 3u) != 0) return TEMPO_ERR_WORKSPACE;
+  if (worklist_bytes < sizeof(int32_t) * (1 + (size_t)batch * plan.num_splits)) return TEMPO_ERR_WORKSPACE;
+  const hipError_t e = launch_worklist_build(t_per_seq, batch, t_max, window, ilog2_exact(plan.tokens_per_split),
+                                             plan.num_splits, static_cast<int32_t*>(worklist),
+                                             static_cast<hipStream_t>(stream));
+  return launch_status(e, "worklist_build");
+}
+
+int tempo_decode_step_ragged(const tempo_kv* kv, const void* q, const void* k_new, const void* v_new, void* out,
+                             int32_t batch, int32_t num_q_heads, int32_t t_max, const int32_t* t_per_seq,
+                             int32_t window, float scale, const void* worklist, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+  if (!t_per_seq || !worklist) return TEMPO_ERR_NULL;
+  if ((k_new == nullptr) != (v_new == nullptr)) return TEMPO_ERR_NULL;
+  tempo_plan plan;
+  const int rc = worklist_plan(kv, batch, num_q_heads, t_max, window, &plan);
+  if (rc != TEMPO_OK) return rc;
+  return decode(kv, q, k_new, v_new, out, batch, num_q_heads, t_max, t_per_seq, window, scale, workspace,
+                workspace_bytes, stream, 1, nullptr, 0, static_cast<const int32_t*>(worklist));
 }
 
 int tempo_attn_decode_padded_causal(const tempo_kv* kv, const void* q, void* out, int32_t batch,

@@ -82,6 +82,8 @@ struct AttnParams {
   const int32_t* count_per_seq;  // prompt kernel: may be null; sequence b answers only its first count_per_seq[b] steps
   const float* rope_cos;     // [positions][D/2]; non-null: q (and k_new) arrive unrotated and are
   const float* rope_sin;     //   rotated to their step's position inside the kernel
+  const int32_t* worklist;   // bf16 decode kernel: may be null; [0] = number of items, then one item per
+                             //   workgroup row: sequence in the low 16 bits, split in the high 16
   float* ws_ml;              // [B][C][Hq][S][2]  (running max in log2 units, running sum)
   float* ws_acc;             // [B][C][Hq][S][D]
   void* out;                 // [B][C][Hq][D]
@@ -157,6 +159,8 @@ hipError_t launch_rope_rotate(const float* rope_cos, const float* rope_sin, cons
 hipError_t launch_rope_append(const StoreParams& p, const float* rope_cos, const float* rope_sin,
                               const void* k_raw, const void* v_new, int D, int dtype, hipStream_t stream);
 hipError_t launch_combine(const AttnParams& p, int batch, int D, int dtype, hipStream_t stream);
+hipError_t launch_worklist_build(const int32_t* t_per_seq, int batch, int t_max, int window, int tps_log2,
+                                 int num_splits, int32_t* worklist, hipStream_t stream);
 hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, int workgroups,
                               hipStream_t stream);
 hipError_t launch_stream_copy(const void* src, void* dst, size_t bytes, int workgroups,

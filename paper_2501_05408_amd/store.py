@@ -103,6 +103,23 @@ class BlockStore:
                                    self.workspace_bytes)
         return out
 
+    def build_worklist(self, t_max, t_per_seq, window=0):
+        """The work list of a ragged step at per-sequence steps t_per_seq (int32 device tensor): the
+        non-empty (sequence, split) items, longest first.  Valid for every store of the same shape."""
+        nbytes = T.tempo_attn_worklist_bytes(self.kv, self.batch, self.Hq, t_max, window)
+        if nbytes == 0:
+            raise T.TempoError(T.TEMPO_ERR_SHAPE, "tempo_attn_worklist_bytes")
+        worklist = torch.empty(nbytes // 4, dtype=torch.int32, device=self.device)
+        T.tempo_attn_worklist_build(self.kv, self.batch, self.Hq, t_max, t_per_seq, window, worklist, nbytes)
+        return worklist
+
+    def step_ragged(self, q, k_new, v_new, out, t_max, t_per_seq, worklist, window=0, scale=None):
+        """The ragged step (append fused unless k_new is None) with its launch driven by a work list."""
+        T.tempo_decode_step_ragged(self.kv, q, k_new, v_new, out, self.batch, self.Hq, t_max, t_per_seq, window,
+                                   self.scale if scale is None else scale, worklist, self.workspace,
+                                   self.workspace_bytes)
+        return out
+
     def step_causal_noalloc(self, q, k_new, v_new, out, t, t_per_seq=None, scale=None):
         """step_causal with the split partials in the library's static device array (no workspace)."""
         T.tempo_decode_step_causal_noalloc(self.kv, q, k_new, v_new, out, self.batch, self.Hq, t, t_per_seq,

@@ -100,6 +100,10 @@ SIGNATURES = {
                                                 ctypes.c_float, _vp, ctypes.c_size_t, _vp]),
     "tempo_decode_step_window": (ctypes.c_int, [_kvp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _i32,
                                                 ctypes.c_float, _vp, ctypes.c_size_t, _vp]),
+    "tempo_attn_worklist_bytes": (ctypes.c_size_t, [_kvp, _i32, _i32, _i32, _i32]),
+    "tempo_attn_worklist_build": (ctypes.c_int, [_kvp, _i32, _i32, _i32, _vp, _i32, _vp, ctypes.c_size_t, _vp]),
+    "tempo_decode_step_ragged": (ctypes.c_int, [_kvp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _i32,
+                                                ctypes.c_float, _vp, _vp, ctypes.c_size_t, _vp]),
     "tempo_decode_step_causal_noalloc": (ctypes.c_int, [_kvp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp,
                                                         ctypes.c_float, _vp]),
     "tempo_attn_decode_padded_causal": (ctypes.c_int, [_kvp, _vp, _vp, _i32, _i32, _i32, _vp, _i32, ctypes.c_float,
@@ -326,6 +330,25 @@ def tempo_decode_step_window(kv, q, k_new, v_new, out, batch, num_q_heads, t, t_
                                            batch, num_q_heads, t, _ptr(t_per_seq), window, scale,
                                            _ptr(workspace), workspace_bytes, _stream(stream)),
            "tempo_decode_step_window")
+
+
+def tempo_attn_worklist_bytes(kv, batch, num_q_heads, t_max, window=0) -> int:
+    return load().tempo_attn_worklist_bytes(ctypes.byref(kv), batch, num_q_heads, t_max, window)
+
+
+def tempo_attn_worklist_build(kv, batch, num_q_heads, t_max, t_per_seq, window, worklist, worklist_bytes,
+                              stream=None):
+    _check(load().tempo_attn_worklist_build(ctypes.byref(kv), batch, num_q_heads, t_max, _ptr(t_per_seq), window,
+                                            _ptr(worklist), worklist_bytes, _stream(stream)),
+           "tempo_attn_worklist_build")
+
+
+def tempo_decode_step_ragged(kv, q, k_new, v_new, out, batch, num_q_heads, t_max, t_per_seq, window, scale,
+                             worklist, workspace, workspace_bytes, stream=None):
+    _check(load().tempo_decode_step_ragged(ctypes.byref(kv), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), batch,
+                                           num_q_heads, t_max, _ptr(t_per_seq), window, scale, _ptr(worklist),
+                                           _ptr(workspace), workspace_bytes, _stream(stream)),
+           "tempo_decode_step_ragged")
 
 
 def tempo_decode_step_causal_noalloc(kv, q, k_new, v_new, out, batch, num_q_heads, t, t_per_seq, scale,

@@ -228,6 +228,73 @@ def test_ragged_steps_random_block_table(dtype, window):
 
 
 # ----------------------------------------------------------------------------
+# Ragged steps driven by a work list: the list holds exactly the non-empty (sequence, split)
+# items, full splits first and the newest splits by falling size; the step gives the bits of
+# the entry points without a list, and the oracle's values.
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("B,Hq,Hkv,D,Z,T_len,window", [(7, 6, 2, 128, 32, 300, 0), (7, 6, 2, 128, 32, 300, 45),
+                                                        (300, 2, 1, 64, 32, 2100, 0), (33, 8, 8, 64, 64, 5000, 1500)])
+def test_ragged_work_list(B, Hq, Hkv, D, Z, T_len, window):
+    dtype = T.TEMPO_BF16
+    lengths = synth.integers(60 + B, 1, B, 1, T_len)
+    lengths[0], lengths[-1] = 1, T_len
+    st = BlockStore(B, Hq, Hkv, D, Z, T_len - 1, dtype, fill="nan")
+    plain = BlockStore(B, Hq, Hkv, D, Z, T_len - 1, dtype, fill="nan")
+    K = synth.device_normal((B, T_len, Hkv, D), 6001, torch.bfloat16, DEV)
+    V = synth.device_normal((B, T_len, Hkv, D), 6002, torch.bfloat16, DEV)
+    q = synth.device_normal((B, Hq, D), 6003, torch.bfloat16, DEV)
+    # every sequence holds its steps 0..L-2 (rows beyond are NaN in the store); the step appends L-1
+    for s_ in (st, plain):
+        for b in range(B):
+            L = int(lengths[b])
+            if L > 1:
+                one = T.make_kv(s_.k_pool, s_.v_pool, s_.block_table[b:b + 1], s_.num_blocks, s_.max_blocks_per_seq,
+                                Z, Hkv, D, dtype)
+                T.tempo_kv_append_block(one, K[b:b + 1, :L - 1].contiguous(), V[b:b + 1, :L - 1].contiguous(), 1, 0,
+                                        None, L - 1)
+    tps = torch.from_numpy(lengths - 1).to(DEV).to(torch.int32)
+    ar = torch.arange(B, device=DEV)
+    k_t, v_t = K[ar, tps.long()].contiguous(), V[ar, tps.long()].contiguous()
+    plan = T.tempo_attn_plan(st.kv, B, Hq, T_len - 1, window, True)
+    worklist = st.build_worklist(T_len - 1, tps, window)
+    torch.cuda.synchronize()
+    # the list, item by item
+    wl = worklist.cpu().numpy()
+    tps_ = plan.tokens_per_split
+    want, newest = set(), {}
+    for b in range(B):
+        t_b = int(lengths[b]) - 1
+        lo = max(0, t_b - window + 1) if window else 0
+        n = t_b // tps_ - lo // tps_ + 1
+        assert n <= plan.num_splits
+        want |= {(b, s_) for s_ in range(n)}
+        newest[b] = (n - 1, t_b - max(lo, (t_b // tps_) * tps_) + 1)
+    count = int(wl[0])
+    items = [(int(x) & 0xFFFF, int(x) >> 16) for x in wl[1:1 + count]]
+    assert count == len(want) and set(items) == want and len(set(items)) == count
+    n_full = count - B
+    assert all(s_ < newest[b][0] for b, s_ in items[:n_full])            # full splits first
+    tail_classes = [7 - ((newest[b][1] - 1) * 8) // tps_ for b, s_ in items[n_full:]]
+    assert all(s_ == newest[b][0] for b, s_ in items[n_full:])
+    assert tail_classes == sorted(tail_classes)                           # then the newest splits, longest class first
+    # the step: same bits as without a list, the oracle's values, the same store
+    out = st.step_ragged(q, k_t, v_t, st.new_out(), T_len - 1, tps, worklist, window)
+    if window:
+        ref_out = plain.step_window(q, k_t, v_t, plain.new_out(), T_len - 1, window, t_per_seq=tps)
+    else:
+        ref_out = plain.step_causal(q, k_t, v_t, plain.new_out(), T_len - 1, t_per_seq=tps)
+    torch.cuda.synchronize()
+    assert torch.equal(out, ref_out)
+    assert torch.equal(st.k_pool.view(torch.int16), plain.k_pool.view(torch.int16))
+    assert torch.equal(st.v_pool.view(torch.int16), plain.v_pool.view(torch.int16))
+    ref = oracle.attend(np64(q), np64(K), np64(V), lengths - 1, window, 1.0 / np.sqrt(D))
+    assert_close(out, ref, dtype, f"ragged step with a work list, window={window}")
+    # attention only (the store already holds the steps): k_new = v_new = None
+    again = st.step_ragged(q, None, None, st.new_out(), T_len - 1, tps, worklist, window)
+    assert torch.equal(again, out)
+
+
+# ----------------------------------------------------------------------------
 # The padded + masked baseline gives the same result as the dynamic range at every
 # step, while the pool beyond the step holds NaN (masking is by index).
 # ----------------------------------------------------------------------------
@@ -627,10 +694,14 @@ def test_ragged_multi_layer_shared_pool_bf16():
         flats.append((K, V))
     # the step: all 28 layers, one fused call each
     qs = [synth.device_normal((B, Hq, D), 2400 + layer, torch.bfloat16, DEV) for layer in range(layers)]
+    worklist = stores[0].build_worklist(T_max - 1, tps)            # one list serves every layer of the step
     for layer, st in enumerate(stores):
         K, V = flats[layer]
-        outs.append(st.step_causal(qs[layer], K[ar, tps.long()].contiguous(), V[ar, tps.long()].contiguous(),
-                                   st.new_out(), T_max - 1, t_per_seq=tps))
+        k_t, v_t = K[ar, tps.long()].contiguous(), V[ar, tps.long()].contiguous()
+        if layer % 2:                                              # odd layers: the launch driven by the work list
+            outs.append(st.step_ragged(qs[layer], k_t, v_t, st.new_out(), T_max - 1, tps, worklist))
+        else:
+            outs.append(st.step_causal(qs[layer], k_t, v_t, st.new_out(), T_max - 1, t_per_seq=tps))
     torch.cuda.synchronize()
     for layer, st in enumerate(stores):
         K, V = flats[layer]

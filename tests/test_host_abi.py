@@ -241,6 +241,21 @@ def test_bad_arguments_are_refused_before_any_launch():
     assert padded(good, t=101) == T.TEMPO_ERR_RANGE
     assert padded(kv_desc(T.TEMPO_F32)) == T.TEMPO_ERR_DTYPE
 
+    # ragged work list: bf16, groups of at most 16 heads, batch * splits within one grid dimension
+    wl_kv = kv_desc(T.TEMPO_BF16, Z=256, Hkv=8, num_blocks=64 * 32, max_blocks=32)
+    assert T.tempo_attn_worklist_bytes(wl_kv, 64, 24, 8191) >= 4 * (1 + 64 * 8)
+    assert T.tempo_attn_worklist_bytes(kv_desc(T.TEMPO_F32, Z=256, Hkv=8, max_blocks=32), 64, 24, 8191) == 0
+    assert T.tempo_attn_worklist_bytes(wl_kv, 64, 8 * 17, 8191) == 0
+    assert lib.tempo_attn_worklist_build(ctypes.byref(wl_kv), 64, 24, 8191, fake, 0, fake, 16, None) == T.TEMPO_ERR_WORKSPACE
+    assert lib.tempo_attn_worklist_build(ctypes.byref(wl_kv), 64, 24, 8191, None, 0, fake, 1 << 20, None) == T.TEMPO_ERR_NULL
+    assert lib.tempo_attn_worklist_build(ctypes.byref(wl_kv), 64, 24, 8191, fake, 0, fake + 2, 1 << 20, None) == T.TEMPO_ERR_WORKSPACE
+    assert lib.tempo_decode_step_ragged(ctypes.byref(wl_kv), fake, fake, fake, fake, 64, 24, 8191, fake, 0, 0.1, None,
+                                        fake << 4, 1 << 30, None) == T.TEMPO_ERR_NULL
+    assert lib.tempo_decode_step_ragged(ctypes.byref(wl_kv), fake, fake, None, fake, 64, 24, 8191, fake, 0, 0.1, fake,
+                                        fake << 4, 1 << 30, None) == T.TEMPO_ERR_NULL
+    assert lib.tempo_decode_step_ragged(ctypes.byref(wl_kv), fake, fake, fake, fake, 64, 24, 8191, fake, 0, 0.1, fake,
+                                        fake << 4, 16, None) == T.TEMPO_ERR_WORKSPACE
+
     def block(kv, queries, t=5, Hq=6, w=None):
         if w is None:
             return lib.tempo_attn_block_causal(ctypes.byref(kv), fake, fake, 2, Hq, queries, t, None, 0.1, None, 0, None)
