@@ -30,7 +30,9 @@
  * paper's printed inverse-window example; for the rotary embedding: closed
  * forms at chosen angles, norm preservation, the relative-position identity and
  * composition of rotations; for releases and ring sizes: the paper's printed
- * inverse-window example read as "last reader of key j", and closed forms).
+ * inverse-window example read as "last reader of key j", and closed forms; for the
+ * discounted sum: closed forms of constant and impulse rewards, the recurrence between
+ * neighbouring steps, a differently written evaluator, the parameters Algorithm 1 prints).
  * Nothing is "parity unpinned".
  */
 #include <math.h>
@@ -278,6 +280,32 @@ int tempo_oracle_rope_table(int positions, int D, double theta, double* cos_out,
       const double angle = (double)t * pow(theta, -2.0 * (double)i / (double)D);
       cos_out[(size_t)t * half + i] = cos(angle);
       sin_out[(size_t)t * half + i] = sin(angle);
+    }
+  }
+  return 0;
+}
+
+/*
+ * Anti-causal window reduction of the paper's reinforcement-learning example (Section 3,
+ * Algorithm 1): the return of step t is the discounted sum of the rewards of the steps
+ * t .. min(t+n, T)-1 (an n-step return), or of all steps t .. T-1 (the whole future):
+ *     g[b][t] = sum_{k = 0}^{m-1} gamma^k * r[b][t+k],   m = min(n, T-t),  or  m = T-t  if n == 0.
+ * The paper names the operation ("discounted_sum") without a formula; this is the usual
+ * meaning of a discounted return, the first reward undiscounted.  The range is the forward
+ * (anti-causal) window whose inverse the paper prints next to the attention windows.
+ *   r, g  [B][T] fp64, row-major.   Returns 0, or -1 on a bad argument.
+ */
+int tempo_oracle_discounted_sum(const double* r, int B, int T, int n, double gamma, double* g) {
+  if (!r || !g || B < 1 || T < 1 || n < 0) return -1;
+  for (int b = 0; b < B; ++b) {
+    for (int t = 0; t < T; ++t) {
+      const int stop = (n == 0 || t + n > T) ? T : t + n;   /* the slice t : min(t+n, T) */
+      double sum = 0.0, weight = 1.0;                         /* gamma^0 */
+      for (int j = t; j < stop; ++j) {
+        sum += weight * r[(size_t)b * T + j];
+        weight *= gamma;
+      }
+      g[(size_t)b * T + t] = sum;
     }
   }
   return 0;

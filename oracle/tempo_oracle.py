@@ -55,6 +55,8 @@ def _bind(path: str):
         lib.tempo_oracle_rope.restype = ctypes.c_int
         lib.tempo_oracle_rope_table.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_double, dp, dp]
         lib.tempo_oracle_rope_table.restype = ctypes.c_int
+        lib.tempo_oracle_discounted_sum.argtypes = [dp, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double, dp]
+        lib.tempo_oracle_discounted_sum.restype = ctypes.c_int
         lib.tempo_oracle_threads.argtypes = []
         lib.tempo_oracle_threads.restype = ctypes.c_int
     return lib
@@ -155,6 +157,20 @@ def rope_table(positions: int, D: int, theta: float):
     if rc != 0:
         raise ValueError("oracle: bad argument to rope_table")
     return c, s
+
+
+def discounted_sum(r, n: int, gamma: float) -> np.ndarray:
+    """r [B][T] -> g [B][T] (fp64): g[b][t] = sum_k gamma^k r[b][t+k] over t .. min(t+n, T)-1 (n = 0: t .. T-1)."""
+    r = np.ascontiguousarray(r, dtype=np.float64)
+    if r.ndim != 2:
+        raise ValueError("oracle: discounted_sum takes [B][T]")
+    B, T = r.shape
+    g = np.empty_like(r)
+    dp = ctypes.POINTER(ctypes.c_double)
+    rc = _load().tempo_oracle_discounted_sum(r.ctypes.data_as(dp), B, T, int(n), float(gamma), g.ctypes.data_as(dp))
+    if rc != 0:
+        raise ValueError("oracle: bad argument to discounted_sum")
+    return g
 
 
 def threads() -> int:

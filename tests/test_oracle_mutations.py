@@ -32,6 +32,8 @@ PIN_TESTS = [
     pins.test_p12_release_follows_the_printed_inverse_window,
     pins.test_p12_release_closed_forms_and_safety,
     pins.test_p12_ring_blocks_is_the_smallest_circular_store_that_holds,
+    pins.test_p13_discounted_sum_printed_parameters_and_closed_forms,
+    pins.test_p13_discounted_sum_impulse_recurrence_and_second_evaluator,
 ]
 
 # (name, text to find, replacement) -- each is a mistake someone could make.
@@ -81,6 +83,13 @@ MUTATIONS = [
      "if (visible(j, first, window)) { oldest = first; break; }"),
     ("ring counts keys of the first step only", "for (int j = 0; j <= last; ++j) {\n      if (j >= oldest && tile != counted_tile)",
      "for (int j = 0; j <= first; ++j) {\n      if (j >= oldest && tile != counted_tile)"),
+    ("discounted sum looks into the past", "for (int j = t; j < stop; ++j) {\n        sum += weight * r[(size_t)b * T + j];",
+     "for (int j = t; j < stop; ++j) {\n        sum += weight * r[(size_t)b * T + (2 * t - j < 0 ? 0 : 2 * t - j)];"),
+    ("discounted sum window one step too wide", "(n == 0 || t + n > T) ? T : t + n;", "(n == 0 || t + n + 1 > T) ? T : t + n + 1;"),
+    ("discounted sum discounts the first reward", "double sum = 0.0, weight = 1.0;", "double sum = 0.0, weight = gamma;"),
+    ("discounted sum not clipped at T", "(n == 0 || t + n > T) ? T : t + n;", "(n == 0) ? T : (t + n > T ? T - 1 : t + n);"),
+    ("discounted sum forgets to discount", "weight *= gamma;", "weight *= 1.0;"),
+    ("discounted sum mixes sequences", "sum += weight * r[(size_t)b * T + j];", "sum += weight * r[j];"),
     ("append slot one late", "for (int j = 0; j < t; ++j) {\n    if (++s == Z)", "for (int j = 0; j <= t; ++j) {\n    if (++s == Z)"),
 ]
 

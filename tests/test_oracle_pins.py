@@ -439,6 +439,70 @@ def test_p12_ring_blocks_is_the_smallest_circular_store_that_holds():
 
 
 # ----------------------------------------------------------------------------
+# P13 anti-causal window reduction (Section 3, Algorithm 1: returns as discounted sums of the
+#     rewards over t : min(t+n, T) or t : T).
+# ----------------------------------------------------------------------------
+def test_p13_discounted_sum_printed_parameters_and_closed_forms():
+    rows = [l for l in open(os.path.join(GOLDEN, "discounted_sum.txt")) if not l.startswith("#")]
+    seen = 0
+    for row in rows:
+        name, slice_, n, gamma, B, T = [c.strip() for c in row.split("|")]
+        n, gamma, B, T = int(n), float(gamma), int(B), int(T)
+        assert (n == 0) == (slice_ == "t:T")
+        g = oracle.discounted_sum(np.ones((B, T)), n, gamma)
+        for t in range(T):
+            m = T - t if n == 0 else min(n, T - t)               # steps in the slice
+            want = (1.0 - gamma ** m) / (1.0 - gamma)            # geometric series, first term undiscounted
+            assert abs(g[0, t] - want) <= 1e-12 * want and np.all(g[:, t] == g[0, t])
+        assert g[0, T - 1] == 1.0                                # the last step sees only its own reward
+        if n == 5:
+            assert abs(g[0, 0] - (1 + 0.95 + 0.95 ** 2 + 0.95 ** 3 + 0.95 ** 4)) < 1e-12
+            assert abs(g[0, T - 2] - 1.95) < 1e-12               # clipped at T: two steps left
+        seen += 1
+    assert seen == 2
+    # gamma = 1: plain window sums; gamma = 0 or n = 1: the reward itself
+    r = synth.normal(41, 1, (3, 37))
+    assert np.allclose(oracle.discounted_sum(r, 4, 1.0)[:, 10], r[:, 10:14].sum(axis=1), atol=1e-14)
+    assert np.array_equal(oracle.discounted_sum(r, 0, 0.0), r)
+    assert np.array_equal(oracle.discounted_sum(r, 1, 0.7), r)
+    # a window that reaches past T everywhere is the whole future
+    assert np.array_equal(oracle.discounted_sum(r, 37, 0.9), oracle.discounted_sum(r, 0, 0.9))
+    with pytest.raises(ValueError):
+        oracle.discounted_sum(r, -1, 0.9)
+
+
+def test_p13_discounted_sum_impulse_recurrence_and_second_evaluator():
+    T, gamma = 23, 0.8
+    for n in (0, 1, 3, 7, 40):
+        # one reward of 1 at step j: step t sees it iff t <= j < min(t+n, T), with weight gamma^(j-t):
+        # pins the direction (future, not past), the window width, the clipping, the exponent's origin
+        for j in (0, 5, T - 1):
+            r = np.zeros((1, T))
+            r[0, j] = 1.0
+            g = oracle.discounted_sum(r, n, gamma)[0]
+            for t in range(T):
+                stop = T if n == 0 else min(t + n, T)
+                want = gamma ** (j - t) if t <= j < stop else 0.0
+                assert abs(g[t] - want) < 1e-15, (n, j, t)
+        r = synth.normal(42, n, (2, T))
+        g = oracle.discounted_sum(r, n, gamma)
+        # neighbouring steps: g[t] = r[t] + gamma g[t+1] - gamma^n r[t+n]  (last term only while t+n < T)
+        for t in range(T - 1):
+            drop = gamma ** n * r[:, t + n] if (n and t + n < T) else 0.0
+            assert np.allclose(g[:, t], r[:, t] + gamma * g[:, t + 1] - drop, atol=1e-13)
+        # a second evaluator, written differently: exact rational arithmetic on rounded inputs
+        from fractions import Fraction
+        for t in (0, 4, T - 2, T - 1):
+            stop = T if n == 0 else min(t + n, T)
+            exact = sum(Fraction(gamma) ** (j - t) * Fraction(float(r[1, j])) for j in range(t, stop))
+            assert abs(g[1, t] - float(exact)) < 1e-13
+        # linear in r
+        r2 = synth.normal(43, n, (2, T))
+        assert np.allclose(oracle.discounted_sum(2.0 * r - r2, n, gamma), 2.0 * g - oracle.discounted_sum(r2, n, gamma),
+                           atol=1e-12)
+
+
+# ----------------------------------------------------------------------------
 # The input generator is shared by both sides, so pin what it promises.
 # ----------------------------------------------------------------------------
 # ----------------------------------------------------------------------------
