@@ -322,6 +322,21 @@ def other_workloads(torch, T, BlockStore, synth, dev, kv_bytes_per_token):
     torch.cuda.empty_cache()
 
     out["ragged_28layers_b64"] = ragged_step_bench(torch, T, BlockStore, synth, dev, kv_bytes_per_token)
+
+    # the anti-causal window reduction of the paper's reinforcement-learning example (Section 3,
+    # Algorithm 1): returns over t : min(t+5, T) and over t : T, batch 64, T = 200 and 1000
+    for T_len in (200, 1000):
+        r = torch.empty((64, T_len), dtype=torch.float32, device=dev).normal_()
+        g = torch.empty_like(r)
+        for n in (5, 0):
+            dt = graph_timed(torch, lambda i: T.tempo_discounted_sum(r, g, 64, T_len, n, 0.95), 16, 30)["median"]
+            nbytes = 2 * r.numel() * 4
+            out[f"discounted_sum_b64_T{T_len}_{'future' if n == 0 else 'n' + str(n)}"] = {
+                "us_per_call": us(dt), "bytes_per_call": nbytes,
+                "roofline": dict(hbm_roofline("discounted_suffix" if n == 0 else "discounted_window", nbytes, dt,
+                                              "one launch, graph replay"),
+                                 note="a few hundred KB per call: bound by launch latency (an empty kernel's "
+                                      "period is 1.9 us), not by HBM")}
     return out
 
 

@@ -567,6 +567,25 @@ size_t tempo_attn_plan_workspace_bytes(const tempo_kv* kv, int32_t batch, int32_
                                        const tempo_plan* plan);
 
 /*
+ * Anti-causal window reduction (Section 3, Algorithm 1: the returns of the paper's
+ * reinforcement-learning example, `r[t : min(t+n, T)].discounted_sum(gamma)` and
+ * `r[t : T].discounted_sum(gamma)`): for every sequence b and step t
+ *     g[b][t] = sum_{k=0}^{m-1} gamma^k * r[b][t+k],    m = min(n, T - t),
+ * the first reward undiscounted; n = 0 (or any n >= T) means the whole future, m = T - t.
+ * The forward counterpart of the attention windows above: a reduction over a range of the
+ * temporal dimension whose extent depends on t.
+ *   r, g    device, [batch][T] float, row-major; g must not be r (a step reads later rewards)
+ *   n       0, or 1 .. 1024, or >= T (TEMPO_ERR_RANGE for a window between 1024 and T)
+ *   gamma   any finite value (TEMPO_ERR_RANGE otherwise)
+ * One launch: a short window is folded per step from a tile staged in LDS; the whole
+ * future is a reverse scan of g[t] = r[t] + gamma g[t+1], O(T) work per sequence.  fp32
+ * arithmetic; against exact arithmetic the error of g[b][t] stays within
+ * 1e-5 * sum_k |gamma|^k |r[b][t+k]|.
+ */
+int tempo_discounted_sum(const float* r, float* g, int32_t batch, int32_t T, int32_t n, float gamma,
+                         void* stream);
+
+/*
  * Measurement aid, not part of the decode path: read `bytes` (a multiple of 16)
  * of device memory at src (16-byte aligned) once with 16-byte-per-lane loads,
  * using `workgroups` workgroups of 256 threads, and discard the data (sink:

@@ -20,7 +20,7 @@ LIB = os.path.join(LIBDIR, "libtempo.so")
 OBJDIR = os.path.join(HERE, "_build")
 
 SOURCES = ["tempo_api.hip", "kv_store.hip", "attn_partial_bf16.hip", "attn_partial_f32.hip",
-           "attn_combine.hip", "stream_read.hip", "rope.hip", "attn_prefill_bf16.hip", "worklist.hip"]
+           "attn_combine.hip", "stream_read.hip", "rope.hip", "attn_prefill_bf16.hip", "worklist.hip", "discounted_sum.hip"]
 HEADERS = [os.path.join(CSRC, "tempo_internal.h"), os.path.join(CSRC, "attn_bf16_common.h"),
            os.path.join(CSRC, "attn_combine.h"), os.path.join(ROOT, "include", "tempo.h")]
 

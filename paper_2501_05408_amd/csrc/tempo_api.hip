@@ -1053,6 +1053,17 @@ int tempo_attn_decode_combine(const tempo_kv* kv, void* out, int32_t batch, int3
                     const_cast<void*>(workspace), static_cast<hipStream_t>(stream));
 }
 
+int tempo_discounted_sum(const float* r, float* g, int32_t batch, int32_t T, int32_t n, float gamma, void* stream) {
+  if (!r || !g) return TEMPO_ERR_NULL;
+  if (batch < 1 || batch > 65535 || T < 1) return TEMPO_ERR_SHAPE;
+  if (n < 0 || !(gamma >= -3.0e38f && gamma <= 3.0e38f)) return TEMPO_ERR_RANGE;       // a finite discount
+  if (n > discounted_sum_max_window() && n < T) return TEMPO_ERR_RANGE;                 // neither a short window nor the whole future
+  if (r == g) return TEMPO_ERR_SHAPE;                                                   // a step reads rewards of later steps
+  if ((int64_t)T > INT32_MAX - 4096) return TEMPO_ERR_SHAPE;
+  const hipError_t e = launch_discounted_sum(r, g, batch, T, n, gamma, static_cast<hipStream_t>(stream));
+  return launch_status(e, "discounted_sum");
+}
+
 int tempo_stream_read(const void* src, size_t bytes, void* sink, int32_t workgroups, void* stream) {
   if (!src || !sink) return TEMPO_ERR_NULL;
   if (bytes < 16 || bytes % 16 != 0 || (reinterpret_cast<uintptr_t>(src) & 15u) != 0) return TEMPO_ERR_SHAPE;

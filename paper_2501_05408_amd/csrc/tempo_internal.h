@@ -161,6 +161,8 @@ hipError_t launch_rope_append(const StoreParams& p, const float* rope_cos, const
 hipError_t launch_combine(const AttnParams& p, int batch, int D, int dtype, hipStream_t stream);
 hipError_t launch_worklist_build(const int32_t* t_per_seq, int batch, int t_max, int window, int tps_log2,
                                  int num_splits, int32_t* worklist, hipStream_t stream);
+hipError_t launch_discounted_sum(const float* r, float* g, int batch, int T, int n, float gamma, hipStream_t stream);
+int discounted_sum_max_window();
 hipError_t launch_stream_read(const void* src, size_t bytes, void* sink, int workgroups,
                               hipStream_t stream);
 hipError_t launch_stream_copy(const void* src, void* dst, size_t bytes, int workgroups,

@@ -143,6 +143,7 @@ SIGNATURES = {
     "tempo_attn_decode_combine": (ctypes.c_int, [_kvp, _vp, _i32, _i32, _i32, _vp, _i32, _planp, _vp,
                                                  ctypes.c_size_t, _vp]),
     "tempo_attn_plan_workspace_bytes": (ctypes.c_size_t, [_kvp, _i32, _i32, _planp]),
+    "tempo_discounted_sum": (ctypes.c_int, [_vp, _vp, _i32, _i32, _i32, ctypes.c_float, _vp]),
     "tempo_stream_read": (ctypes.c_int, [_vp, ctypes.c_size_t, _vp, _i32, _vp]),
     "tempo_stream_copy": (ctypes.c_int, [_vp, _vp, ctypes.c_size_t, _i32, _vp]),
 }
@@ -508,6 +509,10 @@ def tempo_attn_decode_combine(kv, out, batch, num_q_heads, t, t_per_seq, window,
                                             _ptr(t_per_seq), window, ctypes.byref(plan), _ptr(workspace),
                                             workspace_bytes, _stream(stream)),
            "tempo_attn_decode_combine")
+
+
+def tempo_discounted_sum(r, g, batch, T, n, gamma, stream=None):
+    _check(load().tempo_discounted_sum(_ptr(r), _ptr(g), batch, T, n, gamma, _stream(stream)), "tempo_discounted_sum")
 
 
 def tempo_stream_read(src, nbytes, sink, workgroups, stream=None):

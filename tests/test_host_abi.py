@@ -256,6 +256,16 @@ def test_bad_arguments_are_refused_before_any_launch():
     assert lib.tempo_decode_step_ragged(ctypes.byref(wl_kv), fake, fake, fake, fake, 64, 24, 8191, fake, 0, 0.1, fake,
                                         fake << 4, 16, None) == T.TEMPO_ERR_WORKSPACE
 
+    # the anti-causal window reduction: a short window or the whole future, a finite discount, no aliasing
+    def dsum(r=fake, g=fake + 4096, batch=2, T_len=5000, n=5, gamma=0.9):
+        return lib.tempo_discounted_sum(r, g, batch, T_len, n, gamma, None)
+
+    assert dsum(r=None) == T.TEMPO_ERR_NULL and dsum(g=None) == T.TEMPO_ERR_NULL
+    assert dsum(g=fake) == T.TEMPO_ERR_SHAPE
+    assert dsum(batch=0) == T.TEMPO_ERR_SHAPE and dsum(T_len=0) == T.TEMPO_ERR_SHAPE
+    assert dsum(n=-1) == T.TEMPO_ERR_RANGE and dsum(n=1025) == T.TEMPO_ERR_RANGE and dsum(n=4999) == T.TEMPO_ERR_RANGE
+    assert dsum(gamma=float("inf")) == T.TEMPO_ERR_RANGE and dsum(gamma=float("nan")) == T.TEMPO_ERR_RANGE
+
     def block(kv, queries, t=5, Hq=6, w=None):
         if w is None:
             return lib.tempo_attn_block_causal(ctypes.byref(kv), fake, fake, 2, Hq, queries, t, None, 0.1, None, 0, None)
