@@ -197,7 +197,7 @@ __device__ __forceinline__ void merge_waves(const AttnParams& p, const float* sm
   }
 }
 
-template <int D, bool kRope>
+template <int D, bool kRope, bool kList>
 __global__ __launch_bounds__(512) void attn_partial_bf16(AttnParams p) {
   constexpr int KS = D / 32;
   constexpr int DT = D / 16;
@@ -208,8 +208,10 @@ __global__ __launch_bounds__(512) void attn_partial_bf16(AttnParams p) {
   const int hkv = blockIdx.x;
   // Which (sequence, split) this workgroup takes: its grid position, or, for a ragged batch
   // with a work list, the list's item (non-empty items only, longest first).
+  // (A template parameter, not a test of the pointer: a branch here sits in front of the
+  // argument -> table -> data chain of EVERY launch and cost 0.3 us when it was one.)
   int b = blockIdx.y, zsplit = blockIdx.z;
-  if (p.worklist) {
+  if (kList) {
     const_i32_ptr list = (const_i32_ptr)p.worklist;
     if ((int)blockIdx.y >= list[0]) return;  // uniform over the workgroup
     const int item = list[1 + blockIdx.y];
@@ -225,7 +227,7 @@ __global__ __launch_bounds__(512) void attn_partial_bf16(AttnParams p) {
   // is the one a fused append lands in and the one t may cut short; launching
   // all of those first keeps their longer path out of the launch's last round.
   // (A work list names the split itself.)
-  const int split = p.worklist ? zsplit : rg.nchunks - 1 - zsplit;
+  const int split = kList ? zsplit : rg.nchunks - 1 - zsplit;
   const int chunk = rg.chunk0 + split;
   const int cs = chunk << p.tps_log2, ce = ((chunk + 1) << p.tps_log2) - 1;
   const int start = rg.lo > cs ? rg.lo : cs;
@@ -376,12 +378,17 @@ hipError_t launch_partial_bf16(const AttnParams& p, int batch, int D, int grid_s
   if (grid.y > 65535u) return hipErrorInvalidConfiguration;
   const dim3 block(64 * waves);
   const size_t lds = partial_bf16_lds_bytes(waves, p.queries * p.G, D);
-  if (p.rope_cos) {
-    if (D == 128) return launch((attn_partial_bf16<128, true>), grid, block, lds, stream, p);
-    return launch((attn_partial_bf16<64, true>), grid, block, lds, stream, p);
+  if (p.worklist) {
+    if (p.rope_cos) return hipErrorInvalidConfiguration;  // no caller combines the two
+    if (D == 128) return launch((attn_partial_bf16<128, false, true>), grid, block, lds, stream, p);
+    return launch((attn_partial_bf16<64, false, true>), grid, block, lds, stream, p);
   }
-  if (D == 128) return launch((attn_partial_bf16<128, false>), grid, block, lds, stream, p);
-  return launch((attn_partial_bf16<64, false>), grid, block, lds, stream, p);
+  if (p.rope_cos) {
+    if (D == 128) return launch((attn_partial_bf16<128, true, false>), grid, block, lds, stream, p);
+    return launch((attn_partial_bf16<64, true, false>), grid, block, lds, stream, p);
+  }
+  if (D == 128) return launch((attn_partial_bf16<128, false, false>), grid, block, lds, stream, p);
+  return launch((attn_partial_bf16<64, false, false>), grid, block, lds, stream, p);
 }
 
 }  // namespace tempo
