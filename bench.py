@@ -463,6 +463,10 @@ def step_only(torch, T, BlockStore, synth, dev, name, repeats):
     o = sts[0].new_out()
     if name == "window512":
         fn, keys = (lambda i: sts[i % 8].step_window(q, k, v, o, 8191, 512)), 512
+    elif name == "window512odd":   # the window starts inside a 32-slot group, as it does at most steps
+        fn, keys = (lambda i: sts[i % 8].step_window(q, k, v, o, 8000, 512)), 512
+    elif name == "t300":
+        fn, keys = (lambda i: sts[i % 8].step_causal(q, k, v, o, 300)), 301
     elif name == "long8191":
         fn, keys = (lambda i: sts[i % 8].step_causal(q, k, v, o, 8191)), 8192
     elif name == "t255":
