@@ -161,6 +161,23 @@ def launch_bound_legs(torch, T, BlockStore, synth, dev, kv_bytes_per_token):
             T.tempo_attn_plan(sts[0].kv, 16, Hq, t, 0))
     del sts
     torch.cuda.empty_cache()
+    # the other head size (32 query heads in groups of 4, head_dim 64: half the bytes per key)
+    sts64 = []
+    for _ in range(R):
+        st = BlockStore(16, 32, 8, 64, Z, 8191, T.TEMPO_BF16, device=dev)
+        st.k_pool.normal_()
+        st.v_pool.normal_()
+        sts64.append(st)
+    q64 = synth.device_normal((16, 32, 64), 74, torch.bfloat16, dev)
+    k64 = synth.device_normal((16, 8, 64), 75, torch.bfloat16, dev)
+    v64 = synth.device_normal((16, 8, 64), 76, torch.bfloat16, dev)
+    o64 = sts64[0].new_out()
+    for t in (4095, 8191):
+        leg(f"head_dim64_hq32_b16_t{t}", lambda i: sts64[i % R].step_causal(q64, k64, v64, o64, t),
+            16 * (t + 1) * 2 * 8 * 64 * 2, T.tempo_attn_plan(sts64[0].kv, 16, 32, t, 0))
+        out[f"head_dim64_hq32_b16_t{t}"]["roofline"]["kernel"] = "attn_partial_bf16<64, false>"
+    del sts64
+    torch.cuda.empty_cache()
     sts = layers(16, 16383)
     leg("window512_b16_t8191", lambda i: sts[i % R].step_window(q16, k16, v16, o, 8191, 512),
         16 * 512 * kv_bytes_per_token, T.tempo_attn_plan(sts[0].kv, 16, Hq, 8191, 512))

@@ -574,6 +574,39 @@ def test_llama_shape_causal_bf16_full_size_every_step_appended():
         assert_close(got[i], ref, dtype, f"llama causal, appended step by step, t={t}")
 
 
+def test_head_dim_64_shape_causal_bf16_full_size():
+    # The other head size the library serves, at a real shape (32 query heads in groups of 4, head_dim 64,
+    # the attention layer of the 1B model of the same family): fused steps at sampled t, append checked.
+    B, Hq, Hkv, D, Z, T_len = 16, 32, 8, 64, 256, 4096
+    dtype = T.TEMPO_BF16
+    K, V = flat_kv(27, B, T_len, Hkv, D)
+    table, nb = random_table(27, B, T_len // Z, extra=0)
+    st = BlockStore(B, Hq, Hkv, D, Z, T_len - 1, dtype, num_blocks=nb, block_table=table, fill="nan")
+    K64, V64 = np64(K), np64(V)
+    steps = [0, 1, 31, 32, 255, 256, 257, 1000, 2047, 2048, 3000, 4094, 4095]
+    done = -1
+    for t in steps:
+        if t - 1 > done:
+            st.append_block(K[:, done + 1:t].contiguous(), V[:, done + 1:t].contiguous(), done + 1, t - 1 - done)
+        q = synth.device_normal((B, Hq, D), 2700 + t, torch.bfloat16, DEV)
+        out = st.step_causal(q, K[:, t].contiguous(), V[:, t].contiguous(), st.new_out(), t)
+        done = t
+        ref = oracle.attend(np64(q), K64, V64, t, 0, 1.0 / np.sqrt(D))
+        assert_close(out, ref, dtype, f"head_dim 64 causal fused step t={t}")
+    kg, vg = st.gather(0, T_len)
+    assert torch.equal(kg, K) and torch.equal(vg, V)
+    # the same store through the window pattern and a block of 4 steps (16 columns)
+    for t, w in ((4095, 512), (3000, 77)):
+        q = synth.device_normal((B, Hq, D), 2750 + t, torch.bfloat16, DEV)
+        out = st.attend_window(q, st.new_out(), t, w)
+        assert_close(out, oracle.attend(np64(q), K64, V64, t, w, 1.0 / np.sqrt(D)), dtype, f"head_dim 64 window t={t}")
+    qb = synth.device_normal((B, 4, Hq, D), 2790, torch.bfloat16, DEV)
+    ob = st.attend_block(qb, torch.empty_like(qb), 4092, 4)
+    for c in range(4):
+        ref = oracle.attend(np64(qb[:, c]), K64, V64, 4092 + c, 0, 1.0 / np.sqrt(D))
+        assert_close(ob[:, c], ref, dtype, f"head_dim 64 block step {c}")
+
+
 def test_llama_shape_window_bf16_full_size():
     B, Hq, Hkv, D, Z, T_len, w = 16, 24, 8, 128, 256, 16384, 512
     dtype = T.TEMPO_BF16
