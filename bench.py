@@ -863,6 +863,8 @@ def main() -> int:
             "algorithmic_bytes_per_launch": step_bytes,
             "stream_read_same_bytes": {"us": us(stream_s), "gbs": round(step_bytes / stream_s / 1e9, 1),
                                        "note": "two plain read launches (K pool, V pool) of one layer"},
+            "kernel_over_stream_read": round(stream_s / kernel_s, 4),
+            "step_over_stream_read": round(stream_s / sec_per_step, 4),
         },
     }
 
