@@ -111,6 +111,15 @@ def test_random_configuration(case):
         st.step_causal(q_last, k_last, v_last, o2, t_max, lps if c["ragged"] else None)
     assert torch.equal(o1.view(torch.uint8), o2.view(torch.uint8)), what + " [fused step differs from append + attend]"
 
+    # 2b. per-sequence steps, bf16, a group the single-step kernel serves: the same step with its
+    #     launch driven by a work list gives the same bits
+    if c["ragged"] and dtype == T.TEMPO_BF16 and G <= 16:
+        worklist = st.build_worklist(t_max, lps, window)
+        o4 = st.step_ragged(q_last, k_last, v_last, st.new_out(), t_max, lps, worklist, window)
+        assert torch.equal(o4.view(torch.uint8), o1.view(torch.uint8)), what + " [work list differs from the dense grid]"
+        o5 = st.step_ragged(q_last, None, None, st.new_out(), t_max, lps, worklist, window)
+        assert torch.equal(o5.view(torch.uint8), o1.view(torch.uint8)), what + " [work list, attention only]"
+
     # 3. uniform steps only: the same block through the prompt entry point into a second store
     if not c["ragged"] and not ring_blocks:
         st2 = BlockStore(B, Hq, Hkv, D, Z, steps - 1, dtype, num_blocks=st.num_blocks, block_table=st.block_table.cpu(),
