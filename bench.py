@@ -10,7 +10,8 @@ the split combine.  (The same step through the separate entry points
 tempo_kv_append + tempo_attn_decode_causal is timed too and reported as
 "separate_calls".)  Successive steps rotate over several layers' pools (a decode
 step of a real model visits every layer's keys/values once), so the key/value
-bytes of a step are not left in the last-level cache by the previous one.
+bytes of a step are not left in the last-level cache by the previous one (4 to 8
+pools of 256 MiB: no more than the warm-up steps, so that warm-up visits each once).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W]
 
@@ -80,12 +81,14 @@ def gpu_timed(torch, fn, n, warm, chunk=None):
             k += 1
     torch.cuda.synchronize()
     wall = (time.perf_counter() - t0) / n
-    per_call = sorted(events[j].elapsed_time(events[j + 1]) * 1e-3 / (bounds[j + 1] - bounds[j])
-                      for j in range(len(bounds) - 1))
+    in_order = [events[j].elapsed_time(events[j + 1]) * 1e-3 / (bounds[j + 1] - bounds[j])
+                for j in range(len(bounds) - 1)]
+    per_call = sorted(in_order)
     mean = events[0].elapsed_time(events[-1]) * 1e-3 / n
     return {"median": per_call[len(per_call) // 2] if len(per_call) % 2 else
             0.5 * (per_call[len(per_call) // 2 - 1] + per_call[len(per_call) // 2]),
-            "min": per_call[0], "mean": mean, "wall": wall, "chunk": chunk, "chunks": len(per_call)}
+            "min": per_call[0], "mean": mean, "wall": wall, "chunk": chunk, "chunks": len(per_call),
+            "first_chunks": in_order[:8]}
 
 
 def graph_timed(torch, fn, group, replays, warm=3):
@@ -663,7 +666,8 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
-    ap.add_argument("--layers", type=int, default=8, help="pools rotated over (cache defeat)")
+    ap.add_argument("--layers", type=int, default=8,
+                    help="most pools rotated over (cache defeat); the run uses max(4, min(this, warmup))")
     ap.add_argument("--no-extras", action="store_true", help="skip the per-t curve, whole-run and other-workload legs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--counters", action="store_true",
@@ -727,7 +731,10 @@ def main() -> int:
         return 0
 
     B, Hq, Hkv, D, Z, t = 16, 24, 8, 128, 256, 4095
-    R = args.layers
+    # Pools rotated over: at least 4 (4 x 256 MiB of keys/values, four times the last-level cache), at most
+    # --layers, and no more than the warm-up steps, so that the W warm-up steps visit every pool once (a pool's
+    # first step after set-up pays for cold address translation: 48-50 us instead of 46-47).
+    R = max(4, min(args.layers, args.warmup))
     T_len = t + 1
     scale = 1.0 / math.sqrt(D)
     kv_bytes_per_token = 2 * Hkv * D * 2                      # K and V, bf16
@@ -842,7 +849,8 @@ def main() -> int:
                    "ms_per_step_median": round(head["median"] * 1e3, 5),
                    "ms_per_step_min": round(head["min"] * 1e3, 5),
                    "ms_per_step_mean_gpu": round(head["mean"] * 1e3, 5),
-                   "ms_per_step_mean_host_wall": round(head["wall"] * 1e3, 5)},
+                   "ms_per_step_mean_host_wall": round(head["wall"] * 1e3, 5),
+                   "ms_per_step_first_chunks_in_order": [round(x * 1e3, 5) for x in head["first_chunks"]]},
         "separate_calls": {"ms_per_step": round(sep * 1e3, 5), "kv_gbs": round(step_bytes / sep / 1e9, 1),
                            "launches": "tempo_kv_append + tempo_attn_decode_causal"},
         "steps_per_s": round(1.0 / sec_per_step, 1),
