@@ -514,7 +514,7 @@ def plan_sweep(torch, T, BlockStore, synth, dev):
             sts.append(st)
         q = synth.device_normal((batch, Hq, D), 61, torch.bfloat16, dev)
         o = sts[0].new_out()
-        for t in (255, 1023, 2047, 4095, 8191):
+        for t in (255, 1023, 1535, 2047, 2500, 3500, 4095, 5000, 8191):
             lib = T.tempo_attn_plan(sts[0].kv, batch, Hq, t, 0)
             rows = {}
             for k in range(7, 14):                                        # 128 .. 8192 keys per split

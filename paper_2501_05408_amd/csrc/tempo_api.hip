@@ -128,14 +128,17 @@ constexpr int kMaxSplits = 1024;
 //     this access pattern (about 6.9 TB/s over all units), but never faster than
 //     about 40 GB/s, so fewer than ~170 busy units cannot use the whole bandwidth.
 //   - A launch pays about 2 us once before its first key arrives (dispatch, kernel
-//     arguments, block table, first loads), about 0.3 us per round (merge, partial
-//     write), and about 3 us for the combine launch if there is more than one split.
+//     arguments, block table, first loads), about 1 us per round (a workgroup's own
+//     argument -> table -> data chain and its merge and partial write, as far as the other
+//     workgroups resident on the unit do not hide them; fitted on steps that are not powers
+//     of two, where short splits looked better than they are), and about 3 us for the
+//     combine launch if there is more than one split.
 // Short splits balance better; long splits mean fewer rounds, fewer partials and,
 // at one split, no combine at all.  Take the LONGEST split length whose estimate is
 // within 3% of the best one.
 constexpr double kSustainedBytesPerNs = 6900.0;  // whole part, GB/s
 constexpr double kUnitBytesPerNs = 40.0;         // one compute unit, GB/s
-constexpr double kLaunchNs = 2000.0, kRoundNs = 300.0, kCombineNs = 3000.0;
+constexpr double kLaunchNs = 2000.0, kRoundNs = 1000.0, kCombineNs = 3000.0;
 
 double plan_cost_ns(int64_t pairs, int64_t splits, int64_t keys_per_split, int bytes_per_key) {
   const int64_t workgroups = pairs * splits;
