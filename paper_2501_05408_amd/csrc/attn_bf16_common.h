@@ -158,14 +158,36 @@ __device__ inline void value_masks(int grp, int v_lo, int v_hi, int lane, uint32
   }
 }
 
+// Maximum over the four lanes {l, l^16, l^32, l^48} that hold one column's logits,
+// left in all four.  Two lane-swap instructions of gfx950 instead of two trips
+// through the LDS permute unit: v_permlane16_swap exchanges the odd 16-lane rows of
+// its first operand with the even rows of its second, v_permlane32_swap the upper
+// half of the first with the lower half of the second; with both operands holding
+// the same values, the maximum of the two results is the exchange-and-reduce step.
+__device__ inline float column_max(float v) {
+  float a = v, b = v;
+  asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 0\n\tv_max_f32 %0, %0, %1" : "+v"(a), "+v"(b));
+  float c = a, d = a;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 0\n\tv_max_f32 %0, %0, %1" : "+v"(c), "+v"(d));
+  return c;
+}
+
+// The same exchange with a sum: the total over the four lanes that hold one column's partial sums.
+__device__ inline float column_sum(float v) {
+  float a = v, b = v;
+  asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 0\n\tv_add_f32 %0, %0, %1" : "+v"(a), "+v"(b));
+  float c = a, d = a;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 0\n\tv_add_f32 %0, %0, %1" : "+v"(c), "+v"(d));
+  return c;
+}
+
 // Online-softmax update of (m, l), rescale of acc, and the bf16 weights of this group.
 template <int D>
 __device__ inline bf16x8 softmax_update(const float* x, int lane, WaveState<D>& st) {
   constexpr int DT = D / 16;
   const int c = lane >> 4;
   float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-  mx = fmaxf(mx, __shfl_xor(mx, 16));
-  mx = fmaxf(mx, __shfl_xor(mx, 32));
+  mx = column_max(mx);  // lane swaps, not two trips through the LDS permute unit
   const float m_new = fmaxf(st.m, mx);
   // A column may have seen no key yet (block of queries: a group beyond an early
   // query's step): keep -inf as its max but exponentiate against 0, never -inf - -inf.

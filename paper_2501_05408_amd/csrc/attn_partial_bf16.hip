@@ -332,8 +332,7 @@ __global__ __launch_bounds__(512) void attn_partial_bf16(AttnParams p) {
   }
 
   // Wave result -> LDS.  Columns live in lane&15 for (m, l) and in (4c + r) for acc.
-  float l_tot = st.l + __shfl_xor(st.l, 16);
-  l_tot += __shfl_xor(l_tot, 32);
+  const float l_tot = column_sum(st.l);
   float* sm_m = smem;                       // [nwaves][16]
   float* sm_l = smem + nwaves * 16;         // [nwaves][16]
   float* sm_acc = smem + nwaves * 32;       // [nwaves][ncols][D]

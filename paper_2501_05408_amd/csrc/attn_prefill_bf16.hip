@@ -37,20 +37,6 @@ namespace {
 typedef __attribute__((address_space(3))) void* lds_ptr;
 typedef const __attribute__((address_space(1))) void* global_ptr;
 
-// Maximum over the four lanes {l, l^16, l^32, l^48} that hold one column's logits,
-// left in all four.  Two lane-swap instructions of gfx950 instead of two trips
-// through the LDS permute unit: v_permlane16_swap exchanges the odd 16-lane rows of
-// its first operand with the even rows of its second, v_permlane32_swap the upper
-// half of the first with the lower half of the second; with both operands holding
-// the same values, the maximum of the two results is the exchange-and-reduce step.
-__device__ inline float column_max(float v) {
-  float a = v, b = v;
-  asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 0\n\tv_max_f32 %0, %0, %1" : "+v"(a), "+v"(b));
-  float c = a, d = a;
-  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 0\n\tv_max_f32 %0, %0, %1" : "+v"(c), "+v"(d));
-  return c;
-}
-
 __device__ inline float max3(float a, float b, float c) {
   float r;
   asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
