@@ -202,8 +202,9 @@ __device__ inline bf16x8 softmax_update(const float* x, int lane, WaveState<D>& 
     psum += (float)pb;  // the sum uses the rounded weights, so out stays a convex combination
   }
   st.l = st.l * alpha + psum;
+  const bool rescale = alpha != 1.0f && st.m != -INFINITY;  // a column that had seen no key holds zeros: nothing to scale
   st.m = m_new;
-  if (__any(alpha != 1.0f)) {
+  if (__any(rescale)) {
     float a[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) a[r] = __shfl(alpha, 4 * c + r);
