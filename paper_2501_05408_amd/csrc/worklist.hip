@@ -76,10 +76,10 @@ __global__ __launch_bounds__(kThreads) void worklist_build(const int32_t* __rest
   for (int b = tid; b < batch; b += kThreads) {
     int n, c;
     seq_items(t_per_seq, b, t_max, window, tps_log2, num_splits, n, c);
-    for (int s = 0; s + 1 < n; ++s) list[at[0]++] = b | (s << 16);
+    for (int s = 0; s + 1 < n; ++s) list[at[0]++] = (int32_t)((uint32_t)b | ((uint32_t)s << 16));
 #pragma unroll
     for (int k = 0; k < kClasses; ++k) {
-      if (k == c) list[at[1 + k]++] = b | ((n - 1) << 16);
+      if (k == c) list[at[1 + k]++] = (int32_t)((uint32_t)b | ((uint32_t)(n - 1) << 16));
     }
   }
 }
