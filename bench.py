@@ -186,13 +186,20 @@ def launch_bound_legs(torch, T, BlockStore, synth, dev, kv_bytes_per_token):
         16 * 512 * kv_bytes_per_token, T.tempo_attn_plan(sts[0].kv, 16, Hq, 8191, 512))
     del sts
     torch.cuda.empty_cache()
-    sts = layers(16, 2 ** 30, ring=4)
+    # the window store: every sequence of every layer owns a ring of 4 blocks, drawn at random from ONE pool
+    # that holds exactly those rings (8 layers x 16 sequences x 4 blocks), as an allocator would hand them out
+    ring_perm = synth.permutation(31, 1, R * 16 * 4)
+    ring_k = torch.empty((R * 16 * 4, Hkv, Z * D), dtype=torch.bfloat16, device=dev).normal_()
+    ring_v = torch.empty((R * 16 * 4, Hkv, Z * D), dtype=torch.bfloat16, device=dev).normal_()
+    sts = [BlockStore(16, Hq, Hkv, D, Z, 2 ** 30, T.TEMPO_BF16, device=dev, ring_blocks=4, num_blocks=R * 16 * 4,
+                      block_table=torch.from_numpy(ring_perm[l * 64:(l + 1) * 64].reshape(16, 4).copy()),
+                      pools=(ring_k, ring_v)) for l in range(R)]
     leg("window512_ring4_b16_t1000000", lambda i: sts[i % R].step_window(q16, k16, v16, o, 1000000, 512),
         16 * 512 * kv_bytes_per_token, T.tempo_attn_plan(sts[0].kv, 16, Hq, 1000000, 512))
-    out["window512_ring4_b16_t1000000"]["pool_mib_per_layer"] = round(2 * sts[0].k_pool.numel() * 2 / 2 ** 20, 1)
+    out["window512_ring4_b16_t1000000"]["pool_mib_per_layer"] = round(2 * ring_k.numel() * 2 / R / 2 ** 20, 1)
     out["window512_ring4_b16_t1000000"]["linear_store_would_need_mib"] = round(
         16 * (1000000 // Z + 1) * Hkv * Z * D * 2 * 2 / 2 ** 20, 1)
-    del sts
+    del sts, ring_k, ring_v
     torch.cuda.empty_cache()
     sts = layers(1, 65535)
     q1, k1, v1 = q16[:1].contiguous(), k16[:1].contiguous(), v16[:1].contiguous()
