@@ -792,3 +792,40 @@ def test_step_replayed_from_a_hip_graph():
     ref = oracle.attend(q[0].astype(np.float64), K.astype(np.float64), V.astype(np.float64), t, 0,
                         1.0 / np.sqrt(D))
     assert_close(eager, ref, dtype, "graph test eager")
+
+
+def test_ragged_step_with_work_list_replayed_from_a_hip_graph():
+    # The list is built once (outside the graph); the captured ragged step is replayed with new queries
+    # and new key/value rows and must give the eager bits every time.
+    B, Hq, Hkv, D, Z, T_len = 6, 12, 4, 128, 64, 900
+    dtype = T.TEMPO_BF16
+    q, K, V = host_inputs(15, B, T_len, Hq, Hkv, D, dtype)
+    lengths = np.array([900, 1, 333, 640, 65, 512], dtype=np.int32)
+    st = BlockStore(B, Hq, Hkv, D, Z, T_len - 1, dtype, fill="nan")
+    qd, Kd, Vd = dev(q, dtype), dev(K, dtype), dev(V, dtype)
+    len_d = torch.from_numpy(lengths).to(DEV)
+    st.prefill(Kd, Vd, T_len - 2, lengths=torch.clamp(len_d - 1, min=1))
+    tps = (len_d - 1).to(torch.int32)
+    ar = torch.arange(B, device=DEV)
+    k_t, v_t = Kd[ar, tps.long()].contiguous(), Vd[ar, tps.long()].contiguous()
+    worklist = st.build_worklist(T_len - 1, tps)
+    q_buf, out = qd[0].clone(), st.new_out()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        st.step_ragged(q_buf, k_t, v_t, out, T_len - 1, tps, worklist)     # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        st.step_ragged(q_buf, k_t, v_t, out, T_len - 1, tps, worklist)
+    for rep in range(4):
+        out.zero_()
+        q_buf.copy_(qd[rep])
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        want = st.step_causal(qd[rep], k_t, v_t, st.new_out(), T_len - 1, t_per_seq=tps)
+        assert torch.equal(out, want)
+    ref = oracle.attend(q[3].astype(np.float64), K.astype(np.float64), V.astype(np.float64), lengths - 1, 0,
+                        1.0 / np.sqrt(D))
+    assert_close(out, ref, dtype, "ragged step with a work list, replayed from a graph")
